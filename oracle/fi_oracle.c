@@ -1,0 +1,578 @@
+/*
+ * CPU oracle for fault-injected mixed-precision GEMM campaigns.
+ * TEST INFRASTRUCTURE: see fi_oracle.h.  Build with
+ *   gcc -O2 -std=c99 -ffp-contract=off -fno-fast-math [-fopenmp] -shared -fPIC
+ * No intrinsics, no blocking beyond the k-blocks the method itself defines, no
+ * reordering: every loop is the definition written out.
+ */
+#include "fi_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ words */
+
+static uint32_t word_of(float x) { uint32_t w; memcpy(&w, &x, 4); return w; }
+static float float_of(uint32_t w) { float x; memcpy(&x, &w, 4); return x; }
+
+/* ------------------------------------------------- O1: operand decoding
+ * Sec. II-A / Fig. 1: FP16 = 1 sign, 5 exponent (bias 15), 10 mantissa bits;
+ * BF16 = 1 sign, 8 exponent (bias 127), 7 mantissa bits.  Value of a normal
+ * number: (-1)^s * 2^(E-bias) * (1 + m/2^p); of a subnormal (E = 0):
+ * (-1)^s * 2^(1-bias) * (m/2^p).  Both formats embed exactly in binary32, so
+ * ldexpf of a small integer is exact, subnormal binary32 results included. */
+float orc_decode16(uint16_t w, int fmt) {
+  int ebits = (fmt == ORC_FP16) ? 5 : 8;
+  int mbits = (fmt == ORC_FP16) ? 10 : 7;
+  int bias = (1 << (ebits - 1)) - 1;
+  int sign = (w >> 15) & 1;
+  int E = (w >> mbits) & ((1 << ebits) - 1);
+  int m = w & ((1 << mbits) - 1);
+  float v;
+  if (E == (1 << ebits) - 1) {
+    v = (m == 0) ? INFINITY : NAN;
+  } else if (E == 0) {
+    v = ldexpf((float)m, 1 - bias - mbits);
+  } else {
+    v = ldexpf((float)((1 << mbits) + m), E - bias - mbits);
+  }
+  return sign ? -v : v;
+}
+
+/* Memo of the pure function above over all 65536 patterns per format. */
+static float g_tab[2][65536];
+__attribute__((constructor)) static void fill_tables(void) {
+  for (int fmt = 0; fmt < 2; ++fmt)
+    for (uint32_t w = 0; w < 65536; ++w) g_tab[fmt][w] = orc_decode16((uint16_t)w, fmt);
+}
+static float dec(uint16_t w, int fmt) { return g_tab[fmt][w]; }
+
+void orc_decode_array(const uint16_t* in, size_t n, int fmt, float* out) {
+  for (size_t t = 0; t < n; ++t) out[t] = orc_decode16(in[t], fmt);
+}
+
+/* ------------------------------------------------------------ accessors */
+
+static uint16_t a_word(const orc_problem* p, const uint16_t* A, int i, int k) {
+  return A[(size_t)i * (size_t)p->lda + (size_t)k];
+}
+static uint16_t b_word(const orc_problem* p, const uint16_t* B, int k, int j) {
+  return p->b_layout == 0 ? B[(size_t)j * (size_t)p->ldb + (size_t)k]
+                          : B[(size_t)k * (size_t)p->ldb + (size_t)j];
+}
+
+static int check_problem(const orc_problem* p) {
+  if (!p) return 1;
+  if (p->M <= 0 || p->N <= 0 || p->K <= 0 || p->kb <= 0) return 1;
+  if (p->K % p->kb != 0) return 1;
+  if (p->fmt != ORC_FP16 && p->fmt != ORC_BF16) return 1;
+  if (p->b_layout != 0 && p->b_layout != 1) return 1;
+  if (!(p->gamma >= 1.0f)) return 1;
+  return 0;
+}
+
+/* Row i of A and column j of B as contiguous float vectors of length K. */
+static void load_a_row(const orc_problem* p, const uint16_t* A, int i, float* out) {
+  for (int k = 0; k < p->K; ++k) out[k] = dec(a_word(p, A, i, k), p->fmt);
+}
+static void load_b_col(const orc_problem* p, const uint16_t* B, int j, float* out) {
+  for (int k = 0; k < p->K; ++k) out[k] = dec(b_word(p, B, k, j), p->fmt);
+}
+
+/* --------------------------------- O2 / O3: blocked FP32 dot product
+ * Sec. IV-C: low-precision products accumulated into one FP32 number.
+ * acc starts at +0; k ascends; each product is rounded once to binary32
+ * (exact for FP16 and, inside the binary32 range, for BF16), each addition is
+ * rounded once, no fused multiply-add.  If fault_s >= 0 the accumulator word
+ * is XORed with mask immediately after the last addition of k-block fault_s
+ * (Sec. III-E: the corrupted value lands in the MMA destination register and
+ * the following MMAs accumulate onto it). */
+static float dot_blocked(const float* a, const float* b, int K, int kb,
+                         int fault_s, uint32_t mask,
+                         uint32_t* word_before, uint32_t* word_after) {
+  float acc = 0.0f;
+  int S = K / kb;
+  for (int s = 0; s < S; ++s) {
+    for (int k = s * kb; k < (s + 1) * kb; ++k) {
+      float prod = a[k] * b[k];
+      acc = acc + prod;
+    }
+    if (s == fault_s) {
+      uint32_t w = word_of(acc);
+      if (word_before) *word_before = w;
+      w ^= mask;
+      if (word_after) *word_after = w;
+      acc = float_of(w);
+    }
+  }
+  return acc;
+}
+
+/* Double-precision sum R and sum of magnitudes Sabs of the same products. */
+static void dot_double(const float* a, const float* b, int K, double* R, double* Sabs) {
+  double r = 0.0, s = 0.0;
+  for (int k = 0; k < K; ++k) {
+    double prod = (double)a[k] * (double)b[k];
+    r += prod;
+    s += fabs(prod);
+  }
+  *R = r;
+  *Sabs = s;
+}
+
+float orc_dot(const orc_problem* p, const uint16_t* A, const uint16_t* B, int i, int j) {
+  float* a = (float*)malloc(sizeof(float) * (size_t)p->K);
+  float* b = (float*)malloc(sizeof(float) * (size_t)p->K);
+  load_a_row(p, A, i, a);
+  load_b_col(p, B, j, b);
+  float c = dot_blocked(a, b, p->K, p->kb, -1, 0, NULL, NULL);
+  free(a);
+  free(b);
+  return c;
+}
+
+int orc_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* Whole-matrix O2 with an optional accumulator fault at (fi, fj, fs).
+ * Af is M x K, Bt is N x K (column j of B stored as row j), both decoded. */
+static void gemm_decoded(int M, int N, int K, int kb, const float* Af, const float* Bt,
+                         int fi, int fj, int fs, uint32_t mask,
+                         float* C, double* R, double* S,
+                         uint32_t* word_before, uint32_t* word_after) {
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+  for (int i = 0; i < M; ++i) {
+    for (int j = 0; j < N; ++j) {
+      const float* a = Af + (size_t)i * K;
+      const float* b = Bt + (size_t)j * K;
+      int here = (i == fi && j == fj);
+      C[(size_t)i * N + j] = dot_blocked(a, b, K, kb, here ? fs : -1, mask,
+                                         here ? word_before : NULL, here ? word_after : NULL);
+      if (R || S) {
+        double r, s;
+        dot_double(a, b, K, &r, &s);
+        if (R) R[(size_t)i * N + j] = r;
+        if (S) S[(size_t)i * N + j] = s;
+      }
+    }
+  }
+}
+
+static int decode_operands(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                           float** Af, float** Bt) {
+  *Af = (float*)malloc(sizeof(float) * (size_t)p->M * p->K);
+  *Bt = (float*)malloc(sizeof(float) * (size_t)p->N * p->K);
+  if (!*Af || !*Bt) { free(*Af); free(*Bt); return 3; }
+  for (int i = 0; i < p->M; ++i) load_a_row(p, A, i, *Af + (size_t)i * p->K);
+  for (int j = 0; j < p->N; ++j) load_b_col(p, B, j, *Bt + (size_t)j * p->K);
+  return 0;
+}
+
+int orc_gemm(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+             float* C, double* R, double* S) {
+  if (check_problem(p) || !A || !B || !C) return 1;
+  float *Af, *Bt;
+  int rc = decode_operands(p, A, B, &Af, &Bt);
+  if (rc) return rc;
+  gemm_decoded(p->M, p->N, p->K, p->kb, Af, Bt, -1, -1, -1, 0, C, R, S, NULL, NULL);
+  free(Af);
+  free(Bt);
+  return 0;
+}
+
+/* ---------------------------------------------------- O4: the detector
+ * Sec. VI-A bounds the exponent of ONE product by the operands' exponents
+ * (m1*m2 < 4  =>  e_m <= e1+e2+1).  Summed over the K products of an output
+ * element the same argument gives |c_ij| <= K * max_k|a_ik| * max_k|b_kj|;
+ * anything above that (times a rounding slack gamma) cannot be a fault-free
+ * result.  Magnitudes are compared on the 15 value bits, which orders finite
+ * FP16/BF16 numbers exactly. */
+int orc_rowcol_absmax(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                      float* ra, float* cb) {
+  if (check_problem(p) || !A || !B || !ra || !cb) return 1;
+  int bad = 0;
+  for (int i = 0; i < p->M; ++i) {
+    float m = 0.0f;
+    for (int k = 0; k < p->K; ++k) {
+      float v = fabsf(dec(a_word(p, A, i, k), p->fmt));
+      if (!(v <= 3.0e38f)) bad = 1;   /* Inf or NaN */
+      if (v > m) m = v;
+    }
+    ra[i] = m;
+  }
+  for (int j = 0; j < p->N; ++j) {
+    float m = 0.0f;
+    for (int k = 0; k < p->K; ++k) {
+      float v = fabsf(dec(b_word(p, B, k, j), p->fmt));
+      if (!(v <= 3.0e38f)) bad = 1;
+      if (v > m) m = v;
+    }
+    cb[j] = m;
+  }
+  return bad ? 2 : 0;
+}
+
+float orc_threshold(int K, float ra, float cb, float gamma) {
+  float t = (float)K * ra;   /* one rounding each */
+  t = t * cb;
+  t = t * gamma;
+  return t;
+}
+
+static float vec_max(const float* v, int n) {
+  float m = 0.0f;
+  for (int t = 0; t < n; ++t) if (v[t] > m) m = v[t];
+  return m;
+}
+
+static float threshold_at(const orc_problem* p, const float* ra, const float* cb,
+                          float ra_max, float cb_max, int i, int j) {
+  if (p->bound_mode == ORC_BOUND_GLOBAL) return orc_threshold(p->K, ra_max, cb_max, p->gamma);
+  return orc_threshold(p->K, ra[i], cb[j], p->gamma);
+}
+
+/* flag <=> NOT (|c| <= T): true for NaN and +-Inf as well. */
+static int flagged(float c, float T) { return !(fabsf(c) <= T); }
+
+/* O5: correction only where detection fired (Sec. VI-B). */
+static float corrected(float c, int flag, int policy, float c_star) {
+  if (!flag) return c;
+  if (policy == ORC_CORRECT_ZERO) return 0.0f;
+  if (policy == ORC_CORRECT_RECOMPUTE) return c_star;
+  return c;
+}
+
+int orc_detect_correct(const orc_problem* p, const float* ra, const float* cb,
+                       float* C, int batch, int policy, const float* c_star,
+                       uint8_t* flags, uint32_t* n_flagged) {
+  if (check_problem(p) || !ra || !cb || !C || batch < 0) return 1;
+  if (policy == ORC_CORRECT_RECOMPUTE && !c_star) return 1;
+  float ra_max = vec_max(ra, p->M), cb_max = vec_max(cb, p->N);
+  for (int t = 0; t < batch; ++t) {
+    uint32_t n = 0;
+    for (int i = 0; i < p->M; ++i) {
+      for (int j = 0; j < p->N; ++j) {
+        size_t e = ((size_t)t * p->M + i) * p->N + j;
+        float T = threshold_at(p, ra, cb, ra_max, cb_max, i, j);
+        int fl = flagged(C[e], T);
+        if (flags) flags[e] = (uint8_t)fl;
+        n += (uint32_t)fl;
+        C[e] = corrected(C[e], fl, policy, c_star ? c_star[(size_t)i * p->N + j] : 0.0f);
+      }
+    }
+    if (n_flagged) n_flagged[t] = n;
+  }
+  return 0;
+}
+
+/* ------------------------------------------- O6: per-element accounting */
+
+static double deviation(float x, float ref) {
+  double d = fabs((double)x - (double)ref);
+  if (!(d <= 1.79e308)) return INFINITY;   /* NaN or Inf */
+  return d;
+}
+
+static void account(orc_record* r, float c_f, float c_star, double Sabs, float T, int policy) {
+  double tau = ldexp(Sabs, -12);
+  int fl = flagged(c_f, T);
+  float c_c = corrected(c_f, fl, policy, c_star);
+  double dpre = deviation(c_f, c_star);
+  double dpost = deviation(c_c, c_star);
+  r->n_flagged += (uint32_t)fl;
+  r->n_bitdiff += (uint32_t)(word_of(c_f) != word_of(c_star));
+  r->n_dev_pre += (uint32_t)!(dpre <= tau);
+  r->n_dev_post += (uint32_t)!(dpost <= tau);
+  if (dpre > r->max_dev_pre) r->max_dev_pre = dpre;
+  if (dpost > r->max_dev_post) r->max_dev_post = dpost;
+  /* Guard bands: decisions that a different (but admissible) FP32 summation
+   * order could take the other way.  Only elements the fault changed can be
+   * borderline: an unchanged element is C*, which never exceeds T. */
+  if (word_of(c_f) == word_of(c_star)) return;
+  double band = 2.0 * tau;
+  if (ldexp((double)T, -6) > band) band = ldexp((double)T, -6);
+  double mag = fabs((double)c_f);
+  if (mag <= 1.79e308 && fabs(mag - (double)T) <= band) r->n_border_T += 1;
+  if (tau > 0.0 && dpre >= 0.5 * tau && dpre <= 2.0 * tau) r->n_border_tau += 1;
+}
+
+static void finish(orc_record* r) {
+  if (r->n_flagged > 0) r->cls = ORC_DETECTED;
+  else if (r->n_dev_pre > 0) r->cls = ORC_SDC;
+  else r->cls = ORC_MASKED;
+}
+
+static int site_valid(const orc_problem* p, const orc_fault* f) {
+  switch (f->kind) {
+    case ORC_SITE_NONE: return 1;
+    case ORC_SITE_ACC:
+      return f->row < (uint32_t)p->M && f->col < (uint32_t)p->N &&
+             f->kblock < (uint32_t)(p->K / p->kb);
+    case ORC_SITE_A: return f->row < (uint32_t)p->M && f->col < (uint32_t)p->K;
+    case ORC_SITE_B: return f->row < (uint32_t)p->K && f->col < (uint32_t)p->N;
+    default: return 0;
+  }
+}
+
+/* ----------------------------------------------------- O3-O6: one trial */
+
+static int trial_full(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                      const orc_fault* f, int policy, float* cf_out, float* cc_out,
+                      orc_record* rec) {
+  int M = p->M, N = p->N, K = p->K;
+  size_t mn = (size_t)M * N;
+  float *Af = NULL, *Bt = NULL;
+  int rc = decode_operands(p, A, B, &Af, &Bt);
+  if (rc) return rc;
+  float* Cstar = (float*)malloc(sizeof(float) * mn);
+  float* Cf = (float*)malloc(sizeof(float) * mn);
+  double* S = (double*)malloc(sizeof(double) * mn);
+  float* ra = (float*)malloc(sizeof(float) * (size_t)M);
+  float* cb = (float*)malloc(sizeof(float) * (size_t)N);
+  orc_rowcol_absmax(p, A, B, ra, cb);     /* statistics of the GOLDEN operands */
+  float ra_max = vec_max(ra, M), cb_max = vec_max(cb, N);
+
+  gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, -1, 0, Cstar, NULL, S, NULL, NULL);
+
+  /* The faulty execution: every element is recomputed with the fault in place. */
+  if (f->kind == ORC_SITE_ACC) {
+    gemm_decoded(M, N, K, p->kb, Af, Bt, (int)f->row, (int)f->col, (int)f->kblock,
+                 f->xor_mask, Cf, NULL, NULL, &rec->site_word_before, &rec->site_word_after);
+  } else if (f->kind == ORC_SITE_A) {
+    uint16_t w = a_word(p, A, (int)f->row, (int)f->col);
+    uint16_t wf = (uint16_t)(w ^ (f->xor_mask & 0xFFFFu));
+    rec->site_word_before = w;
+    rec->site_word_after = wf;
+    Af[(size_t)f->row * K + f->col] = dec(wf, p->fmt);
+    gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, -1, 0, Cf, NULL, NULL, NULL, NULL);
+  } else if (f->kind == ORC_SITE_B) {
+    uint16_t w = b_word(p, B, (int)f->row, (int)f->col);
+    uint16_t wf = (uint16_t)(w ^ (f->xor_mask & 0xFFFFu));
+    rec->site_word_before = w;
+    rec->site_word_after = wf;
+    Bt[(size_t)f->col * K + f->row] = dec(wf, p->fmt);
+    gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, -1, 0, Cf, NULL, NULL, NULL, NULL);
+  } else {
+    memcpy(Cf, Cstar, sizeof(float) * mn);
+  }
+
+  for (int i = 0; i < M; ++i) {
+    for (int j = 0; j < N; ++j) {
+      size_t e = (size_t)i * N + j;
+      float T = threshold_at(p, ra, cb, ra_max, cb_max, i, j);
+      account(rec, Cf[e], Cstar[e], S[e], T, policy);
+      if (cf_out) cf_out[e] = Cf[e];
+      if (cc_out) cc_out[e] = corrected(Cf[e], flagged(Cf[e], T), policy, Cstar[e]);
+    }
+  }
+  free(Af); free(Bt); free(Cstar); free(Cf); free(S); free(ra); free(cb);
+  return 0;
+}
+
+/* Only the elements the fault can reach are recomputed; every other element
+ * equals C* bit for bit by construction and a clean element is never flagged
+ * (|C*_ij| <= T_ij), so it contributes nothing to any counter. */
+static int trial_affected(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                          const float* ra, const float* cb, float ra_max, float cb_max,
+                          const orc_fault* f, int policy, orc_record* rec) {
+  int K = p->K;
+  float* a = (float*)malloc(sizeof(float) * (size_t)K);
+  float* b = (float*)malloc(sizeof(float) * (size_t)K);
+  float* g = (float*)malloc(sizeof(float) * (size_t)K);   /* golden copy of the faulted vector */
+  if (f->kind == ORC_SITE_ACC) {
+    int i = (int)f->row, j = (int)f->col;
+    load_a_row(p, A, i, a);
+    load_b_col(p, B, j, b);
+    float c_star = dot_blocked(a, b, K, p->kb, -1, 0, NULL, NULL);
+    float c_f = dot_blocked(a, b, K, p->kb, (int)f->kblock, f->xor_mask,
+                            &rec->site_word_before, &rec->site_word_after);
+    double R, S;
+    dot_double(a, b, K, &R, &S);
+    account(rec, c_f, c_star, S, threshold_at(p, ra, cb, ra_max, cb_max, i, j), policy);
+  } else if (f->kind == ORC_SITE_A) {
+    int i = (int)f->row, kf = (int)f->col;
+    uint16_t w = a_word(p, A, i, kf);
+    uint16_t wf = (uint16_t)(w ^ (f->xor_mask & 0xFFFFu));
+    rec->site_word_before = w;
+    rec->site_word_after = wf;
+    load_a_row(p, A, i, g);
+    memcpy(a, g, sizeof(float) * (size_t)K);
+    a[kf] = dec(wf, p->fmt);
+    for (int j = 0; j < p->N; ++j) {
+      load_b_col(p, B, j, b);
+      float c_star = dot_blocked(g, b, K, p->kb, -1, 0, NULL, NULL);
+      float c_f = dot_blocked(a, b, K, p->kb, -1, 0, NULL, NULL);
+      double R, S;
+      dot_double(g, b, K, &R, &S);
+      account(rec, c_f, c_star, S, threshold_at(p, ra, cb, ra_max, cb_max, i, j), policy);
+    }
+  } else if (f->kind == ORC_SITE_B) {
+    int kf = (int)f->row, j = (int)f->col;
+    uint16_t w = b_word(p, B, kf, j);
+    uint16_t wf = (uint16_t)(w ^ (f->xor_mask & 0xFFFFu));
+    rec->site_word_before = w;
+    rec->site_word_after = wf;
+    load_b_col(p, B, j, g);
+    memcpy(b, g, sizeof(float) * (size_t)K);
+    b[kf] = dec(wf, p->fmt);
+    for (int i = 0; i < p->M; ++i) {
+      load_a_row(p, A, i, a);
+      float c_star = dot_blocked(a, g, K, p->kb, -1, 0, NULL, NULL);
+      float c_f = dot_blocked(a, b, K, p->kb, -1, 0, NULL, NULL);
+      double R, S;
+      dot_double(a, g, K, &R, &S);
+      account(rec, c_f, c_star, S, threshold_at(p, ra, cb, ra_max, cb_max, i, j), policy);
+    }
+  }
+  free(a); free(b); free(g);
+  return 0;
+}
+
+static void clear_record(orc_record* rec) {
+  memset(rec, 0, sizeof(*rec));
+  rec->valid = 1;
+}
+
+int orc_trial(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+              const orc_fault* f, int policy, int mode,
+              float* cf_out, float* cc_out, orc_record* rec) {
+  if (check_problem(p) || !A || !B || !f || !rec) return 1;
+  if (policy < 0 || policy > 2) return 1;
+  clear_record(rec);
+  orc_fault nofault = {ORC_SITE_NONE, 0, 0, 0, 0};
+  if (!site_valid(p, f)) { rec->valid = 0; f = &nofault; }
+  int rc;
+  if (mode == ORC_MODE_FULL) {
+    rc = trial_full(p, A, B, f, policy, cf_out, cc_out, rec);
+  } else {
+    if (cf_out || cc_out) return 1;
+    float* ra = (float*)malloc(sizeof(float) * (size_t)p->M);
+    float* cb = (float*)malloc(sizeof(float) * (size_t)p->N);
+    orc_rowcol_absmax(p, A, B, ra, cb);
+    rc = trial_affected(p, A, B, ra, cb, vec_max(ra, p->M), vec_max(cb, p->N), f, policy, rec);
+    free(ra); free(cb);
+  }
+  if (rc == 0) finish(rec);
+  return rc;
+}
+
+int orc_campaign(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                 const orc_fault* faults, int n_trials, int policy, int mode,
+                 orc_record* recs) {
+  if (check_problem(p) || !A || !B || !faults || !recs || n_trials < 0) return 1;
+  if (policy < 0 || policy > 2) return 1;
+  if (mode == ORC_MODE_FULL) {
+    for (int t = 0; t < n_trials; ++t) {
+      int rc = orc_trial(p, A, B, &faults[t], policy, ORC_MODE_FULL, NULL, NULL, &recs[t]);
+      if (rc) return rc;
+    }
+    return 0;
+  }
+  float* ra = (float*)malloc(sizeof(float) * (size_t)p->M);
+  float* cb = (float*)malloc(sizeof(float) * (size_t)p->N);
+  orc_rowcol_absmax(p, A, B, ra, cb);
+  float ra_max = vec_max(ra, p->M), cb_max = vec_max(cb, p->N);
+  orc_fault nofault = {ORC_SITE_NONE, 0, 0, 0, 0};
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 4)
+#endif
+  for (int t = 0; t < n_trials; ++t) {
+    const orc_fault* f = &faults[t];
+    clear_record(&recs[t]);
+    if (!site_valid(p, f)) { recs[t].valid = 0; f = &nofault; }
+    trial_affected(p, A, B, ra, cb, ra_max, cb_max, f, policy, &recs[t]);
+    finish(&recs[t]);
+  }
+  free(ra); free(cb);
+  return 0;
+}
+
+void orc_classify(const orc_record* recs, int n, uint8_t* cls, uint64_t counts[3]) {
+  counts[0] = counts[1] = counts[2] = 0;
+  for (int t = 0; t < n; ++t) {
+    uint32_t c;
+    if (recs[t].n_flagged > 0) c = ORC_DETECTED;
+    else if (recs[t].n_dev_pre > 0) c = ORC_SDC;
+    else c = ORC_MASKED;
+    if (cls) cls[t] = (uint8_t)c;
+    counts[c] += 1;
+  }
+}
+
+/* --------------------------------------------------------- O7: sampler
+ * Sec. IV-A selects the injection target uniformly at random and flips
+ * "a random bit(s)" of it.  Owning the GEMM, the site space is closed-form:
+ * (i, j, s) for an accumulator fault, (i, k) for an A-operand fault, (k, j)
+ * for a B-operand fault, times the position of an nbits-wide burst.  Draws
+ * come from SplitMix64 (Steele, Lea, Flood 2014) keyed by the trial index so
+ * any trial can be regenerated alone. */
+uint64_t orc_splitmix64_next(uint64_t* state) {
+  *state += 0x9E3779B97F4A7C15ull;
+  uint64_t z = *state;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+static uint32_t unif(uint32_t n, uint64_t u) {
+  return (uint32_t)(((u >> 32) * (uint64_t)n) >> 32);
+}
+
+int orc_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials,
+                      const orc_problem* p, int kind_mode, int nbits, orc_fault* out) {
+  if (check_problem(p) || !out) return 1;
+  if (kind_mode < 0 || kind_mode > 3) return 1;
+  if (nbits < 1 || nbits > 16) return 1;
+  uint32_t S = (uint32_t)(p->K / p->kb);
+  for (uint32_t n = 0; n < n_trials; ++n) {
+    uint64_t t = (uint64_t)first_trial + n;
+    uint64_t state = seed + (t << 32);
+    uint64_t u0 = orc_splitmix64_next(&state);
+    uint64_t u1 = orc_splitmix64_next(&state);
+    uint64_t u2 = orc_splitmix64_next(&state);
+    uint64_t u3 = orc_splitmix64_next(&state);
+    uint32_t kind;
+    switch (kind_mode) {
+      case ORC_KIND_ALL_ACC: kind = ORC_SITE_ACC; break;
+      case ORC_KIND_ALL_A: kind = ORC_SITE_A; break;
+      case ORC_KIND_ALL_B: kind = ORC_SITE_B; break;
+      default: kind = (t % 2 == 0) ? ORC_SITE_ACC : ORC_SITE_A; break;
+    }
+    orc_fault f;
+    f.kind = kind;
+    uint32_t width;
+    if (kind == ORC_SITE_ACC) {
+      f.row = unif((uint32_t)p->M, u0);
+      f.col = unif((uint32_t)p->N, u1);
+      f.kblock = unif(S, u2);
+      width = 32;
+    } else if (kind == ORC_SITE_A) {
+      uint32_t s = unif(S, u1), kk = unif((uint32_t)p->kb, u2);
+      f.row = unif((uint32_t)p->M, u0);
+      f.col = s * (uint32_t)p->kb + kk;
+      f.kblock = s;
+      width = 16;
+    } else {
+      uint32_t s = unif(S, u1), kk = unif((uint32_t)p->kb, u2);
+      f.col = unif((uint32_t)p->N, u0);
+      f.row = s * (uint32_t)p->kb + kk;
+      f.kblock = s;
+      width = 16;
+    }
+    uint32_t pos = unif(width - (uint32_t)nbits + 1u, u3);
+    f.xor_mask = (uint32_t)(((1ull << nbits) - 1ull) << pos);
+    out[n] = f;
+  }
+  return 0;
+}

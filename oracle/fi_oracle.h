@@ -1,0 +1,132 @@
+/*
+ * CPU oracle for fault-injected mixed-precision GEMM campaigns.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, obviously-correct
+ * statement of what one campaign computes.  Only the tests, the smoke check
+ * and the benchmark's cpu_baseline leg may call it; the product library never
+ * does, and the two share no code, headers, tables or helpers.
+ *
+ * What is modelled (paper sections in parentheses):
+ *   - operands in FP16 (1/5/10) or BF16 (1/8/7), decoded exactly   (Sec. II-A, Fig. 1)
+ *   - D = A x B with FP32 accumulation of low-precision products    (Sec. II-B, Sec. IV-C)
+ *   - one fault per trial: a 1/2/4-bit XOR mask                      (Sec. IV-A, Sec. IV-C)
+ *     applied to the FP32 accumulator word of one output element
+ *     after k-block s, or to one 16-bit operand word for the whole
+ *     trial
+ *   - an output-side magnitude-bound detector that generalises the
+ *     per-product range argument e_m <= e_1+e_2+1 to a K-term sum,
+ *     with correction only when detection fires                     (Sec. VI-A, Sec. VI-B)
+ *   - outcome per trial: masked / SDC / detected                     (Sec. I, Sec. V-B)
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py
+ * against closed forms, the paper's Table IV, worked flips, invariants and an
+ * independent step-by-step NumPy float32 reference.  The masked/SDC/detected
+ * *rates* on the synthetic workloads have no published value: parity unpinned
+ * for the rates (they are compared GPU-vs-oracle only).
+ */
+#ifndef FI_ORACLE_H
+#define FI_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ORC_FP16 = 0, ORC_BF16 = 1 };
+enum { ORC_SITE_NONE = 0, ORC_SITE_ACC = 1, ORC_SITE_A = 2, ORC_SITE_B = 3 };
+enum { ORC_CORRECT_NONE = 0, ORC_CORRECT_ZERO = 1, ORC_CORRECT_RECOMPUTE = 2 };
+enum { ORC_BOUND_ROWCOL = 0, ORC_BOUND_GLOBAL = 1 };
+enum { ORC_MASKED = 0, ORC_SDC = 1, ORC_DETECTED = 2 };
+enum { ORC_MODE_FULL = 0, ORC_MODE_AFFECTED = 1 };
+enum { ORC_KIND_ALL_ACC = 0, ORC_KIND_ALL_A = 1, ORC_KIND_ALL_B = 2, ORC_KIND_MIX_ACC_A = 3 };
+
+/* Problem: A is M x K (row i at A + i*lda, K contiguous).  B is K x N
+ * mathematically; b_layout 0 stores it as N rows of K (b_kj at B[j*ldb+k]),
+ * b_layout 1 as K rows of N (b_kj at B[k*ldb+j]).  All 16-bit words. */
+typedef struct {
+  int M, N, K, kb;      /* kb = k-block size, K % kb == 0 */
+  int fmt;              /* ORC_FP16 / ORC_BF16 */
+  int b_layout;
+  int bound_mode;
+  float gamma;          /* slack factor on the bound, >= 1 */
+  long lda, ldb;        /* leading dimensions in elements */
+} orc_problem;
+
+/* One fault.  ACC: (row=i, col=j, kblock=s, 32-bit mask).
+ * A: (row=i, col=k, low 16 bits of mask).  B: (row=k, col=j, low 16 bits). */
+typedef struct {
+  uint32_t kind, row, col, kblock, xor_mask;
+} orc_fault;
+
+/* Per-trial record (the oracle's own layout). */
+typedef struct {
+  double   max_dev_pre;       /* max |c^f - C*| over affected elements, +Inf for NaN/Inf */
+  double   max_dev_post;      /* same after correction */
+  uint32_t n_flagged;         /* elements with !(|c^f| <= T) */
+  uint32_t n_bitdiff;         /* elements whose word differs from C* */
+  uint32_t n_dev_pre;         /* elements with !(|c^f - C*| <= tau) */
+  uint32_t n_dev_post;        /* same on the corrected output */
+  uint32_t site_word_before;  /* ACC: accumulator word at the injection point; A/B: operand word */
+  uint32_t site_word_after;
+  uint32_t n_border_T;        /* affected elements inside the guard band around T */
+  uint32_t n_border_tau;      /* affected elements inside the guard band around tau */
+  uint32_t valid;             /* 0: site out of range, trial ran fault-free */
+  uint32_t cls;               /* ORC_MASKED / ORC_SDC / ORC_DETECTED */
+} orc_record;
+
+/* O1: exact value of a 16-bit pattern, held in a float. */
+float orc_decode16(uint16_t w, int fmt);
+void  orc_decode_array(const uint16_t* in, size_t n, int fmt, float* out);
+
+/* O2: blocked FP32 dot product of row i of A and column j of B, no fault. */
+float orc_dot(const orc_problem* p, const uint16_t* A, const uint16_t* B, int i, int j);
+
+/* O2 over the whole matrix.  C is M x N row-major.  R and S (nullable) get
+ * the double-precision sum and sum of magnitudes of the products. */
+int orc_gemm(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+             float* C, double* R, double* S);
+
+/* O4 statistics: ra[i] = max_k |a_ik|, cb[j] = max_k |b_kj|.
+ * Returns nonzero if an operand is Inf/NaN. */
+int orc_rowcol_absmax(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                      float* ra, float* cb);
+
+/* O4 threshold: fl32(fl32(fl32(K*ra)*cb)*gamma). */
+float orc_threshold(int K, float ra, float cb, float gamma);
+
+/* O4+O5 on a materialised batch of outputs, in place.  c_star is needed for
+ * RECOMPUTE only.  flags (nullable) is [batch][M][N] bytes; n_flagged [batch]. */
+int orc_detect_correct(const orc_problem* p, const float* ra, const float* cb,
+                       float* C, int batch, int policy, const float* c_star,
+                       uint8_t* flags, uint32_t* n_flagged);
+
+/* O3-O6 for one trial.  mode FULL recomputes every output element with the
+ * fault in place and compares all of them; mode AFFECTED recomputes only the
+ * element / row / column a fault can reach.  cf_out / cc_out (nullable, FULL
+ * only) receive the faulty and the corrected M x N outputs. */
+int orc_trial(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+              const orc_fault* f, int policy, int mode,
+              float* cf_out, float* cc_out, orc_record* rec);
+
+/* A whole campaign; trials are independent. */
+int orc_campaign(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                 const orc_fault* faults, int n_trials, int policy, int mode,
+                 orc_record* recs);
+
+/* O6 classification totals: counts[0..2] = masked, sdc, detected. */
+void orc_classify(const orc_record* recs, int n, uint8_t* cls, uint64_t counts[3]);
+
+/* O7 sampler. */
+uint64_t orc_splitmix64_next(uint64_t* state);
+int orc_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials,
+                      const orc_problem* p, int kind_mode, int nbits, orc_fault* out);
+
+/* Number of threads the row-parallel loops use (1 without OpenMP). */
+int orc_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

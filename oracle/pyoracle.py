@@ -1,0 +1,227 @@
+"""ctypes loader for the CPU oracle (test infrastructure, never used by the product path).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this.
+The record / fault dtypes below mirror oracle/fi_oracle.h and nothing else.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fi_oracle.c")
+_LIB = os.path.join(_HERE, "libfi_oracle.so")
+
+FP16, BF16 = 0, 1
+SITE_NONE, SITE_ACC, SITE_A, SITE_B = 0, 1, 2, 3
+CORRECT_NONE, CORRECT_ZERO, CORRECT_RECOMPUTE = 0, 1, 2
+BOUND_ROWCOL, BOUND_GLOBAL = 0, 1
+MASKED, SDC, DETECTED = 0, 1, 2
+MODE_FULL, MODE_AFFECTED = 0, 1
+KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A = 0, 1, 2, 3
+
+
+class Problem(C.Structure):
+    _fields_ = [("M", C.c_int), ("N", C.c_int), ("K", C.c_int), ("kb", C.c_int),
+                ("fmt", C.c_int), ("b_layout", C.c_int), ("bound_mode", C.c_int),
+                ("gamma", C.c_float), ("lda", C.c_long), ("ldb", C.c_long)]
+
+
+FAULT_DTYPE = np.dtype([("kind", "<u4"), ("row", "<u4"), ("col", "<u4"),
+                        ("kblock", "<u4"), ("xor_mask", "<u4")])
+
+RECORD_DTYPE = np.dtype([("max_dev_pre", "<f8"), ("max_dev_post", "<f8"),
+                         ("n_flagged", "<u4"), ("n_bitdiff", "<u4"),
+                         ("n_dev_pre", "<u4"), ("n_dev_post", "<u4"),
+                         ("site_word_before", "<u4"), ("site_word_after", "<u4"),
+                         ("n_border_T", "<u4"), ("n_border_tau", "<u4"),
+                         ("valid", "<u4"), ("cls", "<u4")])
+
+DEFAULT_GAMMA = 1.0 + 2.0 ** -11
+
+
+def build(force=False):
+    """Compile the oracle with gcc.  -ffp-contract=off keeps a*b+c as two roundings."""
+    if os.path.exists(_LIB) and not force and os.path.getmtime(_LIB) >= max(
+            os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "fi_oracle.h"))):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+           "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        vp, u16p, f32p, f64p = C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p
+        PP = C.POINTER(Problem)
+        L.orc_decode16.restype = C.c_float
+        L.orc_decode16.argtypes = [C.c_uint16, C.c_int]
+        L.orc_decode_array.restype = None
+        L.orc_decode_array.argtypes = [u16p, C.c_size_t, C.c_int, f32p]
+        L.orc_dot.restype = C.c_float
+        L.orc_dot.argtypes = [PP, u16p, u16p, C.c_int, C.c_int]
+        L.orc_gemm.restype = C.c_int
+        L.orc_gemm.argtypes = [PP, u16p, u16p, f32p, f64p, f64p]
+        L.orc_rowcol_absmax.restype = C.c_int
+        L.orc_rowcol_absmax.argtypes = [PP, u16p, u16p, f32p, f32p]
+        L.orc_threshold.restype = C.c_float
+        L.orc_threshold.argtypes = [C.c_int, C.c_float, C.c_float, C.c_float]
+        L.orc_detect_correct.restype = C.c_int
+        L.orc_detect_correct.argtypes = [PP, f32p, f32p, f32p, C.c_int, C.c_int, f32p, vp, vp]
+        L.orc_trial.restype = C.c_int
+        L.orc_trial.argtypes = [PP, u16p, u16p, vp, C.c_int, C.c_int, f32p, f32p, vp]
+        L.orc_campaign.restype = C.c_int
+        L.orc_campaign.argtypes = [PP, u16p, u16p, vp, C.c_int, C.c_int, C.c_int, vp]
+        L.orc_classify.restype = None
+        L.orc_classify.argtypes = [vp, C.c_int, vp, vp]
+        L.orc_splitmix64_next.restype = C.c_uint64
+        L.orc_splitmix64_next.argtypes = [C.POINTER(C.c_uint64)]
+        L.orc_sample_faults.restype = C.c_int
+        L.orc_sample_faults.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, PP, C.c_int, C.c_int, vp]
+        L.orc_threads.restype = C.c_int
+        L.orc_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def problem(M, N, K, kb, fmt, b_layout=0, bound_mode=BOUND_ROWCOL, gamma=DEFAULT_GAMMA,
+            lda=None, ldb=None):
+    if lda is None:
+        lda = K
+    if ldb is None:
+        ldb = K if b_layout == 0 else N
+    return Problem(M, N, K, kb, fmt, b_layout, bound_mode, gamma, lda, ldb)
+
+
+def decode16(w, fmt):
+    return float(np.float32(lib().orc_decode16(int(w), fmt)))
+
+
+def decode_array(words, fmt):
+    words = _u16(words)
+    out = np.empty(words.shape, np.float32)
+    lib().orc_decode_array(_ptr(words), words.size, fmt, _ptr(out))
+    return out
+
+
+def dot(p, A, B, i, j):
+    A, B = _u16(A), _u16(B)
+    return np.float32(lib().orc_dot(C.byref(p), _ptr(A), _ptr(B), i, j))
+
+
+def gemm(p, A, B, want_double=False):
+    A, B = _u16(A), _u16(B)
+    Cm = np.empty((p.M, p.N), np.float32)
+    R = np.empty((p.M, p.N), np.float64) if want_double else None
+    S = np.empty((p.M, p.N), np.float64) if want_double else None
+    rc = lib().orc_gemm(C.byref(p), _ptr(A), _ptr(B), _ptr(Cm), _ptr(R), _ptr(S))
+    if rc:
+        raise ValueError("orc_gemm failed: %d" % rc)
+    return (Cm, R, S) if want_double else Cm
+
+
+def rowcol_absmax(p, A, B):
+    A, B = _u16(A), _u16(B)
+    ra = np.empty(p.M, np.float32)
+    cb = np.empty(p.N, np.float32)
+    rc = lib().orc_rowcol_absmax(C.byref(p), _ptr(A), _ptr(B), _ptr(ra), _ptr(cb))
+    if rc == 1:
+        raise ValueError("orc_rowcol_absmax: bad arguments")
+    return ra, cb, rc == 0
+
+
+def threshold(K, ra, cb, gamma=DEFAULT_GAMMA):
+    return np.float32(lib().orc_threshold(int(K), float(ra), float(cb), float(gamma)))
+
+
+def detect_correct(p, ra, cb, Cb, policy, c_star=None, want_flags=True):
+    """Returns (corrected copy, flags or None, n_flagged[batch])."""
+    Cb = np.array(Cb, dtype=np.float32, copy=True).reshape(-1, p.M, p.N)
+    batch = Cb.shape[0]
+    flags = np.empty(Cb.shape, np.uint8) if want_flags else None
+    nfl = np.zeros(batch, np.uint32)
+    ra = np.ascontiguousarray(ra, np.float32)
+    cb = np.ascontiguousarray(cb, np.float32)
+    cs = None if c_star is None else np.ascontiguousarray(c_star, np.float32)
+    rc = lib().orc_detect_correct(C.byref(p), _ptr(ra), _ptr(cb), _ptr(Cb), batch, policy,
+                                  _ptr(cs), _ptr(flags), _ptr(nfl))
+    if rc:
+        raise ValueError("orc_detect_correct failed: %d" % rc)
+    return Cb, flags, nfl
+
+
+def make_faults(rows):
+    """rows: iterable of (kind, row, col, kblock, xor_mask)."""
+    rows = list(rows)
+    out = np.zeros(len(rows), FAULT_DTYPE)
+    for t, r in enumerate(rows):
+        out[t] = tuple(int(x) for x in r)
+    return out
+
+
+def trial(p, A, B, fault, policy, mode=MODE_FULL, want_outputs=False):
+    A, B = _u16(A), _u16(B)
+    f = make_faults([fault]) if not isinstance(fault, np.ndarray) else fault
+    rec = np.zeros(1, RECORD_DTYPE)
+    cf = np.empty((p.M, p.N), np.float32) if want_outputs else None
+    cc = np.empty((p.M, p.N), np.float32) if want_outputs else None
+    rc = lib().orc_trial(C.byref(p), _ptr(A), _ptr(B), _ptr(f), policy, mode,
+                         _ptr(cf), _ptr(cc), _ptr(rec))
+    if rc:
+        raise ValueError("orc_trial failed: %d" % rc)
+    return (rec[0], cf, cc) if want_outputs else rec[0]
+
+
+def campaign(p, A, B, faults, policy, mode=MODE_AFFECTED):
+    A, B = _u16(A), _u16(B)
+    faults = np.ascontiguousarray(faults)
+    assert faults.dtype == FAULT_DTYPE
+    recs = np.zeros(len(faults), RECORD_DTYPE)
+    rc = lib().orc_campaign(C.byref(p), _ptr(A), _ptr(B), _ptr(faults), len(faults), policy,
+                            mode, _ptr(recs))
+    if rc:
+        raise ValueError("orc_campaign failed: %d" % rc)
+    return recs
+
+
+def classify(recs):
+    recs = np.ascontiguousarray(recs)
+    cls = np.empty(len(recs), np.uint8)
+    counts = np.zeros(3, np.uint64)
+    lib().orc_classify(_ptr(recs), len(recs), _ptr(cls), _ptr(counts))
+    return cls, counts
+
+
+def splitmix64_stream(state, n):
+    st = C.c_uint64(state)
+    return [int(lib().orc_splitmix64_next(C.byref(st))) for _ in range(n)]
+
+
+def sample_faults(seed, first_trial, n_trials, p, kind_mode, nbits):
+    out = np.zeros(n_trials, FAULT_DTYPE)
+    rc = lib().orc_sample_faults(seed, first_trial, n_trials, C.byref(p), kind_mode, nbits, _ptr(out))
+    if rc:
+        raise ValueError("orc_sample_faults failed: %d" % rc)
+    return out
+
+
+def threads():
+    return int(lib().orc_threads())
