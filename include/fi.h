@@ -1,0 +1,175 @@
+/*
+ * fi.h - C ABI of the MI355X (gfx950) fault-injection campaign engine for
+ * mixed-precision GEMM.
+ *
+ * One campaign = many independent trials of the same GEMM C = A x B, FP16 or
+ * BF16 operands, FP32 accumulation (paper Sec. II-B, Sec. IV-C).  Each trial
+ * carries exactly one fault (Sec. IV-A): an XOR mask of 1, 2 or 4 (any number
+ * of) bits applied either to the FP32 accumulator word of one output element
+ * right after k-block s - the register the paper's write-back finally
+ * overwrites (Sec. III-E) - or to one 16-bit operand word for the whole trial.
+ * An output-side detector then flags every element whose magnitude exceeds
+ * what K products of the operands could ever sum to - the K-term form of the
+ * paper's per-product range argument e_m <= e_1 + e_2 + 1 (Sec. VI-A) - and a
+ * corrector acts only where the detector fired (Sec. VI-B).  Each trial is
+ * finally classified masked / SDC / detected (Sec. I, Sec. V-B).
+ *
+ * Conventions
+ *   - Every pointer whose name starts with d_ is DEVICE memory on the current
+ *     HIP device; h_ is host memory.  The library never allocates memory it
+ *     hands to the caller and never frees caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     device work is enqueued on it.  fi_plan_create synchronises that stream
+ *     once (it has to read back an operand-validity word); the other calls do
+ *     not synchronise, so device-side failures surface at the caller's next
+ *     synchronising call.
+ *   - Every function returns an fi_status; on failure output parameters are
+ *     untouched and fi_last_error() describes the problem.  Nothing throws or
+ *     aborts across this boundary.
+ *   - Bit numbering: bit 0 = least significant bit of the word.  FP32 words:
+ *     bits 0..22 mantissa, 23..30 exponent, 31 sign.  FP16: 10 mantissa, 5
+ *     exponent bits; BF16: 7 mantissa, 8 exponent bits (Sec. II-A, Fig. 1).
+ */
+#ifndef FI_H
+#define FI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t fi_status;
+enum {
+  FI_OK = 0,
+  FI_INVALID_ARG = 1,   /* NULL pointer, zero dimension, K % k_block != 0, ... */
+  FI_UNSUPPORTED = 2,   /* dtype / alignment / size the kernels do not handle */
+  FI_OOM = 3,           /* device allocation failed */
+  FI_DEVICE = 4,        /* a HIP call failed; see fi_last_error() */
+  FI_STATE = 5          /* no gfx950 device, or a destroyed plan */
+};
+
+enum { FI_FP16 = 0, FI_BF16 = 1 };
+enum { FI_SITE_NONE = 0, FI_SITE_ACC = 1, FI_SITE_A = 2, FI_SITE_B = 3 };
+enum { FI_CORRECT_NONE = 0, FI_CORRECT_ZERO = 1, FI_CORRECT_RECOMPUTE = 2 };
+enum { FI_BOUND_ROWCOL = 0, FI_BOUND_GLOBAL = 1 };
+enum { FI_MASKED = 0, FI_SDC = 1, FI_DETECTED = 2 };
+enum { FI_KIND_ALL_ACC = 0, FI_KIND_ALL_A = 1, FI_KIND_ALL_B = 2, FI_KIND_MIX_ACC_A = 3 };
+
+/* One fault (Sec. IV-A: one target, a random bit or bits, one fault per trial).
+ *   ACC : row = i, col = j, kblock = s; xor_mask applies to the 32-bit
+ *         accumulator word of element (i, j) after the last product of
+ *         k-block s has been added.
+ *   A   : row = i, col = k; the low 16 bits of xor_mask apply to a_ik for
+ *         every use in this trial (kblock is ignored).
+ *   B   : row = k, col = j; same for b_kj.
+ *   NONE: a fault-free trial.
+ * A site outside the problem makes the trial run fault-free with
+ * fi_trial_result.status = 1. */
+typedef struct {
+  uint32_t kind, row, col, kblock, xor_mask;
+} fi_fault;
+
+/* Per-trial record.  "Affected" elements are those in the output tiles a fault
+ * can reach; all other elements are bit-identical to the fault-free result.
+ *   tau_ij = 2^-12 * sum_k |a_ik * b_kj| is the deviation a trial may show and
+ *   still count as masked (Sec. V-B: small mantissa changes are absorbed
+ *   during accumulation).  Deviations are taken against the plan's own
+ *   fault-free result C*. */
+typedef struct {
+  uint32_t n_flagged;        /* elements with NOT(|c| <= T_ij), whole output       */
+  uint32_t n_bitdiff;        /* affected elements whose word differs from C*        */
+  uint32_t n_dev_pre;        /* affected elements with NOT(|c - C*| <= tau_ij)      */
+  uint32_t n_dev_post;       /* same, after correction                              */
+  float    max_dev_pre;      /* max |c - C*| before correction (+Inf for NaN/Inf)   */
+  float    max_dev_post;     /* ... after correction                                */
+  uint32_t site_word_before; /* ACC: accumulator word at the injection point;       */
+  uint32_t site_word_after;  /*      A/B: the 16-bit operand word                   */
+  uint32_t n_border_T;       /* changed elements within max(2 tau, T/64) of T       */
+  uint32_t n_border_tau;     /* changed elements with tau/2 <= |c - C*| <= 2 tau    */
+  uint32_t status;           /* 0 ok, 1 site out of range (trial ran fault-free)    */
+  uint32_t reserved;
+} fi_trial_result;
+
+/* Problem description.  A is M x K, row i at dA + i*lda (K contiguous).
+ * b_layout 0: B is stored as N rows of K (b_kj at dB[j*ldb + k]) - the layout
+ * of a linear layer's weight; b_layout 1: K rows of N (b_kj at dB[k*ldb + j]),
+ * transposed once into plan-owned memory at plan creation.
+ * Requirements: k_block a multiple of 16, K a multiple of k_block, K <= 65536;
+ * dA/dB 16-byte aligned and lda/ldb multiples of 8 elements. */
+typedef struct {
+  uint32_t M, N, K, k_block;
+  uint32_t dtype;        /* FI_FP16 / FI_BF16 */
+  uint32_t b_layout;
+  uint32_t bound_mode;   /* FI_BOUND_ROWCOL: T_ij = gamma*K*ra_i*cb_j, ra_i = max_k|a_ik|,
+                            cb_j = max_k|b_kj|; FI_BOUND_GLOBAL: gamma*K*max ra*max cb */
+  float    gamma;        /* >= 1; 0 selects the default 1 + 2^-11 */
+  int64_t  lda, ldb;     /* in elements */
+} fi_plan_desc;
+
+typedef struct fi_plan fi_plan;
+
+/* Build a plan for one (A, B): row/column magnitude maxima, the fault-free
+ * result C* (Sec. II-B: D = A x B, C_in = 0) and the magnitude sums behind
+ * tau.  d_A and d_B must stay alive and unmodified until fi_plan_destroy.
+ * The plan owns its scratch (C*, sums, maxima; a transposed copy of B for
+ * b_layout 1) and frees it in fi_plan_destroy.
+ * Errors: INVALID_ARG (NULLs, zero dims, K % k_block, k_block % 16, gamma < 1,
+ * Inf/NaN operand), UNSUPPORTED (dtype, alignment), OOM, DEVICE, STATE. */
+fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* d_B,
+                         void* stream, fi_plan** out);
+fi_status fi_plan_destroy(fi_plan* plan);
+
+/* Device pointers to plan-owned arrays, valid until fi_plan_destroy:
+ * which 0: C* [M][N] float, 1: sum_k|a_ik b_kj| [M][N] float,
+ * 2: fl32(K*ra_i) [M] float, 3: cb_j [N] float. */
+fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr);
+
+/* Optional tuning.  tile_config: -1 keep, else index of a workgroup-tile shape
+ * (0: 256x256, 1: 128x128, 2: 256x64); trial_group: -1 keep, else how many
+ * trials of the same output tile are scheduled next to each other.  Results
+ * do not depend on either; C* is recomputed on `stream` when the tile changes. */
+fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, void* stream);
+
+/* Run n_trials faulty executions of the whole GEMM in one launch, each with
+ * its fault from d_faults[t], followed in the same kernel by the detector,
+ * the corrector (policy) and the per-trial counters (Sec. IV-A trial,
+ * Sec. VI-A/B detect then correct).  d_results[t] is overwritten.
+ * d_c_out is NULL or [n_trials][M][N] floats receiving the corrected outputs
+ * (policy FI_CORRECT_NONE: the raw faulty outputs).
+ * Errors: INVALID_ARG (NULL plan/faults/results, bad policy, n_trials == 0). */
+fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
+                               uint32_t policy, fi_trial_result* d_results, float* d_c_out,
+                               void* stream);
+
+/* The detector / corrector alone on materialised outputs (Sec. VI-A/B):
+ * d_c is [batch][M][N], corrected in place; d_flags is NULL or
+ * [batch][M][N] bytes (1 = flagged); d_n_flagged is NULL or [batch] counters,
+ * overwritten.  Flags equal those of the fused epilogue on the same values. */
+fi_status fi_detect_correct(fi_plan* plan, float* d_c, uint32_t batch, uint32_t policy,
+                            uint8_t* d_flags, uint32_t* d_n_flagged, void* stream);
+
+/* Outcome per trial (Sec. I: SDC; Sec. V-B: unchanged results; Sec. VI-B):
+ * DETECTED if n_flagged > 0, else SDC if n_dev_pre > 0, else MASKED.
+ * d_class is NULL or [n_trials] bytes; d_counts is [3] totals
+ * (masked, sdc, detected), overwritten. */
+fi_status fi_classify(fi_plan* plan, const fi_trial_result* d_results, uint32_t n_trials,
+                      uint8_t* d_class, uint64_t* d_counts, void* stream);
+
+/* Host-side site selection (Sec. IV-A: uniform target, random bit(s)).
+ * Trial t = first_trial + n draws from SplitMix64 seeded with seed + t*2^32:
+ * u0 -> row (A: i; B: column j), u1, u2 -> (column, k-block) for ACC or
+ * (k-block, offset in block) for operands, u3 -> position of an nbits-wide
+ * run of ones; unif(n, u) = floor((u >> 32) * n / 2^32).
+ * h_out is HOST memory for n_trials faults.  No device is needed. */
+fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials,
+                           const fi_plan_desc* desc, uint32_t kind_mode, uint32_t nbits,
+                           fi_fault* h_out);
+
+/* Thread-local description of the last failure on this thread. */
+const char* fi_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

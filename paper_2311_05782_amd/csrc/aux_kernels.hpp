@@ -1,0 +1,187 @@
+// Small kernels around the fault-injecting GEMM: plan statistics, the
+// standalone detector / corrector, classification, fills and a transpose.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fi.h"
+
+namespace fi {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// Clears counters and records.  A kernel rather than a memset so that callers
+// may capture the library's calls into a HIP graph.
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t step = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += step) p[i] = v;
+}
+
+// Exact value of a 16-bit operand word as a float (Sec. II-A formats).
+template <int DT>
+__device__ __forceinline__ float decode16(uint32_t w) {
+  if constexpr (DT == FI_BF16) {
+    return __uint_as_float(w << 16);
+  } else {
+    unsigned short h = (unsigned short)w;
+    return (float)__builtin_bit_cast(_Float16, h);
+  }
+}
+
+// out[r] = scale * max_k |x_rk| for the rows of a K-contiguous 16-bit matrix:
+// the operand magnitude maxima behind the detector's bound (Sec. VI-A: the
+// result's magnitude is bounded by the operands').  Magnitudes of finite
+// FP16/BF16 numbers order like their low 15 bits.  One wave per row.
+template <int DT>
+__global__ void __launch_bounds__(256) row_absmax_kernel(const uint16_t* __restrict__ X, int rows,
+                                                        int K, uint32_t ld, float scale,
+                                                        float* __restrict__ out,
+                                                        uint32_t* __restrict__ nonfinite) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const uint16_t* x = X + (size_t)row * ld;
+  uint32_t m = 0;
+  for (int c = lane; c < K / 8; c += 64) {
+    u32x4_t v = *reinterpret_cast<const u32x4_t*>(x + c * 8);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      uint32_t lo = v[d] & 0x7FFFu, hi = (v[d] >> 16) & 0x7FFFu;
+      m = lo > m ? lo : m;
+      m = hi > m ? hi : m;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    uint32_t w = __shfl_xor(m, o, 64);
+    m = w > m ? w : m;
+  }
+  if (lane == 0) {
+    const uint32_t first_nonfinite = (DT == FI_BF16) ? 0x7F80u : 0x7C00u;
+    if (m >= first_nonfinite) atomicOr(nonfinite, 1u);
+    out[row] = __fmul_rn(scale, decode16<DT>(m));
+  }
+}
+
+// out[0] = max(v[0..n)) for non-negative floats; one workgroup.
+__global__ void __launch_bounds__(1024) max_reduce_kernel(const float* __restrict__ v, int n,
+                                                         float* __restrict__ out) {
+  __shared__ uint32_t part[16];
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < n; i += 1024) {
+    uint32_t w = __float_as_uint(v[i]);
+    m = w > m ? w : m;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    uint32_t w = __shfl_xor(m, o, 64);
+    m = w > m ? w : m;
+  }
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int i = 1; i < 16; ++i) m = part[i] > m ? part[i] : m;
+    out[0] = __uint_as_float(m);
+  }
+}
+
+// [K][N] -> [N][K] for 16-bit words.
+__global__ void __launch_bounds__(256) transpose16_kernel(const uint16_t* __restrict__ in, uint32_t ld_in,
+                                                         uint16_t* __restrict__ out, uint32_t ld_out,
+                                                         int K, int N) {
+  __shared__ uint16_t t[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  const int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  for (int r = ty; r < 32; r += 8) {
+    int k = k0 + r, n = n0 + tx;
+    t[r][tx] = (k < K && n < N) ? in[(size_t)k * ld_in + n] : (uint16_t)0;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    int n = n0 + r, k = k0 + tx;
+    if (n < N && k < K) out[(size_t)n * ld_out + k] = t[tx][r];
+  }
+}
+
+// Detector and corrector on materialised outputs (Sec. VI-A detection,
+// Sec. VI-B correction only where detection fired).  grid = (chunks, batch);
+// one thread handles 4 consecutive elements of a row when N % 4 == 0, else 1.
+// The threshold is built with the same three roundings as the fused epilogue:
+// fl32(fl32(kra_i * cb_j) * gamma).
+template <int VEC>
+__global__ void __launch_bounds__(256) detect_correct_kernel(
+    float* __restrict__ C, int M, int N, const float* __restrict__ kra, const float* __restrict__ cb,
+    float gamma, int bound_global, float t_global, int policy, const float* __restrict__ c_star,
+    uint8_t* __restrict__ flags, uint32_t* __restrict__ n_flagged) {
+  const size_t mn = (size_t)M * N;
+  const size_t per = mn / VEC;
+  float* c = C + (size_t)blockIdx.y * mn;
+  uint8_t* fl = flags ? flags + (size_t)blockIdx.y * mn : nullptr;
+  uint32_t cnt = 0;
+  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < per; q += (size_t)gridDim.x * 256) {
+    const size_t e0 = q * VEC;
+    const int row = (int)(e0 / (size_t)N), col0 = (int)(e0 % (size_t)N);
+    float v[VEC];
+    if constexpr (VEC == 4) {
+      f32x4_t t = *reinterpret_cast<const f32x4_t*>(c + e0);
+      v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+    } else {
+      v[0] = c[e0];
+    }
+    const float kr = kra[row];
+    uint32_t fbits = 0;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      float T = bound_global ? t_global : __fmul_rn(__fmul_rn(kr, cb[col0 + e]), gamma);
+      bool f = !(fabsf(v[e]) <= T);
+      fbits |= (f ? 1u : 0u) << (8 * e);
+      if (f) {
+        cnt += 1;
+        if (policy == FI_CORRECT_ZERO) c[e0 + e] = 0.0f;
+        else if (policy == FI_CORRECT_RECOMPUTE) c[e0 + e] = c_star[e0 + e];
+      }
+    }
+    if (fl) {
+      if constexpr (VEC == 4) *reinterpret_cast<uint32_t*>(fl + e0) = fbits;
+      else fl[e0] = (uint8_t)fbits;
+    }
+  }
+  if (n_flagged && __ballot(cnt != 0)) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+    if ((threadIdx.x & 63) == 0 && cnt) atomicAdd(n_flagged + blockIdx.y, cnt);
+  }
+}
+
+// Outcome per trial and campaign totals, one workgroup, no atomics:
+// DETECTED if anything was flagged, else SDC if anything deviates beyond the
+// tolerance, else MASKED.
+__global__ void __launch_bounds__(1024) classify_kernel(const fi_trial_result* __restrict__ r, uint32_t n,
+                                                       uint8_t* __restrict__ cls,
+                                                       uint64_t* __restrict__ counts) {
+  __shared__ uint32_t part[3][16];
+  uint32_t c0 = 0, c1 = 0, c2 = 0;
+  for (uint32_t t = threadIdx.x; t < n; t += 1024) {
+    uint32_t k = r[t].n_flagged > 0 ? FI_DETECTED : (r[t].n_dev_pre > 0 ? FI_SDC : FI_MASKED);
+    if (cls) cls[t] = (uint8_t)k;
+    c0 += (k == FI_MASKED); c1 += (k == FI_SDC); c2 += (k == FI_DETECTED);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    c0 += __shfl_xor(c0, o, 64); c1 += __shfl_xor(c1, o, 64); c2 += __shfl_xor(c2, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    part[0][threadIdx.x >> 6] = c0; part[1][threadIdx.x >> 6] = c1; part[2][threadIdx.x >> 6] = c2;
+  }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    uint64_t s = 0;
+    for (int i = 0; i < 16; ++i) s += part[threadIdx.x][i];
+    counts[threadIdx.x] = s;
+  }
+}
+
+}  // namespace fi

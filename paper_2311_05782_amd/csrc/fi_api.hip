@@ -1,0 +1,436 @@
+// C ABI of the fault-injection campaign engine (see include/fi.h): argument
+// checking, plan construction and kernel launches.  No device work happens
+// anywhere else.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "aux_kernels.hpp"
+#include "fi.h"
+#include "gemm_fi.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+fi_status fail(fi_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define FI_HIP(call)                                                                        \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return fail(e_ == hipErrorOutOfMemory ? FI_OOM : FI_DEVICE, "%s failed: %s", #call,   \
+                  hipGetErrorString(e_));                                                   \
+  } while (0)
+
+constexpr uint32_t PLAN_MAGIC = 0x46495031u;   // "FIP1"
+constexpr int PAD = 512;                       // row/column vectors are zero padded to this multiple
+
+// Tile configurations: workgroup tile BM x BN computed by WM x WN waves.
+struct TileCfg { int bm, bn, wm, wn; };
+constexpr TileCfg kCfg[] = {
+    {256, 256, 4, 2},   // 8 waves, each 64 x 128: large square-ish problems
+    {128, 128, 2, 2},   // 4 waves, each 64 x 64
+    {256, 64, 4, 1},    // 4 waves, each 64 x 64: narrow outputs (N <= 64)
+};
+constexpr int kNumCfg = sizeof(kCfg) / sizeof(kCfg[0]);
+
+}  // namespace
+
+struct fi_plan {
+  uint32_t magic;
+  fi_plan_desc d;
+  const uint16_t* A;
+  const uint16_t* B;       // effective [N][ldb] K-contiguous matrix
+  uint32_t ldb;
+  uint16_t* Bt;            // plan-owned transposed copy (b_layout 1) or NULL
+  float* c_star;           // [M][N]
+  float* s_abs;            // [M][N]
+  float* kra;              // [pad(M)]
+  float* cb;               // [pad(N)]
+  float* scratch;          // 4 floats + 1 word
+  float t_global;
+  int cfg;                 // index into kCfg
+  int group;               // trials sharing a tile back to back
+  int device;
+};
+
+namespace {
+
+using fi::GemmArgs;
+
+template <int DT, int CFG, int MODE>
+hipError_t launch_cfg(const GemmArgs& a, int n_blocks, hipStream_t s) {
+  constexpr TileCfg c = kCfg[CFG];
+  hipLaunchKernelGGL((fi::gemm_fi_kernel<DT, c.bm, c.bn, c.wm, c.wn, MODE>), dim3(n_blocks),
+                     dim3(c.wm * c.wn * 64), 0, s, a);
+  return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_gemm(int dtype, int cfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
+#define FI_CASE(DT, CFG) \
+  if (dtype == DT && cfg == CFG) return launch_cfg<DT, CFG, MODE>(a, n_blocks, s)
+  FI_CASE(FI_FP16, 0); FI_CASE(FI_FP16, 1); FI_CASE(FI_FP16, 2);
+  FI_CASE(FI_BF16, 0); FI_CASE(FI_BF16, 1); FI_CASE(FI_BF16, 2);
+#undef FI_CASE
+  return hipErrorInvalidValue;
+}
+
+int pick_cfg(const fi_plan_desc& d) {
+  if (d.N <= 64) return 2;
+  if (d.M >= 512 && d.N >= 512) return 0;
+  return 1;
+}
+
+GemmArgs base_args(const fi_plan* p) {
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  const TileCfg c = kCfg[p->cfg];
+  a.A = p->A; a.B = p->B; a.lda = (uint32_t)p->d.lda; a.ldb = p->ldb;
+  a.M = (int)p->d.M; a.N = (int)p->d.N; a.K = (int)p->d.K; a.kb = (int)p->d.k_block;
+  a.tiles_m = (a.M + c.bm - 1) / c.bm;
+  a.tiles_n = (a.N + c.bn - 1) / c.bn;
+  a.kra = p->kra; a.cb = p->cb; a.gamma = p->d.gamma;
+  a.bound_global = p->d.bound_mode == FI_BOUND_GLOBAL;
+  a.t_global = p->t_global;
+  a.c_star = p->c_star; a.s_abs = p->s_abs;
+  a.operand_and = 0xFFFFFFFFu;
+  return a;
+}
+
+// C* and the magnitude sums, with the same kernel family the campaign uses.
+fi_status compute_golden(fi_plan* p, hipStream_t s) {
+  GemmArgs a = base_args(p);
+  a.n_trials = 1; a.group = 1;
+  a.c_out = p->c_star;
+  FI_HIP(launch_gemm<fi::MODE_GOLDEN>((int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
+  a.c_out = p->s_abs;
+  a.operand_and = 0x7FFF7FFFu;
+  FI_HIP(launch_gemm<fi::MODE_GOLDEN>((int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
+  return FI_OK;
+}
+
+fi_status check_device() {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(FI_STATE, "no HIP device: %s", hipGetErrorString(e));
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) return fail(FI_STATE, "hipGetDeviceProperties: %s", hipGetErrorString(e));
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return fail(FI_STATE, "device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+  return FI_OK;
+}
+
+fi_status check_desc(const fi_plan_desc* d, float* gamma_out) {
+  if (!d) return fail(FI_INVALID_ARG, "desc is NULL");
+  if (d->M == 0 || d->N == 0 || d->K == 0) return fail(FI_INVALID_ARG, "M, N, K must be non-zero");
+  if (d->k_block == 0 || d->k_block % 16 != 0)
+    return fail(FI_INVALID_ARG, "k_block must be a non-zero multiple of 16 (got %u)", d->k_block);
+  if (d->K % d->k_block != 0)
+    return fail(FI_INVALID_ARG, "K (%u) must be a multiple of k_block (%u)", d->K, d->k_block);
+  if (d->dtype != FI_FP16 && d->dtype != FI_BF16)
+    return fail(FI_UNSUPPORTED, "dtype %u: only FP16 (0) and BF16 (1) operands", d->dtype);
+  if (d->b_layout > 1) return fail(FI_INVALID_ARG, "b_layout must be 0 or 1");
+  if (d->bound_mode > 1) return fail(FI_INVALID_ARG, "bound_mode must be 0 or 1");
+  float g = d->gamma == 0.0f ? 1.0f + 1.0f / 2048.0f : d->gamma;
+  if (!(g >= 1.0f) || !(g <= 3.0e38f)) return fail(FI_INVALID_ARG, "gamma must be finite and >= 1");
+  if (d->K > 65536u) return fail(FI_UNSUPPORTED, "K > 65536");
+  if (d->M > (1u << 24) || d->N > (1u << 24)) return fail(FI_UNSUPPORTED, "M or N > 2^24");
+  if (gamma_out) *gamma_out = g;
+  return FI_OK;
+}
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+fi_status check_plan(const fi_plan* p) {
+  if (!p) return fail(FI_INVALID_ARG, "plan is NULL");
+  if (p->magic != PLAN_MAGIC) return fail(FI_STATE, "plan is not live (destroyed or corrupt)");
+  return FI_OK;
+}
+
+void free_plan_buffers(fi_plan* p) {
+  if (p->Bt) (void)hipFree(p->Bt);
+  if (p->c_star) (void)hipFree(p->c_star);
+  if (p->s_abs) (void)hipFree(p->s_abs);
+  if (p->kra) (void)hipFree(p->kra);
+  if (p->cb) (void)hipFree(p->cb);
+  if (p->scratch) (void)hipFree(p->scratch);
+}
+
+size_t padded(uint32_t n) { return ((size_t)n + PAD - 1) / PAD * PAD; }
+
+fi_status build_plan(fi_plan* p, const void* d_A, const void* d_B, hipStream_t s) {
+  const fi_plan_desc& d = p->d;
+  const size_t mn = (size_t)d.M * d.N;
+  FI_HIP(hipMalloc(&p->c_star, mn * sizeof(float)));
+  FI_HIP(hipMalloc(&p->s_abs, mn * sizeof(float)));
+  FI_HIP(hipMalloc(&p->kra, padded(d.M) * sizeof(float)));
+  FI_HIP(hipMalloc(&p->cb, padded(d.N) * sizeof(float)));
+  FI_HIP(hipMalloc(&p->scratch, 8 * sizeof(float)));
+  p->A = static_cast<const uint16_t*>(d_A);
+  if (d.b_layout == 0) {
+    p->B = static_cast<const uint16_t*>(d_B);
+    p->ldb = (uint32_t)d.ldb;
+  } else {
+    FI_HIP(hipMalloc(&p->Bt, (size_t)d.N * d.K * sizeof(uint16_t)));
+    dim3 grid((d.N + 31) / 32, (d.K + 31) / 32);
+    hipLaunchKernelGGL(fi::transpose16_kernel, grid, dim3(256), 0, s,
+                       static_cast<const uint16_t*>(d_B), (uint32_t)d.ldb, p->Bt, d.K, (int)d.K, (int)d.N);
+    FI_HIP(hipGetLastError());
+    p->B = p->Bt;
+    p->ldb = d.K;
+  }
+  // statistics
+  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3(64), dim3(256), 0, s,
+                     reinterpret_cast<uint32_t*>(p->kra), padded(d.M), 0u);
+  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3(64), dim3(256), 0, s,
+                     reinterpret_cast<uint32_t*>(p->cb), padded(d.N), 0u);
+  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3(1), dim3(64), 0, s,
+                     reinterpret_cast<uint32_t*>(p->scratch), (size_t)8, 0u);
+  uint32_t* bad = reinterpret_cast<uint32_t*>(p->scratch + 4);
+  if (d.dtype == FI_FP16) {
+    hipLaunchKernelGGL(fi::row_absmax_kernel<FI_FP16>, dim3((d.M + 3) / 4), dim3(256), 0, s, p->A, (int)d.M,
+                       (int)d.K, (uint32_t)d.lda, (float)d.K, p->kra, bad);
+    hipLaunchKernelGGL(fi::row_absmax_kernel<FI_FP16>, dim3((d.N + 3) / 4), dim3(256), 0, s, p->B, (int)d.N,
+                       (int)d.K, p->ldb, 1.0f, p->cb, bad);
+  } else {
+    hipLaunchKernelGGL(fi::row_absmax_kernel<FI_BF16>, dim3((d.M + 3) / 4), dim3(256), 0, s, p->A, (int)d.M,
+                       (int)d.K, (uint32_t)d.lda, (float)d.K, p->kra, bad);
+    hipLaunchKernelGGL(fi::row_absmax_kernel<FI_BF16>, dim3((d.N + 3) / 4), dim3(256), 0, s, p->B, (int)d.N,
+                       (int)d.K, p->ldb, 1.0f, p->cb, bad);
+  }
+  FI_HIP(hipGetLastError());
+  hipLaunchKernelGGL(fi::max_reduce_kernel, dim3(1), dim3(1024), 0, s, p->kra, (int)d.M, p->scratch + 0);
+  hipLaunchKernelGGL(fi::max_reduce_kernel, dim3(1), dim3(1024), 0, s, p->cb, (int)d.N, p->scratch + 1);
+  FI_HIP(hipGetLastError());
+  fi_status st = compute_golden(p, s);
+  if (st != FI_OK) return st;
+  float host[8];
+  FI_HIP(hipMemcpyAsync(host, p->scratch, sizeof(host), hipMemcpyDeviceToHost, s));
+  FI_HIP(hipStreamSynchronize(s));
+  uint32_t badw;
+  memcpy(&badw, &host[4], 4);
+  if (badw) return fail(FI_INVALID_ARG, "A or B holds an Inf or NaN: the magnitude bound is undefined");
+  // T = fl32(fl32(fl32(K*ra_max) * cb_max) * gamma), one rounding per product
+  volatile float t = host[0] * host[1];
+  t = t * d.gamma;
+  p->t_global = t;
+  return FI_OK;
+}
+
+uint64_t splitmix64(uint64_t* state) {
+  uint64_t z = (*state += 0x9E3779B97F4A7C15ull);
+  z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+  z ^= z >> 27; z *= 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return z;
+}
+
+inline uint32_t scale_to(uint32_t n, uint64_t u) { return (uint32_t)(((u >> 32) * (uint64_t)n) >> 32); }
+
+}  // namespace
+
+extern "C" {
+
+const char* fi_last_error(void) { return g_err; }
+
+fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* d_B, void* stream,
+                         fi_plan** out) {
+  float gamma = 0.f;
+  fi_status st = check_desc(desc, &gamma);
+  if (st != FI_OK) return st;
+  if (!d_A || !d_B || !out) return fail(FI_INVALID_ARG, "d_A, d_B and out must be non-NULL");
+  const fi_plan_desc& d = *desc;
+  const int64_t min_ldb = d.b_layout == 0 ? (int64_t)d.K : (int64_t)d.N;
+  if (d.lda < (int64_t)d.K || d.ldb < min_ldb)
+    return fail(FI_INVALID_ARG, "leading dimension smaller than the row length");
+  if ((reinterpret_cast<uintptr_t>(d_A) & 15u) || (d.lda & 7))
+    return fail(FI_UNSUPPORTED, "A must be 16-byte aligned with lda a multiple of 8");
+  if (d.b_layout == 0 && ((reinterpret_cast<uintptr_t>(d_B) & 15u) || (d.ldb & 7)))
+    return fail(FI_UNSUPPORTED, "B must be 16-byte aligned with ldb a multiple of 8");
+  if ((uint64_t)d.M * (uint64_t)d.lda >= (1ull << 31) ||
+      (uint64_t)d.N * (uint64_t)(d.b_layout == 0 ? d.ldb : (int64_t)d.K) >= (1ull << 31))
+    return fail(FI_UNSUPPORTED, "an operand spans 2^31 elements or more");
+  if ((uint64_t)d.M * (uint64_t)d.N >= (1ull << 40)) return fail(FI_UNSUPPORTED, "M*N too large");
+  st = check_device();
+  if (st != FI_OK) return st;
+
+  fi_plan* p = new (std::nothrow) fi_plan;
+  if (!p) return fail(FI_OOM, "host allocation failed");
+  memset(p, 0, sizeof(*p));
+  p->d = d;
+  p->d.gamma = gamma;
+  p->cfg = pick_cfg(d);
+  p->group = 32;
+  (void)hipGetDevice(&p->device);
+  st = build_plan(p, d_A, d_B, as_stream(stream));
+  if (st != FI_OK) {
+    (void)hipStreamSynchronize(as_stream(stream));
+    free_plan_buffers(p);
+    delete p;
+    return st;
+  }
+  p->magic = PLAN_MAGIC;
+  *out = p;
+  return FI_OK;
+}
+
+fi_status fi_plan_destroy(fi_plan* plan) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  (void)hipDeviceSynchronize();   // work that still reads the plan's buffers
+  free_plan_buffers(plan);
+  plan->magic = 0;
+  delete plan;
+  return FI_OK;
+}
+
+fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_ptr) return fail(FI_INVALID_ARG, "d_ptr is NULL");
+  switch (which) {
+    case 0: *d_ptr = plan->c_star; break;
+    case 1: *d_ptr = plan->s_abs; break;
+    case 2: *d_ptr = plan->kra; break;
+    case 3: *d_ptr = plan->cb; break;
+    default: return fail(FI_INVALID_ARG, "which must be 0..3");
+  }
+  return FI_OK;
+}
+
+fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (tile_config >= kNumCfg) return fail(FI_INVALID_ARG, "tile_config must be < %d", kNumCfg);
+  if (trial_group == 0 || trial_group > 4096) return fail(FI_INVALID_ARG, "trial_group must be in 1..4096");
+  if (trial_group > 0) plan->group = trial_group;
+  if (tile_config >= 0 && tile_config != plan->cfg) {
+    plan->cfg = tile_config;
+    return compute_golden(plan, as_stream(stream));
+  }
+  return FI_OK;
+}
+
+fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
+                               fi_trial_result* d_results, float* d_c_out, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_faults || !d_results) return fail(FI_INVALID_ARG, "d_faults and d_results must be non-NULL");
+  if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
+  if (policy > FI_CORRECT_RECOMPUTE) return fail(FI_INVALID_ARG, "unknown correction policy %u", policy);
+  GemmArgs a = base_args(plan);
+  const uint64_t blocks = (uint64_t)a.tiles_m * a.tiles_n * n_trials;
+  if (blocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
+  hipStream_t s = as_stream(stream);
+  const size_t words = (size_t)n_trials * (sizeof(fi_trial_result) / 4);
+  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3((unsigned)((words + 255) / 256 > 1024 ? 1024 : (words + 255) / 256)),
+                     dim3(256), 0, s, reinterpret_cast<uint32_t*>(d_results), words, 0u);
+  FI_HIP(hipGetLastError());
+  a.n_trials = (int)n_trials;
+  a.group = plan->group < (int)n_trials ? plan->group : (int)n_trials;
+  a.faults = d_faults;
+  a.results = d_results;
+  a.c_out = d_c_out;
+  a.policy = (int)policy;
+  FI_HIP(launch_gemm<fi::MODE_CAMPAIGN>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
+  return FI_OK;
+}
+
+fi_status fi_detect_correct(fi_plan* plan, float* d_c, uint32_t batch, uint32_t policy, uint8_t* d_flags,
+                            uint32_t* d_n_flagged, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_c) return fail(FI_INVALID_ARG, "d_c is NULL");
+  if (batch == 0 || batch > 65535u) return fail(FI_INVALID_ARG, "batch must be in 1..65535");
+  if (policy > FI_CORRECT_RECOMPUTE) return fail(FI_INVALID_ARG, "unknown correction policy %u", policy);
+  hipStream_t s = as_stream(stream);
+  const fi_plan_desc& d = plan->d;
+  if (d_n_flagged) {
+    hipLaunchKernelGGL(fi::fill_u32_kernel, dim3((batch + 255) / 256), dim3(256), 0, s, d_n_flagged,
+                       (size_t)batch, 0u);
+    FI_HIP(hipGetLastError());
+  }
+  const size_t mn = (size_t)d.M * d.N;
+  const bool vec = (d.N % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_c) & 15u) == 0) &&
+                   (!d_flags || (reinterpret_cast<uintptr_t>(d_flags) & 3u) == 0);
+  const size_t per = vec ? mn / 4 : mn;
+  size_t gx = (per + 255) / 256;
+  if (gx > 4096) gx = 4096;
+  dim3 grid((unsigned)gx, batch);
+  if (vec) {
+    hipLaunchKernelGGL(fi::detect_correct_kernel<4>, grid, dim3(256), 0, s, d_c, (int)d.M, (int)d.N, plan->kra,
+                       plan->cb, d.gamma, (int)(d.bound_mode == FI_BOUND_GLOBAL), plan->t_global, (int)policy,
+                       plan->c_star, d_flags, d_n_flagged);
+  } else {
+    hipLaunchKernelGGL(fi::detect_correct_kernel<1>, grid, dim3(256), 0, s, d_c, (int)d.M, (int)d.N, plan->kra,
+                       plan->cb, d.gamma, (int)(d.bound_mode == FI_BOUND_GLOBAL), plan->t_global, (int)policy,
+                       plan->c_star, d_flags, d_n_flagged);
+  }
+  FI_HIP(hipGetLastError());
+  return FI_OK;
+}
+
+fi_status fi_classify(fi_plan* plan, const fi_trial_result* d_results, uint32_t n_trials, uint8_t* d_class,
+                      uint64_t* d_counts, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_results || !d_counts) return fail(FI_INVALID_ARG, "d_results and d_counts must be non-NULL");
+  if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
+  hipLaunchKernelGGL(fi::classify_kernel, dim3(1), dim3(1024), 0, as_stream(stream), d_results, n_trials,
+                     d_class, d_counts);
+  FI_HIP(hipGetLastError());
+  return FI_OK;
+}
+
+fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials, const fi_plan_desc* desc,
+                           uint32_t kind_mode, uint32_t nbits, fi_fault* h_out) {
+  fi_status st = check_desc(desc, nullptr);
+  if (st != FI_OK) return st;
+  if (!h_out) return fail(FI_INVALID_ARG, "h_out is NULL");
+  if (kind_mode > FI_KIND_MIX_ACC_A) return fail(FI_INVALID_ARG, "unknown kind_mode %u", kind_mode);
+  if (nbits < 1 || nbits > 16) return fail(FI_INVALID_ARG, "nbits must be in 1..16");
+  const uint32_t nblocks = desc->K / desc->k_block;
+  for (uint32_t n = 0; n < n_trials; ++n) {
+    const uint64_t t = (uint64_t)first_trial + n;
+    uint64_t state = seed + (t << 32);
+    uint64_t u[4];
+    for (int q = 0; q < 4; ++q) u[q] = splitmix64(&state);
+    fi_fault f;
+    uint32_t kind = kind_mode == FI_KIND_ALL_ACC ? FI_SITE_ACC
+                  : kind_mode == FI_KIND_ALL_A   ? FI_SITE_A
+                  : kind_mode == FI_KIND_ALL_B   ? FI_SITE_B
+                  : ((t & 1) ? FI_SITE_A : FI_SITE_ACC);
+    f.kind = kind;
+    uint32_t width = 16;
+    if (kind == FI_SITE_ACC) {
+      f.row = scale_to(desc->M, u[0]);
+      f.col = scale_to(desc->N, u[1]);
+      f.kblock = scale_to(nblocks, u[2]);
+      width = 32;
+    } else {
+      const uint32_t s = scale_to(nblocks, u[1]);
+      const uint32_t k = s * desc->k_block + scale_to(desc->k_block, u[2]);
+      f.kblock = s;
+      if (kind == FI_SITE_A) { f.row = scale_to(desc->M, u[0]); f.col = k; }
+      else                   { f.row = k; f.col = scale_to(desc->N, u[0]); }
+    }
+    const uint32_t pos = scale_to(width - nbits + 1, u[3]);
+    f.xor_mask = (uint32_t)(((1ull << nbits) - 1ull) << pos);
+    h_out[n] = f;
+  }
+  return FI_OK;
+}
+
+}  // extern "C"

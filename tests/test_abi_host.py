@@ -1,0 +1,102 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/fi.h declares,
+rejects bad arguments before touching a device, and its sampler equals the oracle's."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import pyoracle as orc
+from paper_2311_05782_amd import fi
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "fi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fi_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = fi.lib()
+    declared = _declared()
+    assert sorted(fi.EXPORTS) == declared
+    nm = subprocess.run(["nm", "-D", "--defined-only", fi.LIB_PATH], stdout=subprocess.PIPE, text=True).stdout
+    exported = set(re.findall(r" T (fi_[a-z_]+)", nm))
+    assert set(declared) <= exported
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_struct_layouts_match_header():
+    text = open(os.path.join(ROOT, "include", "fi.h")).read()
+    m = re.search(r"typedef struct \{([^}]*)\} fi_trial_result;", text, flags=re.S)
+    body = re.sub(r"/\*.*?\*/", "", m.group(1), flags=re.S)
+    names = re.findall(r"(\w+)\s*[;,]", body)
+    assert names == list(fi.RESULT_DTYPE.names)
+    m = re.search(r"typedef struct \{([^}]*)\} fi_fault;", text, flags=re.S)
+    assert re.findall(r"(\w+)\s*[;,]", m.group(1)) == list(fi.FAULT_DTYPE.names)
+    assert C.sizeof(fi.PlanDesc) == 48
+
+
+@pytest.mark.parametrize("kind_mode,nbits", [(0, 1), (0, 2), (1, 1), (2, 4), (3, 1)])
+def test_sampler_equals_oracle(kind_mode, nbits):
+    for (M, N, K, kb, seed, first) in [(128, 128, 128, 32, 0, 0), (512, 3072, 768, 32, 1, 100),
+                                       (3136, 64, 576, 32, 2 ** 63 + 5, 7), (4096, 4096, 4096, 64, 3, 0)]:
+        mine = fi.fi_sample_faults(seed, first, 300, fi.plan_desc(M, N, K, kb, fi.BF16), kind_mode, nbits)
+        theirs = orc.sample_faults(seed, first, 300, orc.problem(M, N, K, kb, orc.BF16), kind_mode, nbits)
+        assert mine.tobytes() == theirs.tobytes()
+
+
+def _status(call):
+    with pytest.raises(fi.FiError) as e:
+        call()
+    return e.value.status, str(e.value)
+
+
+def test_argument_errors_need_no_device():
+    good = fi.plan_desc(128, 128, 128, 32, fi.FP16)
+    out = C.c_void_p()
+    L = fi.lib()
+    A = C.c_void_p(0x1000)
+    B = C.c_void_p(0x2000)
+
+    def create(desc, a=A, b=B, o=C.byref(out)):
+        return lambda: fi._check(L.fi_plan_create(C.byref(desc) if desc else None, a, b, None, o))
+
+    assert _status(create(None))[0] == fi.INVALID_ARG
+    assert _status(create(fi.plan_desc(0, 128, 128, 32, fi.FP16)))[0] == fi.INVALID_ARG
+    assert _status(create(fi.plan_desc(128, 128, 100, 32, fi.FP16)))[0] == fi.INVALID_ARG   # K % kb
+    assert _status(create(fi.plan_desc(128, 128, 120, 24, fi.FP16)))[0] == fi.INVALID_ARG   # kb % 16
+    assert _status(create(fi.plan_desc(128, 128, 128, 32, 2)))[0] == fi.UNSUPPORTED          # TF32 etc.
+    assert _status(create(fi.plan_desc(128, 128, 128, 32, fi.FP16, gamma=0.5)))[0] == fi.INVALID_ARG
+    assert _status(create(good, a=None))[0] == fi.INVALID_ARG
+    assert _status(create(good, o=None))[0] == fi.INVALID_ARG
+    assert _status(create(fi.plan_desc(128, 128, 128, 32, fi.FP16, lda=64)))[0] == fi.INVALID_ARG
+    assert _status(create(good, a=C.c_void_p(0x1002)))[0] == fi.UNSUPPORTED                  # alignment
+    assert _status(create(fi.plan_desc(128, 128, 128, 32, fi.FP16, lda=132)))[0] == fi.UNSUPPORTED
+    assert out.value is None
+    # NULL plans
+    assert _status(lambda: fi._check(L.fi_plan_destroy(None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_gemm_inject_batch(None, A, 1, 0, B, None, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_detect_correct(None, A, 1, 0, None, None, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_classify(None, A, 1, None, B, None)))[0] == fi.INVALID_ARG
+    # sampler argument checks
+    assert _status(lambda: fi.fi_sample_faults(0, 0, 4, good, 9, 1))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi.fi_sample_faults(0, 0, 4, good, 0, 0))[0] == fi.INVALID_ARG
+    st, msg = _status(lambda: fi.fi_sample_faults(0, 0, 4, good, 0, 17))
+    assert st == fi.INVALID_ARG and "nbits" in msg
+
+
+def test_no_device_is_reported_not_hidden():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a device is present")
+    out = C.c_void_p()
+    good = fi.plan_desc(128, 128, 128, 32, fi.FP16)
+    st, msg = _status(lambda: fi._check(fi.lib().fi_plan_create(C.byref(good), C.c_void_p(0x1000),
+                                                              C.c_void_p(0x2000), None, C.byref(out))))
+    assert st == fi.STATE and out.value is None

@@ -1,0 +1,263 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU oracle on the
+same seeded inputs.  Integer results (sites, words, flags, counters, classes) must be equal;
+where FP32 summation order can matter the rule is the guard-banded one in gpu_util."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import pyoracle as orc
+from paper_2311_05782_amd import fi, workloads as wl
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def test_one_hip_runtime_and_native_library_loaded():
+    import torch
+    assert torch.cuda.is_available()
+    fi.lib()
+    maps = open("/proc/self/maps").read()
+    hips = {ln.split()[-1] for ln in maps.splitlines() if "libamdhip64" in ln}
+    assert len(hips) == 1, hips
+    assert any("libfi_gfx950.so" in ln for ln in maps.splitlines())
+
+
+def _mixed_faults(M, N, K, kb, n, seed):
+    """Accumulator, A, B and fault-free trials, with sites forced into tile corners and tails."""
+    rng = np.random.default_rng(seed)
+    S = K // kb
+    rows = []
+    for t in range(n):
+        kind = [orc.SITE_ACC, orc.SITE_ACC, orc.SITE_A, orc.SITE_B, orc.SITE_NONE][t % 5]
+        if kind == orc.SITE_ACC:
+            r = (kind, rng.integers(M), rng.integers(N), rng.integers(S), 1 << int(rng.integers(32)))
+        elif kind == orc.SITE_A:
+            r = (kind, rng.integers(M), rng.integers(K), 0, 1 << int(rng.integers(16)))
+        elif kind == orc.SITE_B:
+            r = (kind, rng.integers(K), rng.integers(N), 0, 1 << int(rng.integers(16)))
+        else:
+            r = (kind, 0, 0, 0, 0)
+        rows.append(r)
+    # corners and last elements
+    rows += [(orc.SITE_ACC, M - 1, N - 1, S - 1, 1 << 31), (orc.SITE_ACC, 0, 0, 0, 1 << 23),
+             (orc.SITE_ACC, M - 1, 0, S - 1, 0x00C00000), (orc.SITE_A, M - 1, K - 1, 0, 1 << 9),
+             (orc.SITE_B, K - 1, N - 1, 0, 1 << 14), (orc.SITE_A, 0, 0, 0, 0xF000)]
+    return orc.make_faults(rows)
+
+
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+@pytest.mark.parametrize("shape", [(300, 200, 192, 32), (257, 65, 128, 64), (96, 40, 96, 48), (64, 64, 64, 16)])
+def test_exact_regime_everything_bit_equal(fmt, cfg, shape):
+    # Small-integer operands: every partial sum is exact, so summation order cannot matter and
+    # outputs, words, flags and counters must all be identical.  Shapes span several tiles and
+    # ragged tails in M, N and K (K = 96 is not a multiple of the 64-wide k-tile).
+    M, N, K, kb = shape
+    Aw, Bw = wl.small_integers(M, N, K, fmt, seed=M + N)
+    faults = _mixed_faults(M, N, K, kb, 24, seed=K + cfg)
+    plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg, group=5)
+    p = orc.problem(M, N, K, kb, fmt)
+    gold = orc.gemm(p, Aw, Bw)
+    assert np.array_equal(plan.buffer_to_host(fi.BUF_C_STAR).view(np.uint32), gold.view(np.uint32))
+    for policy in (orc.CORRECT_NONE, orc.CORRECT_ZERO, orc.CORRECT_RECOMPUTE):
+        recs, cout = gu.gpu_campaign(plan, faults, policy, want_c=True)
+        for t in range(len(faults)):
+            o, cf, cc = orc.trial(p, Aw, Bw, faults[t:t + 1], policy, orc.MODE_FULL, want_outputs=True)
+            nan = np.isnan(cc)
+            assert np.array_equal(np.isnan(cout[t]), nan), (t, faults[t])
+            assert np.array_equal(cout[t][~nan].view(np.uint32), cc[~nan].view(np.uint32)), (t, faults[t])
+            g = recs[t]
+            for k in ("n_flagged", "n_dev_pre", "n_dev_post", "site_word_before", "site_word_after"):
+                assert int(g[k]) == int(o[k]), (k, t, faults[t], int(g[k]), int(o[k]))
+            if not nan.any():
+                assert int(g["n_bitdiff"]) == int(o["n_bitdiff"]), (t, faults[t])
+            assert np.float32(g["max_dev_pre"]) == np.float32(o["max_dev_pre"]), (t, faults[t])
+            assert np.float32(g["max_dev_post"]) == np.float32(o["max_dev_post"]), (t, faults[t])
+            assert int(g["status"]) == 0
+    plan.destroy()
+
+
+def _check_unfaulted(plan, Aw, Bw, fmt, rows=None):
+    A = orc.decode_array(Aw, fmt).astype(np.float64)
+    Bt = orc.decode_array(Bw, fmt).astype(np.float64)
+    if rows is not None:
+        A = A[rows]
+    R = A @ Bt.T
+    S = np.abs(A) @ np.abs(Bt).T
+    Cg = plan.buffer_to_host(fi.BUF_C_STAR)
+    Sg = plan.buffer_to_host(fi.BUF_S_ABS)
+    if rows is not None:
+        Cg, Sg = Cg[rows], Sg[rows]
+    # the stated tolerance for fault-free outputs
+    assert np.all(np.abs(Cg.astype(np.float64) - R) <= 2.0 ** -12 * S)
+    assert np.all(np.abs(Sg.astype(np.float64) - S) <= 2.0 ** -12 * S)
+    return float(np.max(np.abs(Cg - R) / np.maximum(S, 1e-300)))
+
+
+def _campaign_parity(w, n_trials=None, cfg=None, policies=None, rows_check=None):
+    fmt = w.fmt
+    n = n_trials or w.n_trials
+    plan = gu.make_plan(w.A, w.B, w.kb, fmt, cfg=cfg)
+    desc = plan.desc
+    faults = fi.fi_sample_faults(w.fault_seed, 0, n, desc, w.kind_mode, w.nbits)
+    p = orc.problem(w.M, w.N, w.K, w.kb, fmt)
+    ofaults = orc.sample_faults(w.fault_seed, 0, n, p, w.kind_mode, w.nbits)
+    assert faults.tobytes() == ofaults.tobytes()          # site selection is bit-exact
+    _check_unfaulted(plan, w.A, w.B, fmt, rows_check)
+    ra, cb, finite = orc.rowcol_absmax(p, w.A, w.B)
+    assert finite
+    kra = plan.buffer_to_host(fi.BUF_KRA)
+    assert np.array_equal(kra, (np.float32(w.K) * ra).astype(np.float32))
+    assert np.array_equal(plan.buffer_to_host(fi.BUF_CB), cb)
+    site_tol = 2.0 ** -12 * w.K * float(ra.max()) * float(cb.max())
+    out = {}
+    for policy in (policies or w.policies):
+        recs = gu.gpu_campaign(plan, faults, policy)
+        ora = orc.campaign(p, w.A, w.B, ofaults, policy, orc.MODE_AFFECTED)
+        s = gu.compare_records(recs, ora, faults, site_tol=site_tol)
+        assert not s["mismatches"], s["mismatches"][:10]
+        # classification kernel against the records it was given
+        d_r = fi.to_device(recs)
+        cls, cnt = gu.gpu_classify(plan, d_r, n)
+        assert np.array_equal(cls, gu.cls_of(recs)) and cnt.tolist() == s["gpu_counts"]
+        ocls, ocnt = orc.classify(ora)
+        # totals agree up to the borderline trials
+        assert sum(abs(int(a) - int(b)) for a, b in zip(cnt, ocnt)) <= 2 * s["borderline"]
+        out[policy] = s
+        print(w.name, "policy", policy, s["gpu_counts"], s["oracle_counts"], "borderline", s["borderline"])
+    plan.destroy()
+    return out
+
+
+def test_tiny_campaign():
+    s = _campaign_parity(wl.tiny())[wl.CORRECT_ZERO]
+    assert sum(s["gpu_counts"]) == 64 and min(s["gpu_counts"]) > 0
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_tiny_campaign_every_tile_shape_many_trials(cfg):
+    w = wl.tiny()
+    _campaign_parity(w, n_trials=1500, cfg=cfg, policies=(wl.CORRECT_ZERO, wl.CORRECT_RECOMPUTE, wl.CORRECT_NONE))
+
+
+def test_bert_linear_campaign_full_size():
+    _campaign_parity(wl.bert_linear())
+
+
+def test_resnet_conv_campaign_full_size():
+    _campaign_parity(wl.resnet_conv())
+
+
+def test_detector_stress_campaign_full_size_both_policies():
+    out = _campaign_parity(wl.detector_stress())
+    z, r = out[wl.CORRECT_ZERO], out[wl.CORRECT_RECOMPUTE]
+    assert z["gpu_counts"] == r["gpu_counts"]     # the class does not depend on the corrector
+
+
+def test_square4096_campaign_full_size_launch_configuration_of_the_benchmark():
+    # 1024 trials of 4096^3 in one launch; every trial is checked against the oracle, which
+    # can compute each faulted element on its own.  Unfaulted outputs: sampled rows.
+    w = wl.square4096()
+    rows = np.random.default_rng(0).choice(w.M, 48, replace=False)
+    _campaign_parity(w, rows_check=np.sort(rows))
+
+
+def test_zero_fault_trials_are_masked_on_every_workload():
+    for make in (wl.tiny, wl.bert_linear, wl.resnet_conv, wl.detector_stress):
+        w = make()
+        plan = gu.make_plan(w.A, w.B, w.kb, w.fmt)
+        faults = orc.make_faults([(orc.SITE_NONE, 0, 0, 0, 0), (orc.SITE_ACC, 1, 1, 0, 0),
+                                  (orc.SITE_A, 2, 3, 0, 0), (orc.SITE_NONE, 5, 5, 5, 5)])
+        recs = gu.gpu_campaign(plan, faults, wl.CORRECT_ZERO)
+        for k in ("n_flagged", "n_bitdiff", "n_dev_pre", "n_dev_post", "status"):
+            assert not recs[k].any(), (w.name, k)
+        assert not recs["max_dev_pre"].any() and (gu.cls_of(recs) == fi.MASKED).all()
+        plan.destroy()
+
+
+def test_out_of_range_sites_run_fault_free_and_say_so():
+    w = wl.tiny()
+    plan = gu.make_plan(w.A, w.B, w.kb, w.fmt)
+    faults = orc.make_faults([(orc.SITE_ACC, 128, 0, 0, 1), (orc.SITE_ACC, 0, 128, 0, 1),
+                              (orc.SITE_ACC, 0, 0, 4, 1), (orc.SITE_A, 0, 128, 0, 1),
+                              (orc.SITE_B, 128, 0, 0, 1), (9, 0, 0, 0, 1), (orc.SITE_ACC, 5, 5, 1, 1 << 30)])
+    recs = gu.gpu_campaign(plan, faults, wl.CORRECT_ZERO)
+    assert recs["status"].tolist() == [1, 1, 1, 1, 1, 1, 0]
+    assert not recs["n_bitdiff"][:6].any() and recs["n_bitdiff"][6] == 1
+    plan.destroy()
+
+
+def test_layouts_leading_dimensions_and_global_bound():
+    M, N, K, kb, fmt = 200, 136, 128, 32, orc.FP16
+    Aw, Bw = wl.gaussian(M, N, K, fmt, seed=12)
+    p = orc.problem(M, N, K, kb, fmt)
+    faults = fi.fi_sample_faults(5, 0, 200, fi.plan_desc(M, N, K, kb, fmt), fi.KIND_MIX_ACC_A, 1)
+    of = gu.to_orc_faults(faults)
+    base = gu.make_plan(Aw, Bw, kb, fmt)
+    cbase = base.buffer_to_host(fi.BUF_C_STAR)
+    rbase = gu.gpu_campaign(base, faults, wl.CORRECT_ZERO)
+    # B given as K rows of N
+    alt = gu.make_plan(Aw, np.ascontiguousarray(Bw.T), kb, fmt, b_layout=1)
+    assert np.array_equal(alt.buffer_to_host(fi.BUF_C_STAR).view(np.uint32), cbase.view(np.uint32))
+    assert gu.gpu_campaign(alt, faults, wl.CORRECT_ZERO).tobytes() == rbase.tobytes()
+    # padded leading dimensions
+    Ap = np.zeros((M, K + 8), np.uint16); Ap[:, :K] = Aw
+    Bp = np.zeros((N, K + 16), np.uint16); Bp[:, :K] = Bw
+    import torch
+    dA, dB = fi.words_to_device(Ap), fi.words_to_device(Bp)
+    pad = fi.Plan(fi.plan_desc(M, N, K, kb, fmt, lda=K + 8, ldb=K + 16), dA, dB)
+    assert np.array_equal(pad.buffer_to_host(fi.BUF_C_STAR).view(np.uint32), cbase.view(np.uint32))
+    assert gu.gpu_campaign(pad, faults, wl.CORRECT_ZERO).tobytes() == rbase.tobytes()
+    # global bound against the oracle
+    glob = gu.make_plan(Aw, Bw, kb, fmt, bound_mode=fi.BOUND_GLOBAL)
+    pg = orc.problem(M, N, K, kb, fmt, bound_mode=orc.BOUND_GLOBAL)
+    s = gu.compare_records(gu.gpu_campaign(glob, faults, wl.CORRECT_ZERO),
+                           orc.campaign(pg, Aw, Bw, of, wl.CORRECT_ZERO), faults, site_tol=1.0)
+    assert not s["mismatches"], s["mismatches"][:5]
+    s = gu.compare_records(rbase, orc.campaign(p, Aw, Bw, of, wl.CORRECT_ZERO), faults, site_tol=1.0)
+    assert not s["mismatches"], s["mismatches"][:5]
+    for pl in (base, alt, pad, glob):
+        pl.destroy()
+
+
+def test_nonfinite_operands_are_a_plan_error():
+    Aw, Bw = wl.gaussian(64, 64, 64, orc.BF16, seed=1)
+    Aw = Aw.copy(); Aw[3, 9] = 0x7F80
+    with pytest.raises(fi.FiError) as e:
+        gu.make_plan(Aw, Bw, 32, orc.BF16)
+    assert e.value.status == fi.INVALID_ARG
+
+
+@pytest.mark.parametrize("N", [136, 130])
+def test_standalone_detector_equals_fused_epilogue_and_oracle(N):
+    import torch
+    M, K, kb, fmt = 150, 128, 32, orc.FP16
+    Aw, Bw = wl.gaussian(M, N, K, fmt, seed=3)
+    p = orc.problem(M, N, K, kb, fmt)
+    plan = gu.make_plan(Aw, Bw, kb, fmt)
+    faults = fi.fi_sample_faults(8, 0, 64, plan.desc, fi.KIND_MIX_ACC_A, 2)
+    faults["xor_mask"][::3] = 1 << 30            # plenty of exponent-MSB flips
+    faults["xor_mask"][1::8] = 1 << 14           # FP16 operand exponent MSB: Inf / NaN rows
+    raw_recs, raw = gu.gpu_campaign(plan, faults, wl.CORRECT_NONE, want_c=True)
+    ra, cb, _ = orc.rowcol_absmax(p, Aw, Bw)
+    cstar = plan.buffer_to_host(fi.BUF_C_STAR)
+    for policy in (wl.CORRECT_ZERO, wl.CORRECT_RECOMPUTE, wl.CORRECT_NONE):
+        fused_recs, fused = gu.gpu_campaign(plan, faults, policy, want_c=True)
+        d_c = torch.from_numpy(raw.copy()).cuda()
+        d_fl = torch.empty(raw.shape, dtype=torch.uint8, device="cuda")
+        d_n = torch.empty(len(faults), dtype=torch.int32, device="cuda")
+        plan.fi_detect_correct(d_c, len(faults), policy, d_fl, d_n)
+        torch.cuda.synchronize()
+        alone, flags, nfl = d_c.cpu().numpy(), d_fl.cpu().numpy(), d_n.cpu().numpy().astype(np.uint32)
+        assert np.array_equal(nfl, fused_recs["n_flagged"]) and np.array_equal(nfl, raw_recs["n_flagged"])
+        assert np.array_equal(alone.view(np.uint32), fused.view(np.uint32))
+        oc, oflags, on = orc.detect_correct(p, ra, cb, raw, policy, c_star=cstar)
+        assert np.array_equal(flags, oflags) and np.array_equal(nfl, on)
+        assert np.array_equal(alone.view(np.uint32), oc.view(np.uint32))
+        assert nfl.sum() > 50
+    # counters and flags are optional
+    d_c = torch.from_numpy(raw.copy()).cuda()
+    plan.fi_detect_correct(d_c, len(faults), wl.CORRECT_ZERO)
+    torch.cuda.synchronize()
+    plan.destroy()
