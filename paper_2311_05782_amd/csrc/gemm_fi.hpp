@@ -73,7 +73,8 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
 }
 
 // Slot permutation of the eight 16-byte chunks of a 128-byte LDS row.
-__device__ __forceinline__ int lds_swizzle(int row) { return (row ^ (row >> 3)) & 7; }
+// Depends on row bits 0..3 only, so it is the same for row and row + 32.
+__device__ __forceinline__ int lds_swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
 #pragma unroll

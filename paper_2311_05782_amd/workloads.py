@@ -117,12 +117,13 @@ def detector_stress(seed=4):
     return _finish(w, a, b)
 
 
-def small_integers(M, N, K, fmt, seed=0, lim=4):
-    """Operands are integers in [-lim, lim]: every product and partial sum is an
+def small_integers(M, N, K, fmt, seed=0, lim=4, step=1):
+    """Operands are multiples of `step` in [-lim, lim]: every product and partial sum is an
     exactly representable integer, so any summation order gives the same bits."""
     rng = np.random.default_rng(seed)
-    a = rng.integers(-lim, lim + 1, size=(M, K)).astype(np.float32)
-    b = rng.integers(-lim, lim + 1, size=(N, K)).astype(np.float32)
+    n = lim // step
+    a = (rng.integers(-n, n + 1, size=(M, K)) * step).astype(np.float32)
+    b = (rng.integers(-n, n + 1, size=(N, K)) * step).astype(np.float32)
     return to_words(a, fmt), to_words(b, fmt)
 
 

@@ -8,7 +8,7 @@ from paper_2311_05782_amd import fi
 
 def make_plan(Aw, Bw, kb, fmt, cfg=None, group=None, **kw):
     M, K = Aw.shape
-    N = Bw.shape[0]
+    N = Bw.shape[1] if kw.get("b_layout", 0) == 1 else Bw.shape[0]
     d_A, d_B = fi.words_to_device(Aw), fi.words_to_device(Bw)
     desc = fi.plan_desc(M, N, K, kb, fmt, **kw)
     plan = fi.Plan(desc, d_A, d_B)

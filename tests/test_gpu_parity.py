@@ -23,26 +23,39 @@ def test_one_hip_runtime_and_native_library_loaded():
     assert any("libfi_gfx950.so" in ln for ln in maps.splitlines())
 
 
-def _mixed_faults(M, N, K, kb, n, seed):
-    """Accumulator, A, B and fault-free trials, with sites forced into tile corners and tails."""
+def _mixed_faults(Aw, Bw, fmt, kb, n, seed):
+    """Accumulator, A, B and fault-free trials for the exact regime, with sites forced into
+    tile corners and ragged tails.  Operands are even integers, so accumulators are 0 or at
+    least 4 in magnitude; accumulator bits 12..31 and operand masks that turn a word into
+    another small integer, 64 or Inf keep every partial sum exactly representable (or send
+    it so far up or down that every summation order rounds it the same way)."""
     rng = np.random.default_rng(seed)
+    (M, K), N = Aw.shape, Bw.shape[0]
     S = K // kb
+    targets = wl.to_words(np.array([0, 2, -2, 4, -4, 64, np.inf, -np.inf], np.float32), fmt)
+
+    def op_mask(word):
+        return int(word) ^ int(targets[rng.integers(len(targets))])
+
     rows = []
     for t in range(n):
         kind = [orc.SITE_ACC, orc.SITE_ACC, orc.SITE_A, orc.SITE_B, orc.SITE_NONE][t % 5]
         if kind == orc.SITE_ACC:
-            r = (kind, rng.integers(M), rng.integers(N), rng.integers(S), 1 << int(rng.integers(32)))
+            r = (kind, rng.integers(M), rng.integers(N), rng.integers(S), 1 << int(rng.integers(12, 32)))
         elif kind == orc.SITE_A:
-            r = (kind, rng.integers(M), rng.integers(K), 0, 1 << int(rng.integers(16)))
+            i, k = rng.integers(M), rng.integers(K)
+            r = (kind, i, k, 0, op_mask(Aw[i, k]))
         elif kind == orc.SITE_B:
-            r = (kind, rng.integers(K), rng.integers(N), 0, 1 << int(rng.integers(16)))
+            k, j = rng.integers(K), rng.integers(N)
+            r = (kind, k, j, 0, op_mask(Bw[j, k]))
         else:
             r = (kind, 0, 0, 0, 0)
         rows.append(r)
     # corners and last elements
     rows += [(orc.SITE_ACC, M - 1, N - 1, S - 1, 1 << 31), (orc.SITE_ACC, 0, 0, 0, 1 << 23),
-             (orc.SITE_ACC, M - 1, 0, S - 1, 0x00C00000), (orc.SITE_A, M - 1, K - 1, 0, 1 << 9),
-             (orc.SITE_B, K - 1, N - 1, 0, 1 << 14), (orc.SITE_A, 0, 0, 0, 0xF000)]
+             (orc.SITE_ACC, M - 1, 0, S - 1, 0x00C00000), (orc.SITE_ACC, 0, N - 1, 0, 1 << 30),
+             (orc.SITE_A, M - 1, K - 1, 0, 0x8000), (orc.SITE_B, K - 1, N - 1, 0, 0x8000),
+             (orc.SITE_A, 0, 0, 0, 0x18000 | op_mask(Aw[0, 0])), (orc.SITE_B, 0, 0, 0, op_mask(Bw[0, 0]))]
     return orc.make_faults(rows)
 
 
@@ -54,8 +67,8 @@ def test_exact_regime_everything_bit_equal(fmt, cfg, shape):
     # outputs, words, flags and counters must all be identical.  Shapes span several tiles and
     # ragged tails in M, N and K (K = 96 is not a multiple of the 64-wide k-tile).
     M, N, K, kb = shape
-    Aw, Bw = wl.small_integers(M, N, K, fmt, seed=M + N)
-    faults = _mixed_faults(M, N, K, kb, 24, seed=K + cfg)
+    Aw, Bw = wl.small_integers(M, N, K, fmt, seed=M + N, lim=4, step=2)
+    faults = _mixed_faults(Aw, Bw, fmt, kb, 25, seed=K + cfg)
     plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg, group=5)
     p = orc.problem(M, N, K, kb, fmt)
     gold = orc.gemm(p, Aw, Bw)
