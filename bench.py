@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Throughput of fault-injection campaigns on one MI355X.
+
+One step = one pass of the whole hot path over one batch of trials: every trial runs the
+complete GEMM with its fault, the fused detector / corrector / counters, then the batch is
+classified (fi_gemm_inject_batch + fi_classify).  Inputs, the fault list and the plan
+(fault-free result, magnitude maxima) are resident in HBM before the timed region; plan
+construction is timed separately and reported in `config`.
+
+Prints ONE JSON line.  `value` counts only flops the matrix cores executed: 2*M*N*K per
+trial, every trial recomputing the whole product.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16/BF16
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The CPU oracle as it stands, timed on a row slab of one fault-free pass of the same GEMM
+    (a trial of the oracle in `full` mode is exactly such a pass), scaled to the whole matrix."""
+    import numpy as np
+    from oracle import pyoracle as orc
+    cores = orc.threads()
+
+    def slab_time(rows):
+        p = orc.problem(rows, w.N, w.K, w.kb, w.fmt)
+        t0 = time.perf_counter()
+        orc.gemm(p, np.ascontiguousarray(w.A[:rows]), w.B)
+        return time.perf_counter() - t0
+
+    probe_rows = min(w.M, 4 * cores)
+    t_probe = slab_time(probe_rows)
+    rows = int(min(w.M, max(probe_rows, probe_rows * budget_s / max(t_probe, 1e-6))))
+    rows = max(cores, rows // cores * cores)
+    t = slab_time(rows) if rows > probe_rows else t_probe
+    flops = 2.0 * rows * w.N * w.K
+    t_trial = t * w.M / rows
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "trials_per_s": 1.0 / t_trial,
+            "sample": "rows 0..%d of one fault-free %dx%dx%d pass (%.1f s), scaled by M/%d to a whole trial"
+                      % (rows - 1, w.M, w.N, w.K, t, rows)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="square4096")
+    ap.add_argument("--trials", type=int, default=0, help="trials per batch (default: the workload's)")
+    ap.add_argument("--tile", type=int, default=-1)
+    ap.add_argument("--group", type=int, default=-1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: campaigns shard by trial with no exchange, and this build "
+              "runs on a single MI355X.  Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2311_05782_amd import fi, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs an MI355X; no device is visible.", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = wl.ALL[args.workload]()
+    n_trials = args.trials or w.n_trials
+    policy = w.policies[0]
+
+    d_A, d_B = fi.words_to_device(w.A), fi.words_to_device(w.B)
+    desc = fi.plan_desc(w.M, w.N, w.K, w.kb, w.fmt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plan = fi.Plan(desc, d_A, d_B)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    if args.tile >= 0 or args.group > 0:
+        plan.tune(args.tile, args.group if args.group > 0 else -1)
+    faults = fi.fi_sample_faults(w.fault_seed, 0, n_trials, desc, w.kind_mode, w.nbits)
+    d_f = fi.to_device(faults)
+    d_r = fi.empty_results(n_trials)
+    d_cls = torch.empty(n_trials, dtype=torch.uint8, device="cuda")
+    d_cnt = torch.empty(3, dtype=torch.int64, device="cuda")
+
+    def step():
+        plan.fi_gemm_inject_batch(d_f, n_trials, policy, d_r)
+        plan.fi_classify(d_r, n_trials, d_cls, d_cnt)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # HIP events on the launching stream bracket the GEMM kernel of every step.
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record()
+        plan.fi_gemm_inject_batch(d_f, n_trials, policy, d_r)
+        ev[k][1].record()
+        plan.fi_classify(d_r, n_trials, d_cls, d_cnt)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    kern_ms = [a.elapsed_time(b) for a, b in ev]
+    flops_per_launch = w.flops_per_trial * n_trials
+    ms_per_step = wall * 1e3 / args.steps
+    tflops = flops_per_launch * args.steps / wall / 1e12
+    achieved = flops_per_launch / (sum(kern_ms) / len(kern_ms) * 1e-3) / 1e12
+    counts = d_cnt.cpu().numpy().tolist()
+
+    out = {
+        "metric": "fault-injected GEMM throughput (every trial recomputes the whole GEMM)",
+        "value": round(tflops, 2), "unit": "TFLOP/s",
+        "trials_per_s": round(n_trials * args.steps / wall, 1),
+        "frac_of_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS, 4),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.fmt == wl.BF16 else "fp16", "data": "synthetic",
+        "config": {"workload": "%s: M=%d N=%d K=%d %s operands, FP32 accumulate, k-block %d, %d trials/batch, "
+                               "%d-bit faults (kind mode %d), fused detect + %s"
+                               % (w.name, w.M, w.N, w.K, "BF16" if w.fmt == wl.BF16 else "FP16", w.kb, n_trials,
+                                  w.nbits, w.kind_mode, {0: "no correction", 1: "zero-correct", 2: "recompute-correct"}[policy]),
+                   "trials_per_batch": n_trials, "plan_create_ms": round(plan_ms, 2),
+                   "outcomes_masked_sdc_detected": counts},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "gemm_fi_kernel", "kernel_ms_avg": round(sum(kern_ms) / len(kern_ms), 3),
+                     "kernel_ms_min": round(min(kern_ms), 3)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"]["value"] = float("%.4g" % out["cpu_baseline"]["value"])
+        out["cpu_baseline"]["trials_per_s"] = float("%.4g" % out["cpu_baseline"]["trials_per_s"])
+    plan.destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -130,6 +130,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   constexpr int STAGE = (BM + BN) * 128;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a multiple of the 32x32 MFMA");
   static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "every thread stages whole chunks");
+  static_assert(ROWS_PER_PASS % 16 == 0, "the slot permutation repeats every 16 rows");
   static_assert(2 * STAGE <= 160 * 1024, "two stages fit the 160 KB LDS");
 
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE];
@@ -146,7 +147,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
 
   // ---- this trial's fault, and what it means for this workgroup and wave (all uniform)
   uint32_t fkind = FI_SITE_NONE, frow = 0, fcol = 0, fmask = 0;
-  int hook_k = -1;          // k index (exclusive end) after which the owning wave flips its accumulator
+  int hook_kt = -1;         // owning wave: flip the accumulator after this k-tile
+  int kshift = 0;           // this workgroup's k-tiles start at -kshift (see below)
   int sel_t = 0, sel_v = 0, sel_lane = -1;
   bool affected = false;    // this tile can differ from the fault-free result
   int opfault_kt = -1;      // k-tile in which this workgroup stages a faulted operand word
@@ -168,59 +170,111 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
       fkind = FI_SITE_NONE;
     }
     if (fkind == FI_SITE_ACC) {
-      int li = (int)frow - m0, lj = (int)fcol - n0;
+      const int li = (int)frow - m0, lj = (int)fcol - n0;
       if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
         affected = true;
-        int wi = li - wm * WTM, wj = lj - wn * WTN;
+        // k-block s ends at k = (s+1)*kb, a multiple of 16 but not always of the 64-wide
+        // k-tile.  The workgroup that owns the site shifts its k-tiling down by kshift so that
+        // this boundary is the end of a k-tile: its first tile starts at k = -kshift with the
+        // part below 0 read as zeros.  The sequence of 16-wide MFMA steps over real data is
+        // unchanged (steps over zeros leave the +0 accumulators as they are), so every other
+        // element of the tile still equals the fault-free result bit for bit.
+        const int hook_k = ((int)f.kblock + 1) * p.kb;
+        kshift = (BK - hook_k % BK) % BK;
+        const int wi = li - wm * WTM, wj = lj - wn * WTN;
         if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
-          int ri = wi & 31, rj = wj & 31;
+          const int ri = wi & 31, rj = wj & 31;
           sel_t = (wi >> 5) * TN + (wj >> 5);
           sel_v = 4 * (ri >> 3) + (ri & 3);
           sel_lane = rj + 32 * ((ri >> 2) & 1);
-          hook_k = ((int)f.kblock + 1) * p.kb;
+          hook_kt = (hook_k + kshift) / BK - 1;
         }
       }
     } else if (fkind == FI_SITE_A) {
-      int li = (int)frow - m0;
-      if (li >= 0 && li < BM) { affected = true; opfault_kt = (int)fcol / BK; }
+      const int li = (int)frow - m0;
+      if (li >= 0 && li < BM) { affected = true; opfault_kt = (int)fcol / BK; }   // kshift is 0 here
     } else if (fkind == FI_SITE_B) {
-      int lj = (int)fcol - n0;
+      const int lj = (int)fcol - n0;
       if (lj >= 0 && lj < BN) { affected = true; opfault_kt = (int)frow / BK; }
     }
   }
 
-  // ---- staging maps
-  const int st_row = tid >> 3, st_ch = tid & 7;       // pass c adds c * ROWS_PER_PASS rows
+  // ---- staging maps.  Thread t stages chunk (t & 7) of rows (t >> 3) + c * ROWS_PER_PASS.
+  // Rows past the end of A or B are clamped to the last row: they feed only output rows /
+  // columns that are never stored or counted.  Chunks below k = 0 or past K must read as zero.
+  const int st_row = tid >> 3, st_ch = tid & 7;
+  const int st_soff = st_row * 128 + ((st_ch ^ lds_swizzle(st_row)) << 4);   // same slot every pass
   uint32_t a_goff[A_CH], b_goff[B_CH];                // element offsets of this thread's chunks at k = 0
-  bool a_ok[A_CH], b_ok[B_CH];
-  int a_soff[A_CH], b_soff[B_CH];                     // byte offsets inside a stage
 #pragma unroll
-  for (int c = 0; c < A_CH; ++c) {
-    int row = st_row + c * ROWS_PER_PASS;
-    a_ok[c] = (m0 + row) < p.M;
-    a_goff[c] = (uint32_t)(m0 + row) * p.lda + (uint32_t)(st_ch * 8);
-    a_soff[c] = row * 128 + ((st_ch ^ lds_swizzle(row)) << 4);
-  }
+  for (int c = 0; c < A_CH; ++c)
+    a_goff[c] = (uint32_t)min(m0 + st_row + c * ROWS_PER_PASS, p.M - 1) * p.lda + (uint32_t)(st_ch * 8);
 #pragma unroll
-  for (int c = 0; c < B_CH; ++c) {
-    int row = st_row + c * ROWS_PER_PASS;
-    b_ok[c] = (n0 + row) < p.N;
-    b_goff[c] = (uint32_t)(n0 + row) * p.ldb + (uint32_t)(st_ch * 8);
-    b_soff[c] = BM * 128 + row * 128 + ((st_ch ^ lds_swizzle(row)) << 4);
-  }
+  for (int c = 0; c < B_CH; ++c)
+    b_goff[c] = (uint32_t)min(n0 + st_row + c * ROWS_PER_PASS, p.N - 1) * p.ldb + (uint32_t)(st_ch * 8);
 
   u32x4 ga[A_CH], gb[B_CH];
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
   auto load_tile = [&](int kt) {
-    const int k0 = kt * BK;
-    const bool kin = (k0 + st_ch * 8) < p.K;
+    const int k0 = kt * BK - kshift;
+    if (k0 >= 0 && k0 + BK <= p.K) {   // uniform: every k-tile that lies inside [0, K)
 #pragma unroll
-    for (int c = 0; c < A_CH; ++c)
-      ga[c] = (a_ok[c] && kin) ? *reinterpret_cast<const u32x4*>(p.A + a_goff[c] + k0) : zero4;
+      for (int c = 0; c < A_CH; ++c) ga[c] = *reinterpret_cast<const u32x4*>(p.A + a_goff[c] + k0);
 #pragma unroll
-    for (int c = 0; c < B_CH; ++c)
-      gb[c] = (b_ok[c] && kin) ? *reinterpret_cast<const u32x4*>(p.B + b_goff[c] + k0) : zero4;
+      for (int c = 0; c < B_CH; ++c) gb[c] = *reinterpret_cast<const u32x4*>(p.B + b_goff[c] + k0);
+    } else {
+      const int kme = k0 + st_ch * 8;
+      const bool kin = kme >= 0 && kme < p.K;
+      const int kc = kin ? k0 : -st_ch * 8;
+      const uint32_t keep = kin ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+      for (int c = 0; c < A_CH; ++c) ga[c] = *reinterpret_cast<const u32x4*>(p.A + a_goff[c] + kc) & keep;
+#pragma unroll
+      for (int c = 0; c < B_CH; ++c) gb[c] = *reinterpret_cast<const u32x4*>(p.B + b_goff[c] + kc) & keep;
+    }
+  };
+
+  // Operand fault (rare, uniform): the thread holding the faulted 16-bit word XORs it in its
+  // staging registers; one thread of one workgroup reports the word.
+  auto operand_fault = [&](int kt) {
+    const int kk = (fkind == FI_SITE_A ? (int)fcol : (int)frow) - kt * BK;   // 0..63
+    const int want_row = (fkind == FI_SITE_A) ? (int)frow - m0 : (int)fcol - n0;
+    const int sh = (kk & 1) * 16, dw = (kk & 7) >> 1;
+    const uint32_t m16 = (fmask & 0xFFFFu) << sh;
+    const bool my_chunk = st_ch == (kk >> 3);
+    uint32_t before = 0;
+    bool mine = false;
+    if (fkind == FI_SITE_A) {
+#pragma unroll
+      for (int c = 0; c < A_CH; ++c) {
+        const bool hit = my_chunk && (st_row + c * ROWS_PER_PASS == want_row);
+        mine = mine || hit;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const bool h = hit && d == dw;
+          before = h ? ga[c][d] : before;
+          ga[c][d] ^= h ? m16 : 0u;
+        }
+      }
+      mine = mine && tile_n == 0;
+    } else {
+#pragma unroll
+      for (int c = 0; c < B_CH; ++c) {
+        const bool hit = my_chunk && (st_row + c * ROWS_PER_PASS == want_row);
+        mine = mine || hit;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const bool h = hit && d == dw;
+          before = h ? gb[c][d] : before;
+          gb[c][d] ^= h ? m16 : 0u;
+        }
+      }
+      mine = mine && tile_m == 0;
+    }
+    if (mine) {
+      before = (before >> sh) & 0xFFFFu;
+      p.results[trial].site_word_before = before;
+      p.results[trial].site_word_after = before ^ (fmask & 0xFFFFu);
+    }
   };
 
   auto store_tile = [&](int kt, int stage) {
@@ -230,52 +284,19 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
 #pragma unroll
       for (int c = 0; c < B_CH; ++c) gb[c] &= p.operand_and;
     } else {
-      if (kt == opfault_kt) {   // uniform, at most one k-tile of a few workgroups per trial
-        const int kk = (fkind == FI_SITE_A ? (int)fcol : (int)frow) - kt * BK;   // 0..63
-        const int want_row = (fkind == FI_SITE_A) ? (int)frow - m0 : (int)fcol - n0;
-        const uint32_t m16 = (fmask & 0xFFFFu) << ((kk & 1) * 16);
-        if (st_ch == (kk >> 3)) {
-          const int dw = (kk & 7) >> 1;
-          if (fkind == FI_SITE_A) {
-#pragma unroll
-            for (int c = 0; c < A_CH; ++c) {
-              if (st_row + c * ROWS_PER_PASS == want_row) {
-                uint32_t before = (ga[c][dw] >> ((kk & 1) * 16)) & 0xFFFFu;
-                ga[c][dw] ^= m16;
-                if (tile_n == 0) {
-                  p.results[trial].site_word_before = before;
-                  p.results[trial].site_word_after = before ^ (fmask & 0xFFFFu);
-                }
-              }
-            }
-          } else {
-#pragma unroll
-            for (int c = 0; c < B_CH; ++c) {
-              if (st_row + c * ROWS_PER_PASS == want_row) {
-                uint32_t before = (gb[c][dw] >> ((kk & 1) * 16)) & 0xFFFFu;
-                gb[c][dw] ^= m16;
-                if (tile_m == 0) {
-                  p.results[trial].site_word_before = before;
-                  p.results[trial].site_word_after = before ^ (fmask & 0xFFFFu);
-                }
-              }
-            }
-          }
-        }
-      }
+      if (kt == opfault_kt) operand_fault(kt);
     }
-    uint8_t* s = smem + stage * STAGE;
+    uint8_t* s = smem + stage * STAGE + st_soff;
 #pragma unroll
-    for (int c = 0; c < A_CH; ++c) *reinterpret_cast<u32x4*>(s + a_soff[c]) = ga[c];
+    for (int c = 0; c < A_CH; ++c)
+      *reinterpret_cast<u32x4*>(s + c * ROWS_PER_PASS * 128) = ga[c];
 #pragma unroll
-    for (int c = 0; c < B_CH; ++c) *reinterpret_cast<u32x4*>(s + b_soff[c]) = gb[c];
+    for (int c = 0; c < B_CH; ++c)
+      *reinterpret_cast<u32x4*>(s + BM * 128 + c * ROWS_PER_PASS * 128) = gb[c];
   };
 
   // ---- fragment read maps: row = wave base + 32*t + l32, chunk = 2*kk + lhi
   const int sw = lds_swizzle(l32);
-  int slot[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) slot[kk] = ((2 * kk + lhi) ^ sw) << 4;
   const int a_rd = (wm * WTM + l32) * 128;
   const int b_rd = BM * 128 + (wn * WTN + l32) * 128;
 
@@ -287,7 +308,41 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const int nkt = (p.K + BK - 1) / BK;
+  // One 16-wide k-step of the wave tile: TM + TN ds_read_b128, TM x TN MFMAs.
+  auto k16_step = [&](const uint8_t* s, int kk) {
+    const int slot = ((2 * kk + lhi) ^ sw) << 4;
+    u32x4 af[TM], bf[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const u32x4*>(s + a_rd + i * 4096 + slot);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const u32x4*>(s + b_rd + j * 4096 + slot);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = mfma_32x32x16<DT>(af[i], bf[j], acc[i][j]);
+  };
+
+  // Accumulator fault: XOR the owning lane's register.  Which 32x32 tile is a uniform choice
+  // among TM*TN static ones; the register inside the tile's 16 is picked by a dynamic vector
+  // index, which stays in registers for a 16-element vector.
+  auto accumulator_fault = [&]() {
+    const uint32_t lane_mask = (lane == sel_lane) ? fmask : 0u;
+    uint32_t before = 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        if (i * TN + j == sel_t) {
+          before = __float_as_uint(acc[i][j][sel_v]);
+          acc[i][j][sel_v] = __uint_as_float(before ^ lane_mask);
+        }
+    if (lane == sel_lane) {
+      p.results[trial].site_word_before = before;
+      p.results[trial].site_word_after = before ^ fmask;
+    }
+  };
+
+  const int nkt = (p.K + kshift + BK - 1) / BK;
   load_tile(0);
   store_tile(0, 0);
   __syncthreads();
@@ -297,131 +352,125 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     if (kt + 1 < nkt) load_tile(kt + 1);
     const uint8_t* s = smem + stage * STAGE;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      u32x4 af[TM], bf[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const u32x4*>(s + a_rd + i * 4096 + slot[kk]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bf[j] = *reinterpret_cast<const u32x4*>(s + b_rd + j * 4096 + slot[kk]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = mfma_32x32x16<DT>(af[i], bf[j], acc[i][j]);
-
-      if constexpr (MODE == MODE_CAMPAIGN) {
-        // Accumulator fault: k-block s ends at k = (s+1)*kb; kb is a multiple of 16, so
-        // that boundary is the end of one of these 16-wide steps.  Taken by one wave of
-        // one workgroup per trial.
-        if (hook_k == kt * BK + (kk + 1) * 16) {
-#pragma unroll
-          for (int t = 0; t < TM * TN; ++t) {
-            if (t == sel_t) {
-#pragma unroll
-              for (int v = 0; v < 16; ++v) {
-                uint32_t w = __float_as_uint(acc[t / TN][t % TN][v]);
-                if (v == sel_v && lane == sel_lane) {
-                  p.results[trial].site_word_before = w;
-                  w ^= fmask;
-                  p.results[trial].site_word_after = w;
-                }
-                acc[t / TN][t % TN][v] = __uint_as_float(w);
-              }
-            }
-          }
-        }
-      }
+    for (int kk = 0; kk < 4; ++kk) k16_step(s, kk);
+    if constexpr (MODE == MODE_CAMPAIGN) {
+      if (kt == hook_kt) accumulator_fault();   // one wave of one workgroup per trial
     }
     if (kt + 1 < nkt) store_tile(kt + 1, stage ^ 1);
     __syncthreads();
   }
 
-  // ---- epilogue: detector, corrector, counters
-  const float inf = __uint_as_float(0x7F800000u);
-  uint32_t n_flag = 0, n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
-  float mx_pre = 0.0f, mx_post = 0.0f;
-  float* cout = nullptr;
-  if (p.c_out) {
-    cout = p.c_out + (MODE == MODE_CAMPAIGN ? (size_t)trial * (size_t)p.M * (size_t)p.N : (size_t)0);
-  }
-
+  // ---- epilogue 1: detector, corrector, optional store (every tile of every trial)
+  const int row_base = m0 + wm * WTM + 4 * lhi;       // + 32*i + 8*q + e
+  const int col_base = n0 + wn * WTN + l32;           // + 32*j
+  if constexpr (MODE == MODE_GOLDEN) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r0 = m0 + wm * WTM + i * 32 + 8 * q + 4 * lhi;     // rows r0 .. r0+3
-      f32x4 kra4 = {0.f, 0.f, 0.f, 0.f};
-      if constexpr (MODE == MODE_CAMPAIGN) kra4 = *reinterpret_cast<const f32x4*>(p.kra + r0);
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * WTN + j * 32 + l32;
-        float cbj = 0.f;
-        if constexpr (MODE == MODE_CAMPAIGN) cbj = p.cb[col];
+        for (int v = 0; v < 16; ++v) {
+          const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3), col = col_base + 32 * j;
+          if (row < p.M && col < p.N) p.c_out[(size_t)row * p.N + col] = acc[i][j][v];
+        }
+    return;
+  } else {
+    uint32_t n_flag = 0;
+    float* cout = p.c_out ? p.c_out + (size_t)trial * (size_t)p.M * (size_t)p.N : nullptr;
+    float cbj[TN];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int row = r0 + e;
-          const bool inb = row < p.M && col < p.N;
-          float c = acc[i][j][4 * q + e];
-          if constexpr (MODE == MODE_GOLDEN) {
-            if (inb) cout[(size_t)row * p.N + col] = c;
-          } else {
-            float T = p.bound_global ? p.t_global
-                                     : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
+    for (int j = 0; j < TN; ++j) cbj[j] = p.cb[col_base + 32 * j];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r0 = row_base + 32 * i + 8 * q;
+        const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + r0);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int col = col_base + 32 * j;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int row = r0 + e;
+            const float c = acc[i][j][4 * q + e];
+            const float T = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj[j]), p.gamma);
+            const bool inb = row < p.M && col < p.N;
             const bool flag = inb && !(fabsf(c) <= T);
             n_flag += flag ? 1u : 0u;
-            float cc = c;
-            if (flag) {
-              if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
-              else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
-            }
-            if (affected && inb) {
-              const size_t idx = (size_t)row * p.N + col;
-              const float cs = p.c_star[idx];
-              const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
-              const float dpre = finite_or_inf(fabsf(c - cs));
-              const float dpost = finite_or_inf(fabsf(cc - cs));
-              const bool changed = __float_as_uint(c) != __float_as_uint(cs);
-              n_bit += changed ? 1u : 0u;
-              n_pre += !(dpre <= tau) ? 1u : 0u;
-              n_post += !(dpost <= tau) ? 1u : 0u;
-              mx_pre = fmaxf(mx_pre, dpre);
-              mx_post = fmaxf(mx_post, dpost);
-              if (changed) {
-                const float band = fmaxf(2.0f * tau, T * 0.015625f);
-                const float mag = fabsf(c);
-                n_bT += (mag <= 3.4028234e38f && fabsf(mag - T) <= band) ? 1u : 0u;
-                n_btau += (tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
+            if (cout) {
+              float cc = c;
+              if (flag) {
+                if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+                else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
               }
+              if (inb) cout[(size_t)row * p.N + col] = cc;
             }
-            if (cout && inb) cout[(size_t)row * p.N + col] = cc;
           }
         }
       }
     }
-  }
-
-  if constexpr (MODE == MODE_CAMPAIGN) {
     fi_trial_result* r = p.results + trial;
     if (__ballot(n_flag != 0)) {
-      uint32_t s = wave_sum(n_flag);
-      if (lane == 0) atomicAdd(&r->n_flagged, s);
+      const uint32_t sum = wave_sum(n_flag);
+      if (lane == 0) atomicAdd(&r->n_flagged, sum);
     }
+
+    // ---- epilogue 2: deviation from the fault-free result, only where a fault can reach
     if (affected) {
-      uint32_t s;
-      s = wave_sum(n_bit);  if (lane == 0 && s) atomicAdd(&r->n_bitdiff, s);
-      s = wave_sum(n_pre);  if (lane == 0 && s) atomicAdd(&r->n_dev_pre, s);
-      s = wave_sum(n_post); if (lane == 0 && s) atomicAdd(&r->n_dev_post, s);
-      s = wave_sum(n_bT);   if (lane == 0 && s) atomicAdd(&r->n_border_T, s);
-      s = wave_sum(n_btau); if (lane == 0 && s) atomicAdd(&r->n_border_tau, s);
+      uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
+      float mx_pre = 0.0f, mx_post = 0.0f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int r0 = row_base + 32 * i + 8 * q;
+          const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + r0);
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int col = col_base + 32 * j;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int row = r0 + e;
+              if (row < p.M && col < p.N) {
+                const float c = acc[i][j][4 * q + e];
+                const float T = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj[j]), p.gamma);
+                const size_t idx = (size_t)row * p.N + col;
+                const float cs = p.c_star[idx];
+                const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
+                const bool flag = !(fabsf(c) <= T);
+                float cc = c;
+                if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+                if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
+                const float dpre = finite_or_inf(fabsf(c - cs));
+                const float dpost = finite_or_inf(fabsf(cc - cs));
+                const bool changed = __float_as_uint(c) != __float_as_uint(cs);
+                n_bit += changed ? 1u : 0u;
+                n_pre += !(dpre <= tau) ? 1u : 0u;
+                n_post += !(dpost <= tau) ? 1u : 0u;
+                mx_pre = fmaxf(mx_pre, dpre);
+                mx_post = fmaxf(mx_post, dpost);
+                const float band = fmaxf(2.0f * tau, T * 0.015625f);
+                const float mag = fabsf(c);
+                n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - T) <= band) ? 1u : 0u;
+                n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
+              }
+            }
+          }
+        }
+      }
+      uint32_t sum;
+      sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&r->n_bitdiff, sum);
+      sum = wave_sum(n_pre);  if (lane == 0 && sum) atomicAdd(&r->n_dev_pre, sum);
+      sum = wave_sum(n_post); if (lane == 0 && sum) atomicAdd(&r->n_dev_post, sum);
+      sum = wave_sum(n_bT);   if (lane == 0 && sum) atomicAdd(&r->n_border_T, sum);
+      sum = wave_sum(n_btau); if (lane == 0 && sum) atomicAdd(&r->n_border_tau, sum);
       // non-negative floats (and +Inf) order like their words
-      s = wave_max(__float_as_uint(mx_pre));
-      if (lane == 0 && s) atomicMax(reinterpret_cast<uint32_t*>(&r->max_dev_pre), s);
-      s = wave_max(__float_as_uint(mx_post));
-      if (lane == 0 && s) atomicMax(reinterpret_cast<uint32_t*>(&r->max_dev_post), s);
+      sum = wave_max(__float_as_uint(mx_pre));
+      if (lane == 0 && sum) atomicMax(reinterpret_cast<uint32_t*>(&r->max_dev_pre), sum);
+      sum = wave_max(__float_as_uint(mx_post));
+      if (lane == 0 && sum) atomicMax(reinterpret_cast<uint32_t*>(&r->max_dev_post), sum);
     }
   }
-  (void)inf;
 }
 
 }  // namespace fi
