@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--group", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference row for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: campaigns shard by trial with no exchange, and this build "
@@ -94,6 +96,13 @@ def main():
     def step():
         plan.fi_gemm_inject_batch(d_f, n_trials, policy, d_r)
         plan.fi_classify(d_r, n_trials, d_cls, d_cnt)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)           # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
