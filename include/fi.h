@@ -128,7 +128,8 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
 /* Optional tuning.  tile_config: -1 keep, else index of a workgroup-tile shape
  * (0: 256x256, 1: 128x128, 2: 256x64); trial_group: -1 keep, else how many
  * trials of the same output tile are scheduled next to each other.  Results
- * do not depend on either; C* is recomputed on `stream` when the tile changes. */
+ * do not depend on either (every tile shape accumulates each element in the
+ * same order); `stream` is unused. */
 fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, void* stream);
 
 /* Run n_trials faulty executions of the whole GEMM in one launch, each with

@@ -88,6 +88,22 @@ __global__ void __launch_bounds__(1024) max_reduce_kernel(const float* __restric
   }
 }
 
+// out = |in| for FP16/BF16 words (clear the sign bits), 8 words per thread; `in` has rows of
+// ld_in elements of which the first K are copied, `out` is packed [rows][K].  Used once per plan
+// to build the operands of the magnitude-sum GEMM behind the tolerance.
+__global__ void __launch_bounds__(256) abs16_kernel(const uint16_t* __restrict__ in, uint32_t ld_in,
+                                                   uint16_t* __restrict__ out, int rows, int K) {
+  const size_t per_row = (size_t)K / 8, total = per_row * (size_t)rows;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t step = (size_t)gridDim.x * 256;
+  for (; i < total; i += step) {
+    const size_t r = i / per_row, c = i % per_row;
+    u32x4_t v = *reinterpret_cast<const u32x4_t*>(in + r * ld_in + c * 8);
+    v &= 0x7FFF7FFFu;
+    *reinterpret_cast<u32x4_t*>(out + r * (size_t)K + c * 8) = v;
+  }
+}
+
 // [K][N] -> [N][K] for 16-bit words.
 __global__ void __launch_bounds__(256) transpose16_kernel(const uint16_t* __restrict__ in, uint32_t ld_in,
                                                          uint16_t* __restrict__ out, uint32_t ld_out,

@@ -104,18 +104,19 @@ GemmArgs base_args(const fi_plan* p) {
   a.bound_global = p->d.bound_mode == FI_BOUND_GLOBAL;
   a.t_global = p->t_global;
   a.c_star = p->c_star; a.s_abs = p->s_abs;
-  a.operand_and = 0xFFFFFFFFu;
   return a;
 }
 
-// C* and the magnitude sums, with the same kernel family the campaign uses.
-fi_status compute_golden(fi_plan* p, hipStream_t s) {
+// C* with the same kernel family the campaign uses (so that a fault-free tile of a trial is
+// bit-identical to it), and S = |A| x |B| on sign-cleared copies of the operands.
+fi_status compute_golden(fi_plan* p, hipStream_t s, const uint16_t* absA, const uint16_t* absB) {
   GemmArgs a = base_args(p);
   a.n_trials = 1; a.group = 1;
   a.c_out = p->c_star;
   FI_HIP(launch_gemm<fi::MODE_GOLDEN>((int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
+  a.A = absA; a.B = absB;
+  a.lda = a.ldb = (uint32_t)p->d.K;     // the copies are packed
   a.c_out = p->s_abs;
-  a.operand_and = 0x7FFF7FFFu;
   FI_HIP(launch_gemm<fi::MODE_GOLDEN>((int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
   return FI_OK;
 }
@@ -214,8 +215,24 @@ fi_status build_plan(fi_plan* p, const void* d_A, const void* d_B, hipStream_t s
   hipLaunchKernelGGL(fi::max_reduce_kernel, dim3(1), dim3(1024), 0, s, p->kra, (int)d.M, p->scratch + 0);
   hipLaunchKernelGGL(fi::max_reduce_kernel, dim3(1), dim3(1024), 0, s, p->cb, (int)d.N, p->scratch + 1);
   FI_HIP(hipGetLastError());
-  fi_status st = compute_golden(p, s);
+  // sign-cleared operand copies for the magnitude-sum GEMM; freed once the stream has drained
+  uint16_t *absA = nullptr, *absB = nullptr;
+  const size_t nA = (size_t)d.M * d.K, nB = (size_t)d.N * d.K;
+  hipError_t e1 = hipMalloc(&absA, nA * sizeof(uint16_t));
+  hipError_t e2 = hipMalloc(&absB, nB * sizeof(uint16_t));
+  fi_status st = FI_OK;
+  if (e1 != hipSuccess || e2 != hipSuccess) {
+    st = fail(FI_OOM, "device allocation for the magnitude operands failed");
+  } else {
+    hipLaunchKernelGGL(fi::abs16_kernel, dim3(2048), dim3(256), 0, s, p->A, (uint32_t)d.lda, absA, (int)d.M, (int)d.K);
+    hipLaunchKernelGGL(fi::abs16_kernel, dim3(2048), dim3(256), 0, s, p->B, p->ldb, absB, (int)d.N, (int)d.K);
+    st = compute_golden(p, s, absA, absB);
+  }
+  hipError_t es = hipStreamSynchronize(s);
+  if (absA) (void)hipFree(absA);
+  if (absB) (void)hipFree(absB);
   if (st != FI_OK) return st;
+  if (es != hipSuccess) return fail(FI_DEVICE, "plan kernels failed: %s", hipGetErrorString(es));
   float host[8];
   FI_HIP(hipMemcpyAsync(host, p->scratch, sizeof(host), hipMemcpyDeviceToHost, s));
   FI_HIP(hipStreamSynchronize(s));
@@ -316,10 +333,10 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
   if (tile_config >= kNumCfg) return fail(FI_INVALID_ARG, "tile_config must be < %d", kNumCfg);
   if (trial_group == 0 || trial_group > 4096) return fail(FI_INVALID_ARG, "trial_group must be in 1..4096");
   if (trial_group > 0) plan->group = trial_group;
-  if (tile_config >= 0 && tile_config != plan->cfg) {
-    plan->cfg = tile_config;
-    return compute_golden(plan, as_stream(stream));
-  }
+  // C* does not depend on the tile shape: every shape feeds each output element the same
+  // sequence of 16-wide MFMA steps in ascending k.
+  if (tile_config >= 0) plan->cfg = tile_config;
+  (void)stream;
   return FI_OK;
 }
 

@@ -14,10 +14,10 @@
 // the caller asks for the outputs.
 //
 // Data movement: A is [M][K], B is [N][K], both K-contiguous.  A k-tile of 64
-// elements is 128 bytes per row = eight 16-byte chunks.  Chunks are staged
-// global -> VGPR -> LDS; chunk c of row r lands in slot c ^ g(r) of its row so
-// that the ds_read_b128 of 8 (and of 16) consecutive rows touches distinct
-// banks.  LDS is double buffered: one barrier per k-tile.
+// elements is 128 bytes per row = eight 16-byte chunks.  Chunks go global -> LDS
+// directly (global_load_lds, no staging registers); chunk c of row r lands in
+// slot c ^ g(r) of its row so that the ds_read_b128 of 8 (and of 16) consecutive
+// rows touches distinct banks.  LDS is double buffered: one barrier per k-tile.
 //
 // MFMA: v_mfma_f32_32x32x16_{f16,bf16}.  Lane l feeds row (l % 32) of the A
 // fragment and column (l % 32) of the B fragment with the 8 consecutive k
@@ -27,6 +27,9 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
+#include <utility>
 
 #include "fi.h"
 
@@ -58,7 +61,6 @@ struct GemmArgs {
   const float* s_abs;       // [M][N] sum_k |a b|        (campaign)
   float* c_out;             // campaign: nullable [n_trials][M][N]; golden: [M][N]
   int policy;
-  uint32_t operand_and;     // golden: AND mask on every staged dword (0x7FFF7FFF = magnitudes)
 };
 
 template <int DT>
@@ -70,6 +72,17 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
                                                   __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
   }
+}
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Keeps every
+// accumulator index a constant from the front end on, whatever the optimiser's unrolling does.
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
 }
 
 // Slot permutation of the eight 16-byte chunks of a 128-byte LDS row.
@@ -125,12 +138,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   constexpr int NT = WM * WN * 64;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;
-  constexpr int ROWS_PER_PASS = NT / 8;
   constexpr int STAGE = (BM + BN) * 128;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a multiple of the 32x32 MFMA");
-  static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0, "every thread stages whole chunks");
-  static_assert(ROWS_PER_PASS % 16 == 0, "the slot permutation repeats every 16 rows");
   static_assert(2 * STAGE <= 160 * 1024, "two stages fit the 160 KB LDS");
 
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE];
@@ -199,100 +208,102 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     }
   }
 
-  // ---- staging maps.  Thread t stages chunk (t & 7) of rows (t >> 3) + c * ROWS_PER_PASS.
-  // Rows past the end of A or B are clamped to the last row: they feed only output rows /
-  // columns that are never stored or counted.  Chunks below k = 0 or past K must read as zero.
-  const int st_row = tid >> 3, st_ch = tid & 7;
-  const int st_soff = st_row * 128 + ((st_ch ^ lds_swizzle(st_row)) << 4);   // same slot every pass
-  uint32_t a_goff[A_CH], b_goff[B_CH];                // element offsets of this thread's chunks at k = 0
+  // ---- staging: global -> LDS without passing through registers.  One global_load_lds of 16
+  // bytes per lane fills 1024 contiguous LDS bytes = 8 rows x 8 slots: lane l lands in row
+  // (l >> 3), slot (l & 7) of its row group, so it must FETCH chunk slot ^ g(row).  Wave w issues
+  // the row groups w*A_CH .. of the A tile and w*B_CH .. of the B tile.  Rows past the end of A
+  // or B are clamped to the last row (they feed only outputs that are never stored or counted).
+  constexpr int NW = WM * WN;
+  constexpr int A_G = BM / 8 / NW, B_G = BN / 8 / NW;      // row groups per wave
+  static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "row groups divide among the waves");
+  const int lrow = lane >> 3, lslot = lane & 7;
+  uint32_t a_goff[A_G], b_goff[B_G];                  // element offsets of this lane's chunks at k = 0
 #pragma unroll
-  for (int c = 0; c < A_CH; ++c)
-    a_goff[c] = (uint32_t)min(m0 + st_row + c * ROWS_PER_PASS, p.M - 1) * p.lda + (uint32_t)(st_ch * 8);
+  for (int c = 0; c < A_G; ++c) {
+    const int row = (wave * A_G + c) * 8 + lrow;
+    a_goff[c] = (uint32_t)min(m0 + row, p.M - 1) * p.lda + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
+  }
 #pragma unroll
-  for (int c = 0; c < B_CH; ++c)
-    b_goff[c] = (uint32_t)min(n0 + st_row + c * ROWS_PER_PASS, p.N - 1) * p.ldb + (uint32_t)(st_ch * 8);
+  for (int c = 0; c < B_G; ++c) {
+    const int row = (wave * B_G + c) * 8 + lrow;
+    b_goff[c] = (uint32_t)min(n0 + row, p.N - 1) * p.ldb + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
+  }
 
-  u32x4 ga[A_CH], gb[B_CH];
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef const __attribute__((address_space(1))) void glb_void;
 
-  auto load_tile = [&](int kt) {
+  // Issue the loads of k-tile kt into `stage`.  Returns false if the tile is not wholly inside
+  // [0, K): then fix_tile() must zero what lies outside once the loads have landed.
+  auto issue_tile = [&](int kt, int stage) {
     const int k0 = kt * BK - kshift;
-    if (k0 >= 0 && k0 + BK <= p.K) {   // uniform: every k-tile that lies inside [0, K)
+    const bool inside = k0 >= 0 && k0 + BK <= p.K;       // uniform
+    uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
+    uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
+    if (inside) {
 #pragma unroll
-      for (int c = 0; c < A_CH; ++c) ga[c] = *reinterpret_cast<const u32x4*>(p.A + a_goff[c] + k0);
+      for (int c = 0; c < A_G; ++c)
+        __builtin_amdgcn_global_load_lds((glb_void*)(p.A + a_goff[c] + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
 #pragma unroll
-      for (int c = 0; c < B_CH; ++c) gb[c] = *reinterpret_cast<const u32x4*>(p.B + b_goff[c] + k0);
+      for (int c = 0; c < B_G; ++c)
+        __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
     } else {
-      const int kme = k0 + st_ch * 8;
-      const bool kin = kme >= 0 && kme < p.K;
-      const int kc = kin ? k0 : -st_ch * 8;
-      const uint32_t keep = kin ? 0xFFFFFFFFu : 0u;
+      // chunks outside [0, K) are fetched from k = chunk offset (always valid) and zeroed later
 #pragma unroll
-      for (int c = 0; c < A_CH; ++c) ga[c] = *reinterpret_cast<const u32x4*>(p.A + a_goff[c] + kc) & keep;
+      for (int c = 0; c < A_G; ++c) {
+        const int ch = (lslot ^ lds_swizzle((wave * A_G + c) * 8 + lrow)) * 8;
+        const bool kin = (k0 + ch) >= 0 && (k0 + ch) < p.K;
+        __builtin_amdgcn_global_load_lds((glb_void*)(p.A + a_goff[c] + (kin ? k0 : 0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
+      }
 #pragma unroll
-      for (int c = 0; c < B_CH; ++c) gb[c] = *reinterpret_cast<const u32x4*>(p.B + b_goff[c] + kc) & keep;
+      for (int c = 0; c < B_G; ++c) {
+        const int ch = (lslot ^ lds_swizzle((wave * B_G + c) * 8 + lrow)) * 8;
+        const bool kin = (k0 + ch) >= 0 && (k0 + ch) < p.K;
+        __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + (kin ? k0 : 0)), (lds_void*)(sB + c * 1024), 16, 0, 0);
+      }
     }
   };
 
-  // Operand fault (rare, uniform): the thread holding the faulted 16-bit word XORs it in its
-  // staging registers; one thread of one workgroup reports the word.
-  auto operand_fault = [&](int kt) {
-    const int kk = (fkind == FI_SITE_A ? (int)fcol : (int)frow) - kt * BK;   // 0..63
-    const int want_row = (fkind == FI_SITE_A) ? (int)frow - m0 : (int)fcol - n0;
-    const int sh = (kk & 1) * 16, dw = (kk & 7) >> 1;
-    const uint32_t m16 = (fmask & 0xFFFFu) << sh;
-    const bool my_chunk = st_ch == (kk >> 3);
-    uint32_t before = 0;
-    bool mine = false;
-    if (fkind == FI_SITE_A) {
+  // After the loads of k-tile kt have landed (and before the barrier that publishes them): zero
+  // the chunks outside [0, K) and apply an operand fault.  Each lane touches only the 16 bytes it
+  // fetched itself.  Both cases are rare and uniform.
+  auto fix_tile = [&](int kt, int stage) {
+    const int k0 = kt * BK - kshift;
+    uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024) + lane * 16;
+    uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024) + lane * 16;
+    if (!(k0 >= 0 && k0 + BK <= p.K)) {
+      const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
-      for (int c = 0; c < A_CH; ++c) {
-        const bool hit = my_chunk && (st_row + c * ROWS_PER_PASS == want_row);
-        mine = mine || hit;
+      for (int c = 0; c < A_G; ++c) {
+        const int ch = (lslot ^ lds_swizzle((wave * A_G + c) * 8 + lrow)) * 8;
+        if (!((k0 + ch) >= 0 && (k0 + ch) < p.K)) *reinterpret_cast<u32x4*>(sA + c * 1024) = zero4;
+      }
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const bool h = hit && d == dw;
-          before = h ? ga[c][d] : before;
-          ga[c][d] ^= h ? m16 : 0u;
+      for (int c = 0; c < B_G; ++c) {
+        const int ch = (lslot ^ lds_swizzle((wave * B_G + c) * 8 + lrow)) * 8;
+        if (!((k0 + ch) >= 0 && (k0 + ch) < p.K)) *reinterpret_cast<u32x4*>(sB + c * 1024) = zero4;
+      }
+    }
+    if constexpr (MODE == MODE_CAMPAIGN) {
+      if (kt == opfault_kt) {
+        const bool isA = fkind == FI_SITE_A;
+        const int kk = (isA ? (int)fcol : (int)frow) - kt * BK;            // 0..63 (kshift is 0 here)
+        const int want_row = isA ? (int)frow - m0 : (int)fcol - n0;        // row inside the tile
+        const int groups = isA ? A_G : B_G;
+        const int g = want_row >> 3;                                       // row group inside the tile
+        // the lane that fetched chunk (kk >> 3) of that row
+        const int want_lane = ((want_row & 7) << 3) | ((kk >> 3) ^ lds_swizzle(want_row));
+        if (g / groups == wave && lane == want_lane) {
+          uint8_t* base = (isA ? sA : sB) + (g % groups) * 1024;
+          uint16_t* w16 = reinterpret_cast<uint16_t*>(base) + (kk & 7);
+          const uint32_t before = *w16;
+          *w16 = (uint16_t)(before ^ (fmask & 0xFFFFu));
+          if (isA ? tile_n == 0 : tile_m == 0) {
+            p.results[trial].site_word_before = before;
+            p.results[trial].site_word_after = before ^ (fmask & 0xFFFFu);
+          }
         }
       }
-      mine = mine && tile_n == 0;
-    } else {
-#pragma unroll
-      for (int c = 0; c < B_CH; ++c) {
-        const bool hit = my_chunk && (st_row + c * ROWS_PER_PASS == want_row);
-        mine = mine || hit;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const bool h = hit && d == dw;
-          before = h ? gb[c][d] : before;
-          gb[c][d] ^= h ? m16 : 0u;
-        }
-      }
-      mine = mine && tile_m == 0;
     }
-    if (mine) {
-      before = (before >> sh) & 0xFFFFu;
-      p.results[trial].site_word_before = before;
-      p.results[trial].site_word_after = before ^ (fmask & 0xFFFFu);
-    }
-  };
-
-  auto store_tile = [&](int kt, int stage) {
-    if constexpr (MODE == MODE_GOLDEN) {
-#pragma unroll
-      for (int c = 0; c < A_CH; ++c) ga[c] &= p.operand_and;
-#pragma unroll
-      for (int c = 0; c < B_CH; ++c) gb[c] &= p.operand_and;
-    } else {
-      if (kt == opfault_kt) operand_fault(kt);
-    }
-    uint8_t* s = smem + stage * STAGE + st_soff;
-#pragma unroll
-    for (int c = 0; c < A_CH; ++c)
-      *reinterpret_cast<u32x4*>(s + c * ROWS_PER_PASS * 128) = ga[c];
-#pragma unroll
-    for (int c = 0; c < B_CH; ++c)
-      *reinterpret_cast<u32x4*>(s + BM * 128 + c * ROWS_PER_PASS * 128) = gb[c];
   };
 
   // ---- fragment read maps: row = wave base + 32*t + l32, chunk = 2*kk + lhi
@@ -301,25 +312,25 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   const int b_rd = BM * 128 + (wn * WTN + l32) * 128;
 
   f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+  static_for<TM * TN>([&](auto t) {
+    acc[t / TN][t % TN] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  });
 
-  // One 16-wide k-step of the wave tile: TM + TN ds_read_b128, TM x TN MFMAs.
-  auto k16_step = [&](const uint8_t* s, int kk) {
+  // Fragments of one 16-wide k-step: TM + TN ds_read_b128.  Two sets, so the reads of step
+  // kk + 1 are in flight while the TM x TN MFMAs of step kk run.
+  struct Frags { u32x4 a[TM]; u32x4 b[TN]; };
+  auto read_frags = [&](Frags& f, const uint8_t* s, int kk) {
     const int slot = ((2 * kk + lhi) ^ sw) << 4;
-    u32x4 af[TM], bf[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const u32x4*>(s + a_rd + i * 4096 + slot);
+    for (int i = 0; i < TM; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(s + a_rd + i * 4096 + slot);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const u32x4*>(s + b_rd + j * 4096 + slot);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j] = mfma_32x32x16<DT>(af[i], bf[j], acc[i][j]);
+    for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(s + b_rd + j * 4096 + slot);
+  };
+  auto mma_step = [&](const Frags& f) {
+    static_for<TM * TN>([&](auto t) {
+      constexpr int i = t / TN, j = t % TN;
+      acc[i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[i][j]);
+    });
   };
 
   // Accumulator fault: XOR the owning lane's register.  Which 32x32 tile is a uniform choice
@@ -328,14 +339,20 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   auto accumulator_fault = [&]() {
     const uint32_t lane_mask = (lane == sel_lane) ? fmask : 0u;
     uint32_t before = 0;
+    static_for<TM * TN>([&](auto tt) {
+      constexpr int i = tt / TN, j = tt % TN;
+      if (tt == sel_t) {
+        f32x16 t = acc[i][j];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        if (i * TN + j == sel_t) {
-          before = __float_as_uint(acc[i][j][sel_v]);
-          acc[i][j][sel_v] = __uint_as_float(before ^ lane_mask);
+        for (int v = 0; v < 16; ++v) {
+          const bool here = v == sel_v;                       // uniform
+          const uint32_t w = __float_as_uint(t[v]);
+          before = here ? w : before;
+          t[v] = __uint_as_float(w ^ (here ? lane_mask : 0u));
         }
+        acc[i][j] = t;
+      }
+    });
     if (lane == sel_lane) {
       p.results[trial].site_word_before = before;
       p.results[trial].site_word_after = before ^ fmask;
@@ -343,121 +360,128 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   };
 
   const int nkt = (p.K + kshift + BK - 1) / BK;
-  load_tile(0);
-  store_tile(0, 0);
+  issue_tile(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  fix_tile(0, 0);
   __syncthreads();
 
   for (int kt = 0; kt < nkt; ++kt) {
     const int stage = kt & 1;
-    if (kt + 1 < nkt) load_tile(kt + 1);
+    if (kt + 1 < nkt) issue_tile(kt + 1, stage ^ 1);
     const uint8_t* s = smem + stage * STAGE;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) k16_step(s, kk);
+    Frags f0, f1;
+    read_frags(f0, s, 0);
+    read_frags(f1, s, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f0, s, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f1, s, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f1);
+    __builtin_amdgcn_sched_barrier(0);
     if constexpr (MODE == MODE_CAMPAIGN) {
       if (kt == hook_kt) accumulator_fault();   // one wave of one workgroup per trial
     }
-    if (kt + 1 < nkt) store_tile(kt + 1, stage ^ 1);
+    if (kt + 1 < nkt) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
+      fix_tile(kt + 1, stage ^ 1);
+    }
     __syncthreads();
   }
 
-  // ---- epilogue 1: detector, corrector, optional store (every tile of every trial)
+  // ---- epilogue 1: detector, corrector, optional store (every tile of every trial).
+  // Each 32x32 accumulator tile is copied out of the accumulator file once, as a whole vector.
   const int row_base = m0 + wm * WTM + 4 * lhi;       // + 32*i + 8*q + e
   const int col_base = n0 + wn * WTN + l32;           // + 32*j
   if constexpr (MODE == MODE_GOLDEN) {
+    static_for<TM * TN>([&](auto tt) {
+      constexpr int i = tt / TN, j = tt % TN;
+      const f32x16 t = acc[i][j];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3), col = col_base + 32 * j;
-          if (row < p.M && col < p.N) p.c_out[(size_t)row * p.N + col] = acc[i][j][v];
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3), col = col_base + 32 * j;
+        if (row < p.M && col < p.N) p.c_out[(size_t)row * p.N + col] = t[v];
+      }
+    });
     return;
   } else {
     uint32_t n_flag = 0;
     float* cout = p.c_out ? p.c_out + (size_t)trial * (size_t)p.M * (size_t)p.N : nullptr;
-    float cbj[TN];
+    fi_trial_result* r = p.results + trial;
+    uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
+    float mx_pre = 0.0f, mx_post = 0.0f;
+    static_for<TM * TN>([&](auto tt) {
+      {
+        constexpr int i = tt / TN, j = tt % TN;
+        const f32x16 t = acc[i][j];
+        const int col = col_base + 32 * j;
+        const float cbj = p.cb[col];
+        f32x16 T;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) cbj[j] = p.cb[col_base + 32 * j];
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+          for (int e = 0; e < 4; ++e)
+            T[4 * q + e] = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
+        }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r0 = row_base + 32 * i + 8 * q;
-        const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + r0);
+        for (int v = 0; v < 16; ++v) {
+          const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+          const float c = t[v];
+          const bool inb = row < p.M && col < p.N;
+          const bool flag = inb && !(fabsf(c) <= T[v]);
+          n_flag += flag ? 1u : 0u;
+          if (cout) {
+            float cc = c;
+            if (flag) {
+              if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+              else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
+            }
+            if (inb) cout[(size_t)row * p.N + col] = cc;
+          }
+        }
+        // ---- epilogue 2: deviation from the fault-free result, only where a fault can reach
+        if (affected) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int col = col_base + 32 * j;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int row = r0 + e;
-            const float c = acc[i][j][4 * q + e];
-            const float T = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj[j]), p.gamma);
-            const bool inb = row < p.M && col < p.N;
-            const bool flag = inb && !(fabsf(c) <= T);
-            n_flag += flag ? 1u : 0u;
-            if (cout) {
+          for (int v = 0; v < 16; ++v) {
+            const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+            if (row < p.M && col < p.N) {
+              const float c = t[v];
+              const size_t idx = (size_t)row * p.N + col;
+              const float cs = p.c_star[idx];
+              const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
+              const bool flag = !(fabsf(c) <= T[v]);
               float cc = c;
-              if (flag) {
-                if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
-                else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
-              }
-              if (inb) cout[(size_t)row * p.N + col] = cc;
+              if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+              if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
+              const float dpre = finite_or_inf(fabsf(c - cs));
+              const float dpost = finite_or_inf(fabsf(cc - cs));
+              const bool changed = __float_as_uint(c) != __float_as_uint(cs);
+              n_bit += changed ? 1u : 0u;
+              n_pre += !(dpre <= tau) ? 1u : 0u;
+              n_post += !(dpost <= tau) ? 1u : 0u;
+              mx_pre = fmaxf(mx_pre, dpre);
+              mx_post = fmaxf(mx_post, dpost);
+              const float band = fmaxf(2.0f * tau, T[v] * 0.015625f);
+              const float mag = fabsf(c);
+              n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - T[v]) <= band) ? 1u : 0u;
+              n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
             }
           }
         }
       }
-    }
-    fi_trial_result* r = p.results + trial;
+    });
     if (__ballot(n_flag != 0)) {
       const uint32_t sum = wave_sum(n_flag);
       if (lane == 0) atomicAdd(&r->n_flagged, sum);
     }
-
-    // ---- epilogue 2: deviation from the fault-free result, only where a fault can reach
     if (affected) {
-      uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
-      float mx_pre = 0.0f, mx_post = 0.0f;
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int r0 = row_base + 32 * i + 8 * q;
-          const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + r0);
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int col = col_base + 32 * j;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int row = r0 + e;
-              if (row < p.M && col < p.N) {
-                const float c = acc[i][j][4 * q + e];
-                const float T = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj[j]), p.gamma);
-                const size_t idx = (size_t)row * p.N + col;
-                const float cs = p.c_star[idx];
-                const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
-                const bool flag = !(fabsf(c) <= T);
-                float cc = c;
-                if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
-                if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
-                const float dpre = finite_or_inf(fabsf(c - cs));
-                const float dpost = finite_or_inf(fabsf(cc - cs));
-                const bool changed = __float_as_uint(c) != __float_as_uint(cs);
-                n_bit += changed ? 1u : 0u;
-                n_pre += !(dpre <= tau) ? 1u : 0u;
-                n_post += !(dpost <= tau) ? 1u : 0u;
-                mx_pre = fmaxf(mx_pre, dpre);
-                mx_post = fmaxf(mx_post, dpost);
-                const float band = fmaxf(2.0f * tau, T * 0.015625f);
-                const float mag = fabsf(c);
-                n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - T) <= band) ? 1u : 0u;
-                n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
-              }
-            }
-          }
-        }
-      }
       uint32_t sum;
       sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&r->n_bitdiff, sum);
       sum = wave_sum(n_pre);  if (lane == 0 && sum) atomicAdd(&r->n_dev_pre, sum);

@@ -186,6 +186,12 @@ def test_zero_fault_trials_are_masked_on_every_workload():
         for k in ("n_flagged", "n_bitdiff", "n_dev_pre", "n_dev_post", "status"):
             assert not recs[k].any(), (w.name, k)
         assert not recs["max_dev_pre"].any() and (gu.cls_of(recs) == fi.MASKED).all()
+        # the fault-free result does not depend on the workgroup tile: a clean trial run with any
+        # other tile shape is still bit-identical to the plan's C*
+        for cfg in (0, 1, 2):
+            plan.tune(cfg, 3)
+            recs = gu.gpu_campaign(plan, faults, wl.CORRECT_ZERO)
+            assert not recs["n_bitdiff"].any() and not recs["n_flagged"].any(), (w.name, cfg)
         plan.destroy()
 
 
