@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfi_gfx950.so")
 SOURCES = ["fi_api.hip"]
-HEADERS = ["gemm_fi.hpp", "aux_kernels.hpp"]
+HEADERS = ["gemm_fi.hpp", "gemm_fi_multi.hpp", "aux_kernels.hpp"]
 
 
 def stale():

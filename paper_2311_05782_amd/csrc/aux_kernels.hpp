@@ -172,6 +172,48 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
   }
 }
 
+// Splits a batch: trials the multi-trial GEMM kernel can take (no fault, or an accumulator flip
+// at the end of a 64-wide k-tile; out-of-range sites count as "no fault") go to the front of
+// perm in list order, all others (operand faults, flips inside a k-tile) behind them.
+// counts = {front, back}.  One workgroup; each thread owns a contiguous chunk of the list.
+__global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* __restrict__ f, uint32_t n,
+                                                               uint32_t M, uint32_t N, uint32_t K, uint32_t kb,
+                                                               uint32_t* __restrict__ perm,
+                                                               uint32_t* __restrict__ counts) {
+  __shared__ uint32_t offs[1024];
+  __shared__ uint32_t total_fast;
+  const uint32_t chunk = (n + 1023) / 1024;
+  const uint32_t lo = min(threadIdx.x * chunk, n), hi = min(lo + chunk, n);
+  auto fast = [&](uint32_t t) {
+    const fi_fault x = f[t];
+    if (x.kind == FI_SITE_ACC) {
+      const bool valid = x.row < M && x.col < N && x.kblock < K / kb;
+      return !valid || ((x.kblock + 1) * kb) % 64 == 0;
+    }
+    if (x.kind == FI_SITE_A) return !(x.row < M && x.col < K);
+    if (x.kind == FI_SITE_B) return !(x.row < K && x.col < N);
+    return true;   // NONE and unknown kinds run fault-free
+  };
+  uint32_t c = 0;
+  for (uint32_t t = lo; t < hi; ++t) c += fast(t) ? 1u : 0u;
+  offs[threadIdx.x] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {            // 1024 additions: negligible next to the batch itself
+    uint32_t run = 0;
+    for (int i = 0; i < 1024; ++i) { uint32_t v = offs[i]; offs[i] = run; run += v; }
+    total_fast = run;
+    counts[0] = run;
+    counts[1] = n - run;
+  }
+  __syncthreads();
+  uint32_t pf = offs[threadIdx.x];                       // fast trials before my chunk
+  const uint32_t n_fast = total_fast;
+  uint32_t ps = n_fast + (lo - pf);                      // slow trials before my chunk, after the front
+  for (uint32_t t = lo; t < hi; ++t) {
+    if (fast(t)) perm[pf++] = t; else perm[ps++] = t;
+  }
+}
+
 // Outcome per trial and campaign totals, one workgroup, no atomics:
 // DETECTED if anything was flagged, else SDC if anything deviates beyond the
 // tolerance, else MASKED.

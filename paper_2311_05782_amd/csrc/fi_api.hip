@@ -11,6 +11,7 @@
 #include "aux_kernels.hpp"
 #include "fi.h"
 #include "gemm_fi.hpp"
+#include "gemm_fi_multi.hpp"
 
 namespace {
 
@@ -44,6 +45,15 @@ constexpr TileCfg kCfg[] = {
 };
 constexpr int kNumCfg = sizeof(kCfg) / sizeof(kCfg[0]);
 
+// Multi-trial configurations: R trials share one staged BM x BN tile (see gemm_fi_multi.hpp).
+struct MultiCfg { int r, bm, bn, wm, wn; };
+constexpr MultiCfg kMulti[] = {
+    {4, 128, 128, 4, 2},   // each wave 32 x 64 for 4 trials
+    {2, 256, 128, 4, 2},   // each wave 64 x 64 for 2 trials
+    {8, 128, 64, 4, 2},    // each wave 32 x 32 for 8 trials: narrow outputs
+};
+constexpr int kNumMulti = sizeof(kMulti) / sizeof(kMulti[0]);
+
 }  // namespace
 
 struct fi_plan {
@@ -60,8 +70,11 @@ struct fi_plan {
   float* scratch;          // 4 floats + 1 word
   float t_global;
   int cfg;                 // index into kCfg
+  int mcfg;                // index into kMulti, or -1: every trial through the single-trial kernel
   int group;               // trials sharing a tile back to back
   int device;
+  uint32_t* perm;          // [perm_cap] trial order of the current batch + 2 counters behind it
+  uint32_t perm_cap;
 };
 
 namespace {
@@ -84,6 +97,30 @@ hipError_t launch_gemm(int dtype, int cfg, const GemmArgs& a, int n_blocks, hipS
   FI_CASE(FI_BF16, 0); FI_CASE(FI_BF16, 1); FI_CASE(FI_BF16, 2);
 #undef FI_CASE
   return hipErrorInvalidValue;
+}
+
+template <int DT, int MC>
+hipError_t launch_multi_cfg(const GemmArgs& a, int n_blocks, hipStream_t s) {
+  constexpr MultiCfg c = kMulti[MC];
+  hipLaunchKernelGGL((fi::gemm_fi_multi_kernel<DT, c.r, c.bm, c.bn, c.wm, c.wn>), dim3(n_blocks),
+                     dim3(c.wm * c.wn * 64), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_multi(int dtype, int mcfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
+#define FI_CASE(DT, MC) \
+  if (dtype == DT && mcfg == MC) return launch_multi_cfg<DT, MC>(a, n_blocks, s)
+  FI_CASE(FI_FP16, 0); FI_CASE(FI_FP16, 1); FI_CASE(FI_FP16, 2);
+  FI_CASE(FI_BF16, 0); FI_CASE(FI_BF16, 1); FI_CASE(FI_BF16, 2);
+#undef FI_CASE
+  return hipErrorInvalidValue;
+}
+
+// The multi-trial kernel needs whole 64-wide k-tiles.
+int pick_multi(const fi_plan_desc& d) {
+  if (d.K % 64 != 0) return -1;
+  if (d.N <= 64) return 2;
+  return 0;
 }
 
 int pick_cfg(const fi_plan_desc& d) {
@@ -167,6 +204,7 @@ void free_plan_buffers(fi_plan* p) {
   if (p->kra) (void)hipFree(p->kra);
   if (p->cb) (void)hipFree(p->cb);
   if (p->scratch) (void)hipFree(p->scratch);
+  if (p->perm) (void)hipFree(p->perm);
 }
 
 size_t padded(uint32_t n) { return ((size_t)n + PAD - 1) / PAD * PAD; }
@@ -289,6 +327,7 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   p->d = d;
   p->d.gamma = gamma;
   p->cfg = pick_cfg(d);
+  p->mcfg = pick_multi(d);
   p->group = 32;
   (void)hipGetDevice(&p->device);
   st = build_plan(p, d_A, d_B, as_stream(stream));
@@ -330,12 +369,16 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
 fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, void* stream) {
   fi_status st = check_plan(plan);
   if (st != FI_OK) return st;
-  if (tile_config >= kNumCfg) return fail(FI_INVALID_ARG, "tile_config must be < %d", kNumCfg);
+  if (tile_config >= kNumCfg + kNumMulti)
+    return fail(FI_INVALID_ARG, "tile_config must be < %d", kNumCfg + kNumMulti);
+  if (tile_config >= kNumCfg && plan->d.K % 64 != 0)
+    return fail(FI_UNSUPPORTED, "multi-trial tiles need K to be a multiple of 64");
   if (trial_group == 0 || trial_group > 4096) return fail(FI_INVALID_ARG, "trial_group must be in 1..4096");
   if (trial_group > 0) plan->group = trial_group;
   // C* does not depend on the tile shape: every shape feeds each output element the same
   // sequence of 16-wide MFMA steps in ascending k.
-  if (tile_config >= 0) plan->cfg = tile_config;
+  if (tile_config >= kNumCfg) plan->mcfg = tile_config - kNumCfg;
+  else if (tile_config >= 0) { plan->cfg = tile_config; plan->mcfg = -1; }
   (void)stream;
   return FI_OK;
 }
@@ -356,11 +399,35 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
                      dim3(256), 0, s, reinterpret_cast<uint32_t*>(d_results), words, 0u);
   FI_HIP(hipGetLastError());
   a.n_trials = (int)n_trials;
-  a.group = plan->group < (int)n_trials ? plan->group : (int)n_trials;
+  a.group = plan->group;
   a.faults = d_faults;
   a.results = d_results;
   a.c_out = d_c_out;
   a.policy = (int)policy;
+  if (plan->mcfg >= 0) {
+    // Split the batch on the device: trials whose fault leaves the operands alone and lands on a
+    // k-tile boundary share staged operands R at a time; the rest take the single-trial kernel.
+    if (plan->perm_cap < n_trials) {
+      if (plan->perm) (void)hipFree(plan->perm);     // waits for work that may still read it
+      plan->perm = nullptr; plan->perm_cap = 0;
+      FI_HIP(hipMalloc(&plan->perm, ((size_t)n_trials + 2) * sizeof(uint32_t)));
+      plan->perm_cap = n_trials;
+    }
+    uint32_t* counts = plan->perm + plan->perm_cap;
+    hipLaunchKernelGGL(fi::partition_trials_kernel, dim3(1), dim3(1024), 0, s, d_faults, n_trials, plan->d.M,
+                       plan->d.N, plan->d.K, plan->d.k_block, plan->perm, counts);
+    FI_HIP(hipGetLastError());
+    a.perm = plan->perm;
+    a.part_counts = counts;
+    const MultiCfg mc = kMulti[plan->mcfg];
+    GemmArgs m = a;
+    m.tiles_m = (a.M + mc.bm - 1) / mc.bm;
+    m.tiles_n = (a.N + mc.bn - 1) / mc.bn;
+    const uint64_t groups = ((uint64_t)n_trials + mc.r - 1) / mc.r;
+    const uint64_t mblocks = (uint64_t)m.tiles_m * m.tiles_n * groups;
+    if (mblocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
+    FI_HIP(launch_multi((int)plan->d.dtype, plan->mcfg, m, (int)mblocks, s));
+  }
   FI_HIP(launch_gemm<fi::MODE_CAMPAIGN>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
   return FI_OK;
 }

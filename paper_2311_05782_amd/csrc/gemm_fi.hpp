@@ -61,6 +61,11 @@ struct GemmArgs {
   const float* s_abs;       // [M][N] sum_k |a b|        (campaign)
   float* c_out;             // campaign: nullable [n_trials][M][N]; golden: [M][N]
   int policy;
+  // Optional split of the batch (both NULL: every trial goes through gemm_fi_kernel in list order).
+  // perm[0 .. c0) are the trials the multi-trial kernel takes, perm[c0 .. c0+c1) the others;
+  // part_counts = {c0, c1}.
+  const uint32_t* perm;
+  const uint32_t* part_counts;
 };
 
 template <int DT>
@@ -108,26 +113,26 @@ __device__ __forceinline__ float finite_or_inf(float d) {
   return (d <= 3.4028234e38f) ? d : __uint_as_float(0x7F800000u);
 }
 
-// Workgroup id -> (tile, trial).  Workgroups are dealt round-robin to the 8
-// XCDs, each with its own L2; give every XCD one contiguous slice of the work
-// list, and order the list so that `group` consecutive entries are the SAME
-// tile for different trials: the CUs of an XCD then stream the same A and B
-// panels through that XCD's L2 at the same time.
-__device__ __forceinline__ void work_of_block(const GemmArgs& p, int& tile, int& trial) {
+// Workgroup id -> (tile, item), item = a trial or a group of trials.  Workgroups are dealt
+// round-robin to the 8 XCDs, each with its own L2; give every XCD one contiguous slice of the
+// work list, and order the list so that `group` consecutive entries are the SAME tile for
+// different items: the CUs of an XCD then stream the same A and B panels through that XCD's L2
+// at the same time.  The grid holds n_tiles * n_items workgroups.
+__device__ __forceinline__ void work_of_block(int n_tiles, int n_items, int group, int& tile, int& item) {
   uint32_t w = blockIdx.x, total = gridDim.x;
   uint32_t per = total >> 3;
   uint32_t L = (w < per * 8u) ? (w & 7u) * per + (w >> 3) : w;
-  uint32_t G = (uint32_t)p.group, ntiles = (uint32_t)(p.tiles_m * p.tiles_n);
-  uint32_t full = ((uint32_t)p.n_trials / G) * G;
+  uint32_t G = (uint32_t)min(group, n_items), ntiles = (uint32_t)n_tiles;
+  uint32_t full = ((uint32_t)n_items / G) * G;
   uint32_t cut = full * ntiles;
   if (L < cut) {
     uint32_t r = L / G;
-    trial = (int)((r / ntiles) * G + (L % G));
+    item = (int)((r / ntiles) * G + (L % G));
     tile = (int)(r % ntiles);
   } else {
-    uint32_t G2 = (uint32_t)p.n_trials - full;
+    uint32_t G2 = (uint32_t)n_items - full;
     L -= cut;
-    trial = (int)(full + L % G2);
+    item = (int)(full + L % G2);
     tile = (int)(L / G2);
   }
 }
@@ -150,7 +155,13 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   const int l32 = lane & 31, lhi = lane >> 5;
 
   int tile, trial;
-  work_of_block(p, tile, trial);
+  work_of_block(p.tiles_m * p.tiles_n, p.n_trials, p.group, tile, trial);
+  if constexpr (MODE == MODE_CAMPAIGN) {
+    if (p.perm) {   // only the trials the multi-trial kernel left: positions c0 .. c0+c1 of perm
+      if (trial >= (int)p.part_counts[1]) return;      // uniform, before any barrier
+      trial = (int)p.perm[p.part_counts[0] + (uint32_t)trial];
+    }
+  }
   const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 

@@ -1,0 +1,288 @@
+// Fault-injecting GEMM, R trials per workgroup (gfx950).
+//
+// Every trial of a campaign multiplies the SAME operands (paper Sec. IV-A: one fault per run of
+// the unchanged application); only the accumulators differ once a fault has been applied.  So a
+// workgroup can stage one A/B k-tile in LDS, read one set of MFMA fragments per wave, and feed
+// them to R independent accumulator sets - one per trial.  Each trial still executes all of its
+// 2*M*N*K flops on the matrix cores; what is shared is operand traffic: L2 -> LDS bytes and
+// ds_read_b128 per MFMA both fall by the factor the tile shrinks less than R grows
+// (R = 4 on a 128x128 tile: half the bytes per flop of one 256x256 tile per trial).
+//
+// Handles trials whose fault is NONE or an accumulator flip that falls on a 64-wide k-tile
+// boundary, on problems with K % 64 == 0.  The library's partition kernel routes every other
+// trial (operand faults, flips inside a k-tile) to gemm_fi_kernel.
+//
+// The per-element arithmetic is that of gemm_fi_kernel: the same sequence of
+// v_mfma_f32_32x32x16 steps in ascending k, hence bit-identical fault-free results.
+#pragma once
+
+#include "gemm_fi.hpp"
+
+namespace fi {
+
+template <int DT, int R, int BM, int BN, int WM, int WN>
+__global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmArgs p) {
+  constexpr int BK = 64;
+  constexpr int NW = WM * WN;
+  constexpr int WTM = BM / WM, WTN = BN / WN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int STAGE = (BM + BN) * 128;
+  constexpr int A_G = BM / 8 / NW, B_G = BN / 8 / NW;      // 8-row groups staged per wave
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a multiple of the 32x32 MFMA");
+  static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "row groups divide among the waves");
+  static_assert(R * TM * TN * 16 <= 128, "accumulators fit half the register file");
+  static_assert(2 * STAGE <= 160 * 1024, "two stages fit the 160 KB LDS");
+
+  __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, lhi = lane >> 5;
+
+  // ---- work: (tile, group of R eligible trials)
+  const int n_fast = (int)p.part_counts[0];
+  const int n_groups_max = (p.n_trials + R - 1) / R;
+  int tile, grp;
+  work_of_block(p.tiles_m * p.tiles_n, n_groups_max, p.group, tile, grp);
+  if (grp * R >= n_fast) return;                       // uniform: this group holds no trial
+  const int n_act = min(R, n_fast - grp * R);
+  const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // ---- per trial (all uniform): index, and for the wave that owns an accumulator site the
+  // k-tile after which it flips.  Site details are re-derived from the fault when needed.
+  int trial[R], hook_kt[R];
+  uint32_t affected = 0;                               // bit r: this tile holds trial r's site
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    trial[r] = (int)p.perm[grp * R + min(r, n_act - 1)];
+    hook_kt[r] = -1;
+    if (r < n_act) {
+      const fi_fault f = p.faults[trial[r]];
+      const bool is_acc = f.kind == FI_SITE_ACC;
+      const bool valid = f.kind == FI_SITE_NONE ||
+                         (is_acc && f.row < (uint32_t)p.M && f.col < (uint32_t)p.N &&
+                          f.kblock < (uint32_t)(p.K / p.kb));
+      if (!valid && tile == 0 && tid == 0) p.results[trial[r]].status = 1;   // runs fault-free
+      if (is_acc && valid) {
+        const int li = (int)f.row - m0, lj = (int)f.col - n0;
+        if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
+          affected |= 1u << r;
+          const int wi = li - wm * WTM, wj = lj - wn * WTN;
+          if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) hook_kt[r] = ((int)f.kblock + 1) * p.kb / BK - 1;
+        }
+      }
+    }
+  }
+
+  // ---- staging: global -> LDS directly, as in gemm_fi_kernel
+  const int lrow = lane >> 3, lslot = lane & 7;
+  uint32_t a_goff[A_G], b_goff[B_G];
+#pragma unroll
+  for (int c = 0; c < A_G; ++c) {
+    const int row = (wave * A_G + c) * 8 + lrow;
+    a_goff[c] = (uint32_t)min(m0 + row, p.M - 1) * p.lda + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
+  }
+#pragma unroll
+  for (int c = 0; c < B_G; ++c) {
+    const int row = (wave * B_G + c) * 8 + lrow;
+    b_goff[c] = (uint32_t)min(n0 + row, p.N - 1) * p.ldb + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
+  }
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef const __attribute__((address_space(1))) void glb_void;
+  auto issue_tile = [&](int kt, int stage) {
+    const int k0 = kt * BK;
+    uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
+    uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
+#pragma unroll
+    for (int c = 0; c < A_G; ++c)
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + a_goff[c] + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
+#pragma unroll
+    for (int c = 0; c < B_G; ++c)
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
+  };
+
+  // ---- fragments and accumulators
+  const int sw = lds_swizzle(l32);
+  const int a_rd = (wm * WTM + l32) * 128;
+  const int b_rd = BM * 128 + (wn * WTN + l32) * 128;
+
+  f32x16 acc[R][TM][TN];
+  static_for<R * TM * TN>([&](auto t) {
+    acc[t / (TM * TN)][(t / TN) % TM][t % TN] =
+        f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  });
+
+  struct Frags { u32x4 a[TM]; u32x4 b[TN]; };
+  auto read_frags = [&](Frags& f, const uint8_t* s, int kk) {
+    const int slot = ((2 * kk + lhi) ^ sw) << 4;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(s + a_rd + i * 4096 + slot);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(s + b_rd + j * 4096 + slot);
+  };
+  // one fragment set, R accumulator sets
+  auto mma_step = [&](const Frags& f) {
+    static_for<R * TM * TN>([&](auto t) {
+      constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+      acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
+    });
+  };
+
+  // Accumulator flip of trial r (this wave owns its site).  The site is re-read from the fault:
+  // this runs once per trial in the whole grid.
+  auto accumulator_fault = [&](auto rr) {
+    constexpr int r = rr;
+    const fi_fault f = p.faults[trial[r]];
+    const int wi = (int)f.row - m0 - wm * WTM, wj = (int)f.col - n0 - wn * WTN;
+    const int ri = wi & 31, rj = wj & 31;
+    const int sel_t = (wi >> 5) * TN + (wj >> 5);
+    const int sel_v = 4 * (ri >> 3) + (ri & 3);
+    const int sel_lane = rj + 32 * ((ri >> 2) & 1);
+    const uint32_t lane_mask = (lane == sel_lane) ? f.xor_mask : 0u;
+    uint32_t before = 0;
+    static_for<TM * TN>([&](auto tt) {
+      constexpr int i = tt / TN, j = tt % TN;
+      if (tt == sel_t) {
+        f32x16 t = acc[r][i][j];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const bool here = v == sel_v;
+          const uint32_t w = __float_as_uint(t[v]);
+          before = here ? w : before;
+          t[v] = __uint_as_float(w ^ (here ? lane_mask : 0u));
+        }
+        acc[r][i][j] = t;
+      }
+    });
+    if (lane == sel_lane) {
+      p.results[trial[r]].site_word_before = before;
+      p.results[trial[r]].site_word_after = before ^ f.xor_mask;
+    }
+  };
+
+  // ---- main loop: double-buffered LDS, one barrier per k-tile
+  const int nkt = p.K / BK;
+  issue_tile(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  __syncthreads();
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int stage = kt & 1;
+    if (kt + 1 < nkt) issue_tile(kt + 1, stage ^ 1);
+    const uint8_t* s = smem + stage * STAGE;
+    Frags f0, f1;
+    read_frags(f0, s, 0);
+    read_frags(f1, s, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f0, s, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(f1, s, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_step(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    // accumulator faults that fall at the end of this k-tile (at most one wave per trial)
+    static_for<R>([&](auto rr) {
+      if (kt == hook_kt[rr]) accumulator_fault(rr);
+    });
+    if (kt + 1 < nkt) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
+    __syncthreads();
+  }
+
+  // ---- epilogue, trial by trial: detector, corrector, optional store; deviation counters where
+  // the trial's fault can reach.  Thresholds are shared (same rows and columns for every trial).
+  const int row_base = m0 + wm * WTM + 4 * lhi;       // + 32*i + 8*q + e
+  const int col_base = n0 + wn * WTN + l32;           // + 32*j
+  static_for<R>([&](auto rr) {
+    constexpr int r = rr;
+    if (r < n_act) {
+      const bool aff = (affected >> r) & 1u;
+      fi_trial_result* res = p.results + trial[r];
+      float* cout = p.c_out ? p.c_out + (size_t)trial[r] * (size_t)p.M * (size_t)p.N : nullptr;
+      uint32_t n_flag = 0, n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
+      float mx_pre = 0.0f, mx_post = 0.0f;
+      static_for<TM * TN>([&](auto tt) {
+        constexpr int i = tt / TN, j = tt % TN;
+        const f32x16 t = acc[r][i][j];
+        const int col = col_base + 32 * j;
+        const float cbj = p.cb[col];
+        f32x16 T;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            T[4 * q + e] = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+          const float c = t[v];
+          const bool inb = row < p.M && col < p.N;
+          const bool flag = inb && !(fabsf(c) <= T[v]);
+          n_flag += flag ? 1u : 0u;
+          if (cout) {
+            float cc = c;
+            if (flag) {
+              if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+              else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
+            }
+            if (inb) cout[(size_t)row * p.N + col] = cc;
+          }
+        }
+        if (aff) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+            if (row < p.M && col < p.N) {
+              const float c = t[v];
+              const size_t idx = (size_t)row * p.N + col;
+              const float cs = p.c_star[idx];
+              const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
+              const bool flag = !(fabsf(c) <= T[v]);
+              float cc = c;
+              if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+              if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
+              const float dpre = finite_or_inf(fabsf(c - cs));
+              const float dpost = finite_or_inf(fabsf(cc - cs));
+              const bool changed = __float_as_uint(c) != __float_as_uint(cs);
+              n_bit += changed ? 1u : 0u;
+              n_pre += !(dpre <= tau) ? 1u : 0u;
+              n_post += !(dpost <= tau) ? 1u : 0u;
+              mx_pre = fmaxf(mx_pre, dpre);
+              mx_post = fmaxf(mx_post, dpost);
+              const float band = fmaxf(2.0f * tau, T[v] * 0.015625f);
+              const float mag = fabsf(c);
+              n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - T[v]) <= band) ? 1u : 0u;
+              n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
+            }
+          }
+        }
+      });
+      if (__ballot(n_flag != 0)) {
+        const uint32_t sum = wave_sum(n_flag);
+        if (lane == 0) atomicAdd(&res->n_flagged, sum);
+      }
+      if (aff) {
+        uint32_t sum;
+        sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&res->n_bitdiff, sum);
+        sum = wave_sum(n_pre);  if (lane == 0 && sum) atomicAdd(&res->n_dev_pre, sum);
+        sum = wave_sum(n_post); if (lane == 0 && sum) atomicAdd(&res->n_dev_post, sum);
+        sum = wave_sum(n_bT);   if (lane == 0 && sum) atomicAdd(&res->n_border_T, sum);
+        sum = wave_sum(n_btau); if (lane == 0 && sum) atomicAdd(&res->n_border_tau, sum);
+        sum = wave_max(__float_as_uint(mx_pre));
+        if (lane == 0 && sum) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_pre), sum);
+        sum = wave_max(__float_as_uint(mx_post));
+        if (lane == 0 && sum) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_post), sum);
+      }
+    }
+  });
+}
+
+}  // namespace fi
