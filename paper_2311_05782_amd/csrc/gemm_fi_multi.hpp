@@ -160,19 +160,27 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       p.results[trial[r]].site_word_before = before;
       p.results[trial[r]].site_word_after = before ^ f.xor_mask;
     }
+    // Leave nothing of this rare path in flight: the compiler places its waits statically, and a
+    // load pending here would make every iteration of the main loop wait for its own prefetch.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   };
 
-  // ---- main loop: double-buffered LDS, one barrier per k-tile
+  // ---- main loop: double-buffered LDS, one barrier per k-tile.  The barrier sits before the
+  // last of the four MFMA steps of a tile: by then a wave holds the tile's last fragments in
+  // registers, so right after the barrier it reads the first fragments of the next tile while
+  // the matrix cores still have R*TM*TN MFMAs of this tile to issue - the LDS latency that
+  // follows a barrier is covered by work instead of idling the pipe.
   const int nkt = p.K / BK;
   issue_tile(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
+  Frags f0, f1;
+  read_frags(f0, smem, 0);
   for (int kt = 0; kt < nkt; ++kt) {
     const int stage = kt & 1;
-    if (kt + 1 < nkt) issue_tile(kt + 1, stage ^ 1);
+    const bool more = kt + 1 < nkt;
+    if (more) issue_tile(kt + 1, stage ^ 1);
     const uint8_t* s = smem + stage * STAGE;
-    Frags f0, f1;
-    read_frags(f0, s, 0);
     read_frags(f1, s, 1);
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f0);
@@ -185,55 +193,81 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f0);
     __builtin_amdgcn_sched_barrier(0);
+    // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
+    // once all waves are here the next tile has landed and this stage may be overwritten.
+    if (more) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
+    __syncthreads();
+    if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
+    __builtin_amdgcn_sched_barrier(0);
     mma_step(f1);
     __builtin_amdgcn_sched_barrier(0);
     // accumulator faults that fall at the end of this k-tile (at most one wave per trial)
     static_for<R>([&](auto rr) {
       if (kt == hook_kt[rr]) accumulator_fault(rr);
     });
-    if (kt + 1 < nkt) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
-    __syncthreads();
   }
 
   // ---- epilogue, trial by trial: detector, corrector, optional store; deviation counters where
-  // the trial's fault can reach.  Thresholds are shared (same rows and columns for every trial).
+  // the trial's fault can reach.  Thresholds are the same for every trial (same rows and
+  // columns), so they are formed once; elements outside the problem get T = +Inf and, in ragged
+  // tiles, a zeroed accumulator (clamped staging rows made them copies of the last row).
   const int row_base = m0 + wm * WTM + 4 * lhi;       // + 32*i + 8*q + e
   const int col_base = n0 + wn * WTN + l32;           // + 32*j
+  const bool ragged = m0 + BM > p.M || n0 + BN > p.N;
+  f32x16 T[TM * TN];
+  static_for<TM * TN>([&](auto tt) {
+    constexpr int i = tt / TN, j = tt % TN;
+    const int col = col_base + 32 * j;
+    const float cbj = p.cb[min(col, p.N - 1)];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int row = row_base + 32 * i + 8 * q + e;
+        const float t = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
+        T[tt][4 * q + e] = (row < p.M && col < p.N) ? t : __builtin_inff();
+      }
+    }
+  });
+  if (ragged) {
+    static_for<R * TM * TN>([&](auto t) {
+      constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+      f32x16 a = acc[r][i][j];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+        a[v] = (row < p.M && col_base + 32 * j < p.N) ? a[v] : 0.0f;
+      }
+      acc[r][i][j] = a;
+    });
+  }
   static_for<R>([&](auto rr) {
     constexpr int r = rr;
     if (r < n_act) {
       const bool aff = (affected >> r) & 1u;
       fi_trial_result* res = p.results + trial[r];
       float* cout = p.c_out ? p.c_out + (size_t)trial[r] * (size_t)p.M * (size_t)p.N : nullptr;
-      uint32_t n_flag = 0, n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
+      uint32_t n_flag = 0;                             // wave-uniform: popcounts of lane masks
+      uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
       float mx_pre = 0.0f, mx_post = 0.0f;
       static_for<TM * TN>([&](auto tt) {
         constexpr int i = tt / TN, j = tt % TN;
         const f32x16 t = acc[r][i][j];
         const int col = col_base + 32 * j;
-        const float cbj = p.cb[col];
-        f32x16 T;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            T[4 * q + e] = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
-        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
           const float c = t[v];
-          const bool inb = row < p.M && col < p.N;
-          const bool flag = inb && !(fabsf(c) <= T[v]);
-          n_flag += flag ? 1u : 0u;
+          const bool flag = !(fabsf(c) <= T[tt][v]);
+          n_flag += (uint32_t)__builtin_popcountll(__ballot(flag));
           if (cout) {
             float cc = c;
             if (flag) {
               if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
               else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
             }
-            if (inb) cout[(size_t)row * p.N + col] = cc;
+            if (row < p.M && col < p.N) cout[(size_t)row * p.N + col] = cc;
           }
         }
         if (aff) {
@@ -245,7 +279,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
               const size_t idx = (size_t)row * p.N + col;
               const float cs = p.c_star[idx];
               const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
-              const bool flag = !(fabsf(c) <= T[v]);
+              const float Tv = T[tt][v];
+              const bool flag = !(fabsf(c) <= Tv);
               float cc = c;
               if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
               if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
@@ -257,18 +292,15 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
               n_post += !(dpost <= tau) ? 1u : 0u;
               mx_pre = fmaxf(mx_pre, dpre);
               mx_post = fmaxf(mx_post, dpost);
-              const float band = fmaxf(2.0f * tau, T[v] * 0.015625f);
+              const float band = fmaxf(2.0f * tau, Tv * 0.015625f);
               const float mag = fabsf(c);
-              n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - T[v]) <= band) ? 1u : 0u;
+              n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - Tv) <= band) ? 1u : 0u;
               n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
             }
           }
         }
       });
-      if (__ballot(n_flag != 0)) {
-        const uint32_t sum = wave_sum(n_flag);
-        if (lane == 0) atomicAdd(&res->n_flagged, sum);
-      }
+      if (n_flag != 0 && lane == 0) atomicAdd(&res->n_flagged, n_flag);
       if (aff) {
         uint32_t sum;
         sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&res->n_bitdiff, sum);

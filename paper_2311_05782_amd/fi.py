@@ -11,7 +11,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfi_gfx950.so")
+# FI_LIBRARY selects another build of the same ABI (e.g. a tuning experiment).
+LIB_PATH = os.environ.get("FI_LIBRARY") or os.path.join(_HERE, "libfi_gfx950.so")
 
 OK, INVALID_ARG, UNSUPPORTED, OOM, DEVICE, STATE = range(6)
 FP16, BF16 = 0, 1
