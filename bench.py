@@ -21,6 +21,28 @@ sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16/BF16
 
+# HBM bytes of one campaign launch of the default workload and kernel choice, from two
+# `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) scaled by what the same
+# counters read for a plain 1 GiB copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); profiles/ holds the
+# commands.  They describe the kernel sources whose digest is recorded with them and are not
+# reported for any other.
+TRAFFIC = {
+    "sources_sha256": "1472fa0a6a1b0a7c8c2234a8c40a3c9120101d7610a390ffe77cb61e3cb2ea06",
+    "fetch_bytes": 2.2023e6 * 2.0 * 1024,
+    "write_bytes": 151.312 * 1.0 * 1024,
+}
+
+
+def kernel_sources_digest():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2311_05782_amd", "csrc", "*")))
+    for f in files + [os.path.join(ROOT, "include", "fi.h")]:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
 
 def cpu_baseline(w, budget_s=15.0):
     """The CPU oracle as it stands, timed on a row slab of one fault-free pass of the same GEMM
@@ -58,9 +80,13 @@ def main():
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--group", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sources-digest", action="store_true", help="print the kernel sources' digest and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference row for HBM byte counters)")
     args = ap.parse_args()
+    if args.sources_digest:
+        print(kernel_sources_digest())
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: campaigns shard by trial with no exchange, and this build "
               "runs on a single MI355X.  Re-run with --gpus 1.", file=sys.stderr)
@@ -108,7 +134,8 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # HIP events on the launching stream bracket the GEMM kernel of every step.
+    # HIP events on the launching stream bracket the campaign launch of every step: the GEMM
+    # kernel(s) plus the record fill and the trial partition, a few microseconds each.
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -127,9 +154,13 @@ def main():
     tflops = flops_per_launch * args.steps / wall / 1e12
     achieved = flops_per_launch / (sum(kern_ms) / len(kern_ms) * 1e-3) / 1e12
     counts = d_cnt.cpu().numpy().tolist()
+    default_run = (args.workload == "square4096" and not args.trials and args.tile < 0 and args.group <= 0)
+    traffic = None
+    if default_run and TRAFFIC["sources_sha256"] == kernel_sources_digest():
+        traffic = round(TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"])
 
     out = {
-        "metric": "fault-injected GEMM throughput (every trial recomputes the whole GEMM)",
+        "metric": "fault-injected GEMM TFLOP/s and trials/sec on 1 MI355X; % of MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s",
         "trials_per_s": round(n_trials * args.steps / wall, 1),
         "frac_of_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS, 4),
@@ -143,8 +174,9 @@ def main():
                    "trials_per_batch": n_trials, "plan_create_ms": round(plan_ms, 2),
                    "outcomes_masked_sdc_detected": counts},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "gemm_fi_kernel", "kernel_ms_avg": round(sum(kern_ms) / len(kern_ms), 3),
+                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
+                     "traffic_unit": "HBM bytes per launch (fetch + write)", "kernel": plan.describe(),
+                     "flops_per_launch": flops_per_launch, "kernel_ms_avg": round(sum(kern_ms) / len(kern_ms), 3),
                      "kernel_ms_min": round(min(kern_ms), 3)},
     }
     if not args.no_cpu_baseline:

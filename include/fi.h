@@ -125,12 +125,23 @@ fi_status fi_plan_destroy(fi_plan* plan);
  * 2: fl32(K*ra_i) [M] float, 3: cb_j [N] float. */
 fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr);
 
-/* Optional tuning.  tile_config: -1 keep, else index of a workgroup-tile shape
- * (0: 256x256, 1: 128x128, 2: 256x64); trial_group: -1 keep, else how many
- * trials of the same output tile are scheduled next to each other.  Results
- * do not depend on either (every tile shape accumulates each element in the
- * same order); `stream` is unused. */
+/* Optional tuning.  tile_config: -1 keep, else an index into the kernel table:
+ *   0..2  one trial per workgroup on a 256x256, 128x128 or 256x64 output tile
+ *         (every fault kind, any K);
+ *   3..5  R trials per workgroup sharing one staged operand tile: R=4 on 128x128,
+ *         R=2 on 256x128, R=8 on 128x64 (the default when K % 64 == 0).  These take
+ *         the fault-free trials and the accumulator faults whose k-block ends on a
+ *         multiple of 64; the library routes every other trial of the batch to the
+ *         one-trial kernel.  FI_UNSUPPORTED if K % 64 != 0.
+ * trial_group: -1 keep, else how many trials (groups of R trials) of the same
+ * output tile are scheduled next to each other, 1..4096.  Results do not depend on
+ * either (every shape accumulates each element in the same order); `stream` is unused. */
 fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, void* stream);
+
+/* Writes a NUL-terminated description of the kernels the plan launches for a
+ * campaign (template shape, threads, trials per workgroup) into h_buf (HOST memory,
+ * n bytes; truncated to fit).  INVALID_ARG if h_buf is NULL or n == 0. */
+fi_status fi_plan_describe(const fi_plan* plan, char* h_buf, uint64_t n);
 
 /* Run n_trials faulty executions of the whole GEMM in one launch, each with
  * its fault from d_faults[t], followed in the same kernel by the detector,

@@ -382,6 +382,22 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
   return FI_OK;
 }
 
+fi_status fi_plan_describe(const fi_plan* plan, char* h_buf, uint64_t n) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!h_buf || n == 0) return fail(FI_INVALID_ARG, "h_buf is NULL or n is 0");
+  const TileCfg c = kCfg[plan->cfg];
+  const char* dt = plan->d.dtype == FI_BF16 ? "bf16" : "fp16";
+  if (plan->mcfg >= 0) {
+    const MultiCfg m = kMulti[plan->mcfg];
+    snprintf(h_buf, n, "gemm_fi_multi_kernel<%s, R=%d, %dx%d, %d threads> + gemm_fi_kernel<%s, %dx%d, %d threads> "
+             "for trials it cannot take", dt, m.r, m.bm, m.bn, m.wm * m.wn * 64, dt, c.bm, c.bn, c.wm * c.wn * 64);
+  } else {
+    snprintf(h_buf, n, "gemm_fi_kernel<%s, %dx%d, %d threads>", dt, c.bm, c.bn, c.wm * c.wn * 64);
+  }
+  return FI_OK;
+}
+
 fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
                                fi_trial_result* d_results, float* d_c_out, void* stream) {
   fi_status st = check_plan(plan);

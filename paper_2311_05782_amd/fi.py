@@ -24,7 +24,7 @@ KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A = 0, 1, 2, 3
 BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 
 # Symbols include/fi.h declares; the loader checks every one.
-EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune",
+EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
            "fi_gemm_inject_batch", "fi_detect_correct", "fi_classify", "fi_sample_faults",
            "fi_last_error"]
 
@@ -76,6 +76,7 @@ def lib():
     L.fi_plan_destroy.argtypes = [vp]
     L.fi_plan_buffer.argtypes = [vp, C.c_uint32, C.POINTER(vp)]
     L.fi_plan_tune.argtypes = [vp, C.c_int32, C.c_int32, vp]
+    L.fi_plan_describe.argtypes = [vp, C.c_char_p, C.c_uint64]
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_detect_correct.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_classify.argtypes = [vp, vp, C.c_uint32, vp, vp, vp]
@@ -161,6 +162,11 @@ class Plan:
 
     def tune(self, tile_config=-1, trial_group=-1, stream=None):
         _check(lib().fi_plan_tune(self._h, tile_config, trial_group, _stream(stream)))
+
+    def describe(self):
+        buf = C.create_string_buffer(512)
+        _check(lib().fi_plan_describe(self._h, buf, len(buf)))
+        return buf.value.decode()
 
     def fi_gemm_inject_batch(self, d_faults, n_trials, policy, d_results, d_c_out=None, stream=None):
         _check(lib().fi_gemm_inject_batch(self._h, _dptr(d_faults), n_trials, policy, _dptr(d_results),

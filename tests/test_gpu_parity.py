@@ -250,6 +250,24 @@ def test_nonfinite_operands_are_a_plan_error():
     assert e.value.status == fi.INVALID_ARG
 
 
+def test_plan_describe_names_the_kernels_in_use():
+    Aw, Bw = wl.gaussian(128, 128, 128, orc.BF16, seed=2)
+    plan = gu.make_plan(Aw, Bw, 64, orc.BF16)
+    assert "gemm_fi_multi_kernel<bf16, R=8, 128x64" in plan.describe()
+    plan.tune(1)
+    assert plan.describe() == "gemm_fi_kernel<bf16, 128x128, 256 threads>"
+    plan.tune(3)
+    assert "R=4, 128x128" in plan.describe()
+    plan.destroy()
+    Aw, Bw = wl.gaussian(64, 64, 96, orc.FP16, seed=2)        # K % 64 != 0: one-trial kernel only
+    plan = gu.make_plan(Aw, Bw, 32, orc.FP16)
+    assert plan.describe().startswith("gemm_fi_kernel<fp16")
+    with pytest.raises(fi.FiError) as e:
+        plan.tune(5)
+    assert e.value.status == fi.UNSUPPORTED
+    plan.destroy()
+
+
 @pytest.mark.parametrize("N", [136, 130])
 def test_standalone_detector_equals_fused_epilogue_and_oracle(N):
     import torch
