@@ -62,12 +62,19 @@ def cpu_baseline(w, budget_s=15.0):
     rows = int(min(w.M, max(probe_rows, probe_rows * budget_s / max(t_probe, 1e-6))))
     rows = max(cores, rows // cores * cores)
     t = slab_time(rows) if rows > probe_rows else t_probe
+    reps = 1
+    if rows == w.M and t < 0.7 * budget_s:          # a whole pass is quick: time several
+        reps = int(budget_s / t)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            slab_time(rows)
+        t = (time.perf_counter() - t0) / reps
     flops = 2.0 * rows * w.N * w.K
     t_trial = t * w.M / rows
     return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "trials_per_s": 1.0 / t_trial,
-            "sample": "rows 0..%d of one fault-free %dx%dx%d pass (%.1f s), scaled by M/%d to a whole trial"
-                      % (rows - 1, w.M, w.N, w.K, t, rows)}
+            "sample": "rows 0..%d of a fault-free %dx%dx%d pass, %d time(s), %.1f s each, scaled by M/%d to a whole trial"
+                      % (rows - 1, w.M, w.N, w.K, reps, t, rows)}
 
 
 def main():
