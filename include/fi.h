@@ -130,9 +130,9 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
  *         (every fault kind, any K);
  *   3..5  R trials per workgroup sharing one staged operand tile: R=4 on 128x128,
  *         R=2 on 256x128, R=8 on 128x64 (the default when K % 64 == 0).  These take
- *         the fault-free trials and the accumulator faults whose k-block ends on a
- *         multiple of 64; the library routes every other trial of the batch to the
- *         one-trial kernel.  FI_UNSUPPORTED if K % 64 != 0.
+ *         the fault-free trials and the accumulator faults; the library routes the
+ *         operand-fault trials of the batch to the one-trial kernel.
+ *         FI_UNSUPPORTED if K % 64 != 0.
  * trial_group: -1 keep, else how many trials (groups of R trials) of the same
  * output tile are scheduled next to each other, 1..4096.  Results do not depend on
  * either (every shape accumulates each element in the same order); `stream` is unused. */

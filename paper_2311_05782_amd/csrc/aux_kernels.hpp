@@ -172,9 +172,9 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
   }
 }
 
-// Splits a batch: trials the multi-trial GEMM kernel can take (no fault, or an accumulator flip
-// at the end of a 64-wide k-tile; out-of-range sites count as "no fault") go to the front of
-// perm in list order, all others (operand faults, flips inside a k-tile) behind them.
+// Splits a batch: trials the multi-trial GEMM kernel can take (no fault, or an accumulator
+// flip; out-of-range sites count as "no fault") go to the front of perm in list order, all
+// others (operand faults) behind them.
 // counts = {front, back}.  One workgroup; each thread owns a contiguous chunk of the list.
 __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* __restrict__ f, uint32_t n,
                                                                uint32_t M, uint32_t N, uint32_t K, uint32_t kb,
@@ -188,7 +188,7 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
     const fi_fault x = f[t];
     if (x.kind == FI_SITE_ACC) {
       const bool valid = x.row < M && x.col < N && x.kblock < K / kb;
-      return !valid || ((x.kblock + 1) * kb) % 64 == 0;
+      return true;   // any k-block boundary is an MFMA-step boundary
     }
     if (x.kind == FI_SITE_A) return !(x.row < M && x.col < K);
     if (x.kind == FI_SITE_B) return !(x.row < K && x.col < N);

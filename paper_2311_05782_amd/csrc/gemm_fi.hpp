@@ -117,9 +117,11 @@ __device__ __forceinline__ float finite_or_inf(float d) {
 // round-robin to the 8 XCDs, each with its own L2; give every XCD one contiguous slice of the
 // work list, and order the list so that `group` consecutive entries are the SAME tile for
 // different items: the CUs of an XCD then stream the same A and B panels through that XCD's L2
-// at the same time.  The grid holds n_tiles * n_items workgroups.
-__device__ __forceinline__ void work_of_block(int n_tiles, int n_items, int group, int& tile, int& item) {
-  uint32_t w = blockIdx.x, total = gridDim.x;
+// at the same time.  The list holds n_tiles * n_items entries; n_items may be a count only the
+// device knows, so the grid may be larger: returns false for a workgroup beyond the list.
+__device__ __forceinline__ bool work_of_block(int n_tiles, int n_items, int group, int& tile, int& item) {
+  uint32_t w = blockIdx.x, total = (uint32_t)n_tiles * (uint32_t)n_items;
+  if (w >= total) return false;
   uint32_t per = total >> 3;
   uint32_t L = (w < per * 8u) ? (w & 7u) * per + (w >> 3) : w;
   uint32_t G = (uint32_t)min(group, n_items), ntiles = (uint32_t)n_tiles;
@@ -135,6 +137,7 @@ __device__ __forceinline__ void work_of_block(int n_tiles, int n_items, int grou
     item = (int)(full + L % G2);
     tile = (int)(L / G2);
   }
+  return true;
 }
 
 template <int DT, int BM, int BN, int WM, int WN, int MODE>
@@ -155,12 +158,14 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   const int l32 = lane & 31, lhi = lane >> 5;
 
   int tile, trial;
-  work_of_block(p.tiles_m * p.tiles_n, p.n_trials, p.group, tile, trial);
   if constexpr (MODE == MODE_CAMPAIGN) {
-    if (p.perm) {   // only the trials the multi-trial kernel left: positions c0 .. c0+c1 of perm
-      if (trial >= (int)p.part_counts[1]) return;      // uniform, before any barrier
-      trial = (int)p.perm[p.part_counts[0] + (uint32_t)trial];
-    }
+    // With a permutation: only the trials the multi-trial kernel left, positions c0 .. c0+c1.
+    const int n_mine = p.perm ? (int)p.part_counts[1] : p.n_trials;
+    if (n_mine == 0 || !work_of_block(p.tiles_m * p.tiles_n, n_mine, p.group, tile, trial))
+      return;                                          // uniform, before any barrier
+    if (p.perm) trial = (int)p.perm[p.part_counts[0] + (uint32_t)trial];
+  } else {
+    work_of_block(p.tiles_m * p.tiles_n, p.n_trials, p.group, tile, trial);
   }
   const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;

@@ -8,9 +8,9 @@
 // ds_read_b128 per MFMA both fall by the factor the tile shrinks less than R grows
 // (R = 4 on a 128x128 tile: half the bytes per flop of one 256x256 tile per trial).
 //
-// Handles trials whose fault is NONE or an accumulator flip that falls on a 64-wide k-tile
-// boundary, on problems with K % 64 == 0.  The library's partition kernel routes every other
-// trial (operand faults, flips inside a k-tile) to gemm_fi_kernel.
+// Handles trials whose fault is NONE or an accumulator flip (k-blocks are multiples of the
+// 16-wide MFMA step, so every flip falls between two steps), on problems with K % 64 == 0.
+// The library's partition kernel routes every other trial (operand faults) to gemm_fi_kernel.
 //
 // The per-element arithmetic is that of gemm_fi_kernel: the same sequence of
 // v_mfma_f32_32x32x16 steps in ascending k, hence bit-identical fault-free results.
@@ -42,22 +42,25 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
 
   // ---- work: (tile, group of R eligible trials)
   const int n_fast = (int)p.part_counts[0];
-  const int n_groups_max = (p.n_trials + R - 1) / R;
+  const int n_groups = (n_fast + R - 1) / R;           // the grid covers ceil(n_trials / R)
   int tile, grp;
-  work_of_block(p.tiles_m * p.tiles_n, n_groups_max, p.group, tile, grp);
-  if (grp * R >= n_fast) return;                       // uniform: this group holds no trial
+  if (n_groups == 0 || !work_of_block(p.tiles_m * p.tiles_n, n_groups, p.group, tile, grp))
+    return;                                            // uniform: beyond the list
   const int n_act = min(R, n_fast - grp * R);
   const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   // ---- per trial (all uniform): index, and for the wave that owns an accumulator site the
-  // k-tile after which it flips.  Site details are re-derived from the fault when needed.
-  int trial[R], hook_kt[R];
+  // 16-wide MFMA step after which it flips.  Site details are re-derived from the fault when
+  // needed.  next_hook is the earliest such step: the main loop tests one scalar per step.
+  constexpr int NO_HOOK = 0x7fffffff;
+  int next_hook = NO_HOOK;
+  int trial[R], hook_step[R];
   uint32_t affected = 0;                               // bit r: this tile holds trial r's site
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     trial[r] = (int)p.perm[grp * R + min(r, n_act - 1)];
-    hook_kt[r] = -1;
+    hook_step[r] = -1;
     if (r < n_act) {
       const fi_fault f = p.faults[trial[r]];
       const bool is_acc = f.kind == FI_SITE_ACC;
@@ -70,7 +73,10 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
           affected |= 1u << r;
           const int wi = li - wm * WTM, wj = lj - wn * WTN;
-          if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) hook_kt[r] = ((int)f.kblock + 1) * p.kb / BK - 1;
+          if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
+            hook_step[r] = ((int)f.kblock + 1) * p.kb / 16 - 1;
+            next_hook = min(next_hook, hook_step[r]);
+          }
         }
       }
     }
@@ -165,6 +171,18 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   };
 
+  // Accumulator faults due after MFMA step g (at most one wave per trial owns one).
+  auto hooks = [&](int g) __attribute__((always_inline)) {
+    if (g == next_hook) {
+      int nxt = NO_HOOK;
+      static_for<R>([&](auto rr) {
+        if (hook_step[rr] == g) accumulator_fault(rr);
+        else if (hook_step[rr] > g) nxt = min(nxt, hook_step[rr]);
+      });
+      next_hook = nxt;
+    }
+  };
+
   // ---- main loop: double-buffered LDS, one barrier per k-tile.  The barrier sits before the
   // last of the four MFMA steps of a tile: by then a wave holds the tile's last fragments in
   // registers, so right after the barrier it reads the first fragments of the next tile while
@@ -186,13 +204,16 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     mma_step(f0);
     __builtin_amdgcn_sched_barrier(0);
     read_frags(f0, s, 2);
+    hooks(4 * kt);
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f1);
     __builtin_amdgcn_sched_barrier(0);
     read_frags(f1, s, 3);
+    hooks(4 * kt + 1);
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f0);
     __builtin_amdgcn_sched_barrier(0);
+    hooks(4 * kt + 2);
     // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
     // once all waves are here the next tile has landed and this stage may be overwritten.
     if (more) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
@@ -201,10 +222,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f1);
     __builtin_amdgcn_sched_barrier(0);
-    // accumulator faults that fall at the end of this k-tile (at most one wave per trial)
-    static_for<R>([&](auto rr) {
-      if (kt == hook_kt[rr]) accumulator_fault(rr);
-    });
+    hooks(4 * kt + 3);
   }
 
   // ---- epilogue, trial by trial: detector, corrector, optional store; deviation counters where
