@@ -129,7 +129,7 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
  *   0..2  one trial per workgroup on a 256x256, 128x128 or 256x64 output tile
  *         (every fault kind, any K);
  *   3..5  R trials per workgroup sharing one staged operand tile: R=4 on 128x128,
- *         R=2 on 256x128, R=8 on 128x64 (the default when K % 64 == 0).  These take
+ *         R=2 on 128x128, R=8 on 128x64 (the default when K % 64 == 0).  These take
  *         the fault-free trials and the accumulator faults; the library routes the
  *         operand-fault trials of the batch to the one-trial kernel.
  *         FI_UNSUPPORTED if K % 64 != 0.

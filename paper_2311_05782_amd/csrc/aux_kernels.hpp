@@ -173,29 +173,31 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
 }
 
 // Splits a batch: trials the multi-trial GEMM kernel can take (no fault, or an accumulator
-// flip; out-of-range sites count as "no fault") go to the front of perm in list order, all
-// others (operand faults) behind them.
-// counts = {front, back}.  One workgroup; each thread owns a contiguous chunk of the list.
+// flip; out-of-range sites count as "no fault" and get status 1 in their zeroed record) go to
+// the front of perm in list order, all others (operand faults) behind them.
+// counts = {front, back}.  For front position q, desc[5q..5q+4] = {trial, row, col, step, mask}:
+// step = the 16-wide MFMA step after which the accumulator flips, (s+1)*kb/16 - 1, or -1 for no
+// fault.  desc is padded with fault-free entries up to the next multiple of 8 positions.
+// One workgroup; each thread owns a contiguous chunk of the list.
 __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* __restrict__ f, uint32_t n,
                                                                uint32_t M, uint32_t N, uint32_t K, uint32_t kb,
                                                                uint32_t* __restrict__ perm,
-                                                               uint32_t* __restrict__ counts) {
+                                                               uint32_t* __restrict__ counts,
+                                                               uint32_t* __restrict__ desc,
+                                                               fi_trial_result* __restrict__ results) {
   __shared__ uint32_t offs[1024];
   __shared__ uint32_t total_fast;
   const uint32_t chunk = (n + 1023) / 1024;
   const uint32_t lo = min(threadIdx.x * chunk, n), hi = min(lo + chunk, n);
-  auto fast = [&](uint32_t t) {
-    const fi_fault x = f[t];
-    if (x.kind == FI_SITE_ACC) {
-      const bool valid = x.row < M && x.col < N && x.kblock < K / kb;
-      return true;   // any k-block boundary is an MFMA-step boundary
-    }
-    if (x.kind == FI_SITE_A) return !(x.row < M && x.col < K);
-    if (x.kind == FI_SITE_B) return !(x.row < K && x.col < N);
-    return true;   // NONE and unknown kinds run fault-free
+  // 0: operand fault (other kernel); 1: runs fault-free; 2: accumulator flip; 3: bad site
+  auto kind_of = [&](const fi_fault& x) -> int {
+    if (x.kind == FI_SITE_ACC) return (x.row < M && x.col < N && x.kblock < K / kb) ? 2 : 3;
+    if (x.kind == FI_SITE_A) return (x.row < M && x.col < K) ? 0 : 3;
+    if (x.kind == FI_SITE_B) return (x.row < K && x.col < N) ? 0 : 3;
+    return x.kind == FI_SITE_NONE ? 1 : 3;
   };
   uint32_t c = 0;
-  for (uint32_t t = lo; t < hi; ++t) c += fast(t) ? 1u : 0u;
+  for (uint32_t t = lo; t < hi; ++t) c += kind_of(f[t]) != 0 ? 1u : 0u;
   offs[threadIdx.x] = c;
   __syncthreads();
   if (threadIdx.x == 0) {            // 1024 additions: negligible next to the batch itself
@@ -210,7 +212,22 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
   const uint32_t n_fast = total_fast;
   uint32_t ps = n_fast + (lo - pf);                      // slow trials before my chunk, after the front
   for (uint32_t t = lo; t < hi; ++t) {
-    if (fast(t)) perm[pf++] = t; else perm[ps++] = t;
+    const fi_fault x = f[t];
+    const int k = kind_of(x);
+    if (k == 0) { perm[ps++] = t; continue; }
+    uint32_t* d = desc + (size_t)pf * 5;
+    d[0] = t; d[1] = x.row; d[2] = x.col;
+    d[3] = k == 2 ? (x.kblock + 1) * kb / 16 - 1 : 0xFFFFFFFFu;
+    d[4] = x.xor_mask;
+    if (k == 3) results[t].status = 1;
+    perm[pf++] = t;
+  }
+  if (threadIdx.x < 8) {
+    const uint32_t q = n_fast + threadIdx.x;
+    if (q < ((n_fast + 7u) & ~7u)) {
+      uint32_t* d = desc + (size_t)q * 5;
+      d[0] = 0; d[1] = 0; d[2] = 0; d[3] = 0xFFFFFFFFu; d[4] = 0;
+    }
   }
 }
 

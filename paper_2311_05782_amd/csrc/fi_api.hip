@@ -49,7 +49,7 @@ constexpr int kNumCfg = sizeof(kCfg) / sizeof(kCfg[0]);
 struct MultiCfg { int r, bm, bn, wm, wn; };
 constexpr MultiCfg kMulti[] = {
     {4, 128, 128, 4, 2},   // each wave 32 x 64 for 4 trials
-    {2, 256, 128, 4, 2},   // each wave 64 x 64 for 2 trials
+    {2, 128, 128, 4, 2},   // each wave 32 x 64 for 2 trials
     {8, 128, 64, 4, 2},    // each wave 32 x 32 for 8 trials: narrow outputs
 };
 constexpr int kNumMulti = sizeof(kMulti) / sizeof(kMulti[0]);
@@ -74,7 +74,9 @@ struct fi_plan {
   int group;               // trials sharing a tile back to back
   int device;
   uint32_t* perm;          // [perm_cap] trial order of the current batch + 2 counters behind it
+  uint32_t* desc;          // [(perm_cap + 8) * 5] descriptors of the multi-trial kernel's trials
   uint32_t perm_cap;
+  int n_cus;               // compute units of the device: grid of the persistent kernel
 };
 
 namespace {
@@ -204,6 +206,7 @@ void free_plan_buffers(fi_plan* p) {
   if (p->cb) (void)hipFree(p->cb);
   if (p->scratch) (void)hipFree(p->scratch);
   if (p->perm) (void)hipFree(p->perm);
+  if (p->desc) (void)hipFree(p->desc);
 }
 
 size_t padded(uint32_t n) { return ((size_t)n + PAD - 1) / PAD * PAD; }
@@ -329,6 +332,9 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   p->mcfg = pick_multi(d);
   p->group = 32;
   (void)hipGetDevice(&p->device);
+  if (hipDeviceGetAttribute(&p->n_cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess ||
+      p->n_cus < 8)
+    p->n_cus = 8;
   st = build_plan(p, d_A, d_B, as_stream(stream));
   if (st != FI_OK) {
     (void)hipStreamSynchronize(as_stream(stream));
@@ -424,23 +430,30 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
     // k-tile boundary share staged operands R at a time; the rest take the single-trial kernel.
     if (plan->perm_cap < n_trials) {
       if (plan->perm) (void)hipFree(plan->perm);     // waits for work that may still read it
-      plan->perm = nullptr; plan->perm_cap = 0;
+      if (plan->desc) (void)hipFree(plan->desc);
+      plan->perm = nullptr; plan->desc = nullptr; plan->perm_cap = 0;
       FI_HIP(hipMalloc(&plan->perm, ((size_t)n_trials + 2) * sizeof(uint32_t)));
+      FI_HIP(hipMalloc(&plan->desc, ((size_t)n_trials + 8) * fi::kMultiDescWords * sizeof(uint32_t)));
       plan->perm_cap = n_trials;
     }
     uint32_t* counts = plan->perm + plan->perm_cap;
     hipLaunchKernelGGL(fi::partition_trials_kernel, dim3(1), dim3(1024), 0, s, d_faults, n_trials, plan->d.M,
-                       plan->d.N, plan->d.K, plan->d.k_block, plan->perm, counts);
+                       plan->d.N, plan->d.K, plan->d.k_block, plan->perm, counts, plan->desc, d_results);
     FI_HIP(hipGetLastError());
     a.perm = plan->perm;
     a.part_counts = counts;
+    a.desc = plan->desc;
     const MultiCfg mc = kMulti[plan->mcfg];
     GemmArgs m = a;
     m.tiles_m = (a.M + mc.bm - 1) / mc.bm;
     m.tiles_n = (a.N + mc.bn - 1) / mc.bn;
+    // Persistent workgroups, one per CU (the register budget admits no more), each walking the
+    // work list with the grid as stride; a multiple of 8 keeps a workgroup's items on one XCD.
     const uint64_t groups = ((uint64_t)n_trials + mc.r - 1) / mc.r;
-    const uint64_t mblocks = (uint64_t)m.tiles_m * m.tiles_n * groups;
-    if (mblocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
+    const uint64_t items = (uint64_t)m.tiles_m * m.tiles_n * groups;
+    if (items >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 work items; split the batch");
+    const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8);
+    const uint64_t mblocks = items < cus ? items : cus;
     FI_HIP(launch_multi((int)plan->d.dtype, plan->mcfg, m, (int)mblocks, s));
   }
   FI_HIP(launch_gemm<fi::MODE_CAMPAIGN>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));

@@ -66,6 +66,8 @@ struct GemmArgs {
   // part_counts = {c0, c1}.
   const uint32_t* perm;
   const uint32_t* part_counts;
+  // For the multi-trial kernel: 5 words per position of perm[0 .. c0), see gemm_fi_multi.hpp.
+  const uint32_t* desc;
 };
 
 template <int DT>
@@ -117,11 +119,12 @@ __device__ __forceinline__ float finite_or_inf(float d) {
 // round-robin to the 8 XCDs, each with its own L2; give every XCD one contiguous slice of the
 // work list, and order the list so that `group` consecutive entries are the SAME tile for
 // different items: the CUs of an XCD then stream the same A and B panels through that XCD's L2
-// at the same time.  The list holds n_tiles * n_items entries; n_items may be a count only the
-// device knows, so the grid may be larger: returns false for a workgroup beyond the list.
-__device__ __forceinline__ bool work_of_block(int n_tiles, int n_items, int group, int& tile, int& item) {
-  uint32_t w = blockIdx.x, total = (uint32_t)n_tiles * (uint32_t)n_items;
-  if (w >= total) return false;
+// at the same time.  The list holds total = n_tiles * n_items entries; w is a position in
+// dispatch order (a workgroup id, or a persistent workgroup's id plus a multiple of a grid
+// size divisible by 8).  n_items may be a count only the device knows, so a grid may be
+// larger than the list: work_of_block returns false for a workgroup beyond it.
+__device__ __forceinline__ void work_of_index(uint32_t w, uint32_t total, int n_tiles, int n_items, int group,
+                                              int& tile, int& item) {
   uint32_t per = total >> 3;
   uint32_t L = (w < per * 8u) ? (w & 7u) * per + (w >> 3) : w;
   uint32_t G = (uint32_t)min(group, n_items), ntiles = (uint32_t)n_tiles;
@@ -137,6 +140,11 @@ __device__ __forceinline__ bool work_of_block(int n_tiles, int n_items, int grou
     item = (int)(full + L % G2);
     tile = (int)(L / G2);
   }
+}
+__device__ __forceinline__ bool work_of_block(int n_tiles, int n_items, int group, int& tile, int& item) {
+  const uint32_t total = (uint32_t)n_tiles * (uint32_t)n_items;
+  if (blockIdx.x >= total) return false;
+  work_of_index(blockIdx.x, total, n_tiles, n_items, group, tile, item);
   return true;
 }
 

@@ -1,4 +1,4 @@
-// Fault-injecting GEMM, R trials per workgroup (gfx950).
+// Fault-injecting GEMM, R trials per workgroup, persistent workgroups (gfx950).
 //
 // Every trial of a campaign multiplies the SAME operands (paper Sec. IV-A: one fault per run of
 // the unchanged application); only the accumulators differ once a fault has been applied.  So a
@@ -6,11 +6,20 @@
 // them to R independent accumulator sets - one per trial.  Each trial still executes all of its
 // 2*M*N*K flops on the matrix cores; what is shared is operand traffic: L2 -> LDS bytes and
 // ds_read_b128 per MFMA both fall by the factor the tile shrinks less than R grows
-// (R = 4 on a 128x128 tile: half the bytes per flop of one 256x256 tile per trial).
+// (R = 8 on a 128x64 tile: 3/8 of the bytes per flop of one 256x256 tile per trial).
 //
 // Handles trials whose fault is NONE or an accumulator flip (k-blocks are multiples of the
 // 16-wide MFMA step, so every flip falls between two steps), on problems with K % 64 == 0.
-// The library's partition kernel routes every other trial (operand faults) to gemm_fi_kernel.
+// The library's partition kernel routes every other trial (operand faults) to gemm_fi_kernel
+// and writes, for the trials this kernel takes, one 5-word descriptor each in list order:
+// {trial, row, col, MFMA step after which the accumulator flips or -1, xor mask}.
+//
+// Work item = (output tile, group of R trials).  The register budget (R*TM*TN*16 accumulator
+// VGPRs per lane) admits one workgroup per CU, so nothing would hide a workgroup's start-up
+// (descriptor fetch, first operand tile) or wind-down behind another's MFMAs.  Instead the grid
+// is one workgroup per CU and each walks its items with the k-loop running straight through:
+// during the last k-tile of an item the first k-tile of the next item is already loading into
+// the free LDS stage, and the next item's descriptors were fetched an item earlier.
 //
 // The per-element arithmetic is that of gemm_fi_kernel: the same sequence of
 // v_mfma_f32_32x32x16 steps in ascending k, hence bit-identical fault-free results.
@@ -20,6 +29,8 @@
 
 namespace fi {
 
+constexpr int kMultiDescWords = 5;   // trial, row, col, hook step, xor mask
+
 template <int DT, int R, int BM, int BN, int WM, int WN>
 __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmArgs p) {
   constexpr int BK = 64;
@@ -28,10 +39,15 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int STAGE = (BM + BN) * 128;
   constexpr int A_G = BM / 8 / NW, B_G = BN / 8 / NW;      // 8-row groups staged per wave
+  constexpr int NO_HOOK = 0x7fffffff;
+  // Fetch the epilogue's threshold inputs when an item starts (hides their latency) where the
+  // register budget has room for them; else when the epilogue starts.
+  constexpr bool EARLY_T = TM * TN == 1;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a multiple of the 32x32 MFMA");
   static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "row groups divide among the waves");
   static_assert(R * TM * TN * 16 <= 128, "accumulators fit half the register file");
   static_assert(2 * STAGE <= 160 * 1024, "two stages fit the 160 KB LDS");
+  static_assert(R * kMultiDescWords <= 64, "a group's descriptors fit one word per lane");
 
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * STAGE];
 
@@ -40,73 +56,52 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, lhi = lane >> 5;
 
-  // ---- work: (tile, group of R eligible trials)
+  // ---- work list: n_tiles x ceil(n_fast / R) items, walked with the grid as stride
   const int n_fast = (int)p.part_counts[0];
-  const int n_groups = (n_fast + R - 1) / R;           // the grid covers ceil(n_trials / R)
-  int tile, grp;
-  if (n_groups == 0 || !work_of_block(p.tiles_m * p.tiles_n, n_groups, p.group, tile, grp))
-    return;                                            // uniform: beyond the list
-  const int n_act = min(R, n_fast - grp * R);
-  const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  // ---- per trial (all uniform): index, and for the wave that owns an accumulator site the
-  // 16-wide MFMA step after which it flips.  Site details are re-derived from the fault when
-  // needed.  next_hook is the earliest such step: the main loop tests one scalar per step.
-  constexpr int NO_HOOK = 0x7fffffff;
-  int next_hook = NO_HOOK;
-  int trial[R], hook_step[R];
-  uint32_t affected = 0;                               // bit r: this tile holds trial r's site
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    trial[r] = (int)p.perm[grp * R + min(r, n_act - 1)];
-    hook_step[r] = -1;
-    if (r < n_act) {
-      const fi_fault f = p.faults[trial[r]];
-      const bool is_acc = f.kind == FI_SITE_ACC;
-      const bool valid = f.kind == FI_SITE_NONE ||
-                         (is_acc && f.row < (uint32_t)p.M && f.col < (uint32_t)p.N &&
-                          f.kblock < (uint32_t)(p.K / p.kb));
-      if (!valid && tile == 0 && tid == 0) p.results[trial[r]].status = 1;   // runs fault-free
-      if (is_acc && valid) {
-        const int li = (int)f.row - m0, lj = (int)f.col - n0;
-        if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
-          affected |= 1u << r;
-          const int wi = li - wm * WTM, wj = lj - wn * WTN;
-          if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
-            hook_step[r] = ((int)f.kblock + 1) * p.kb / 16 - 1;
-            next_hook = min(next_hook, hook_step[r]);
-          }
-        }
-      }
-    }
-  }
+  const int n_groups = (n_fast + R - 1) / R;
+  const uint32_t n_work = (uint32_t)(p.tiles_m * p.tiles_n) * (uint32_t)n_groups;
+  uint32_t w_cur = blockIdx.x;
+  if (w_cur >= n_work) return;                            // uniform, before any barrier
 
   // ---- staging: global -> LDS directly, as in gemm_fi_kernel
   const int lrow = lane >> 3, lslot = lane & 7;
-  uint32_t a_goff[A_G], b_goff[B_G];
-#pragma unroll
-  for (int c = 0; c < A_G; ++c) {
-    const int row = (wave * A_G + c) * 8 + lrow;
-    a_goff[c] = (uint32_t)min(m0 + row, p.M - 1) * p.lda + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
-  }
-#pragma unroll
-  for (int c = 0; c < B_G; ++c) {
-    const int row = (wave * B_G + c) * 8 + lrow;
-    b_goff[c] = (uint32_t)min(n0 + row, p.N - 1) * p.ldb + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
-  }
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void glb_void;
-  auto issue_tile = [&](int kt, int stage) {
+
+  struct Item {
+    int m0, n0, grp;
+    uint32_t a_goff[A_G], b_goff[B_G];
+  };
+  auto locate = [&](uint32_t w, Item& it) {
+    int tile;
+    work_of_index(w, n_work, p.tiles_m * p.tiles_n, n_groups, p.group, tile, it.grp);
+    it.m0 = (tile / p.tiles_n) * BM;
+    it.n0 = (tile % p.tiles_n) * BN;
+#pragma unroll
+    for (int c = 0; c < A_G; ++c) {
+      const int row = (wave * A_G + c) * 8 + lrow;
+      it.a_goff[c] = (uint32_t)min(it.m0 + row, p.M - 1) * p.lda + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
+    }
+#pragma unroll
+    for (int c = 0; c < B_G; ++c) {
+      const int row = (wave * B_G + c) * 8 + lrow;
+      it.b_goff[c] = (uint32_t)min(it.n0 + row, p.N - 1) * p.ldb + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
+    }
+  };
+  auto issue_tile = [&](const Item& it, int kt, int stage) {
     const int k0 = kt * BK;
     uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
     uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
 #pragma unroll
     for (int c = 0; c < A_G; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + a_goff[c] + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + it.a_goff[c] + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
 #pragma unroll
     for (int c = 0; c < B_G; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + it.b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
+  };
+  // A group's R descriptors, one word per lane; fields are picked out with v_readlane.
+  auto load_desc = [&](int grp) -> uint32_t {
+    return lane < R * kMultiDescWords ? p.desc[(size_t)grp * (R * kMultiDescWords) + lane] : 0u;
   };
 
   // ---- fragments and accumulators
@@ -115,10 +110,6 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   const int b_rd = BM * 128 + (wn * WTN + l32) * 128;
 
   f32x16 acc[R][TM][TN];
-  static_for<R * TM * TN>([&](auto t) {
-    acc[t / (TM * TN)][(t / TN) % TM][t % TN] =
-        f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  });
 
   struct Frags { u32x4 a[TM]; u32x4 b[TN]; };
   auto read_frags = [&](Frags& f, const uint8_t* s, int kk) {
@@ -136,17 +127,50 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     });
   };
 
-  // Accumulator flip of trial r (this wave owns its site).  The site is re-read from the fault:
-  // this runs once per trial in the whole grid.
+  // ---- state of the current item
+  Item cur, nxt;
+  uint32_t desc_cur, desc_nxt = 0;                       // lane-distributed descriptor words
+  int n_act = 0;                                         // trials in this group
+  int trial[R], hook_step[R];                            // hook_step: -1 unless this wave owns the site
+  uint32_t affected = 0;                                 // bit r: this tile holds trial r's site
+  int next_hook = NO_HOOK;                               // earliest pending hook step of this wave
+
+  auto desc_field = [&](int r, int field) -> uint32_t {
+    return (uint32_t)__builtin_amdgcn_readlane((int)desc_cur, r * kMultiDescWords + field);
+  };
+  auto decode = [&]() {
+    n_act = min(R, n_fast - cur.grp * R);
+    affected = 0;
+    next_hook = NO_HOOK;
+    static_for<R>([&](auto rr) {
+      constexpr int r = rr;
+      trial[r] = (int)desc_field(r, 0);
+      hook_step[r] = -1;
+      const int hs = (int)desc_field(r, 3);
+      if (r < n_act && hs >= 0) {
+        const int li = (int)desc_field(r, 1) - cur.m0, lj = (int)desc_field(r, 2) - cur.n0;
+        if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
+          affected |= 1u << r;
+          const int wi = li - wm * WTM, wj = lj - wn * WTN;
+          if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
+            hook_step[r] = hs;
+            next_hook = min(next_hook, hs);
+          }
+        }
+      }
+    });
+  };
+
+  // Accumulator flip of trial r (this wave owns its site); once per trial in the whole grid.
   auto accumulator_fault = [&](auto rr) {
     constexpr int r = rr;
-    const fi_fault f = p.faults[trial[r]];
-    const int wi = (int)f.row - m0 - wm * WTM, wj = (int)f.col - n0 - wn * WTN;
+    const int wi = (int)desc_field(r, 1) - cur.m0 - wm * WTM, wj = (int)desc_field(r, 2) - cur.n0 - wn * WTN;
+    const uint32_t xor_mask = desc_field(r, 4);
     const int ri = wi & 31, rj = wj & 31;
     const int sel_t = (wi >> 5) * TN + (wj >> 5);
     const int sel_v = 4 * (ri >> 3) + (ri & 3);
     const int sel_lane = rj + 32 * ((ri >> 2) & 1);
-    const uint32_t lane_mask = (lane == sel_lane) ? f.xor_mask : 0u;
+    const uint32_t lane_mask = (lane == sel_lane) ? xor_mask : 0u;
     uint32_t before = 0;
     static_for<TM * TN>([&](auto tt) {
       constexpr int i = tt / TN, j = tt % TN;
@@ -164,131 +188,122 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     });
     if (lane == sel_lane) {
       p.results[trial[r]].site_word_before = before;
-      p.results[trial[r]].site_word_after = before ^ f.xor_mask;
+      p.results[trial[r]].site_word_after = before ^ xor_mask;
     }
-    // Leave nothing of this rare path in flight: the compiler places its waits statically, and a
-    // load pending here would make every iteration of the main loop wait for its own prefetch.
+    // Leave nothing of this rare path in flight: the compiler places its waits statically, and
+    // memory traffic pending here would make every iteration of the main loop wait for it.
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   };
-
-  // Accumulator faults due after MFMA step g (at most one wave per trial owns one).
+  // Accumulator faults due after MFMA step g of the item (at most one wave per trial owns one).
   auto hooks = [&](int g) __attribute__((always_inline)) {
     if (g == next_hook) {
-      int nxt = NO_HOOK;
+      int later = NO_HOOK;
       static_for<R>([&](auto rr) {
         if (hook_step[rr] == g) accumulator_fault(rr);
-        else if (hook_step[rr] > g) nxt = min(nxt, hook_step[rr]);
+        else if (hook_step[rr] > g) later = min(later, hook_step[rr]);
       });
-      next_hook = nxt;
+      next_hook = later;
     }
   };
 
-  // ---- main loop: double-buffered LDS, one barrier per k-tile.  The barrier sits before the
-  // last of the four MFMA steps of a tile: by then a wave holds the tile's last fragments in
-  // registers, so right after the barrier it reads the first fragments of the next tile while
-  // the matrix cores still have R*TM*TN MFMAs of this tile to issue - the LDS latency that
-  // follows a barrier is covered by work instead of idling the pipe.
-  const int nkt = p.K / BK;
-  issue_tile(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-  __syncthreads();
-  Frags f0, f1;
-  read_frags(f0, smem, 0);
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int stage = kt & 1;
-    const bool more = kt + 1 < nkt;
-    if (more) issue_tile(kt + 1, stage ^ 1);
-    const uint8_t* s = smem + stage * STAGE;
-    read_frags(f1, s, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step(f0);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(f0, s, 2);
-    hooks(4 * kt);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step(f1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(f1, s, 3);
-    hooks(4 * kt + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step(f0);
-    __builtin_amdgcn_sched_barrier(0);
-    hooks(4 * kt + 2);
-    // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
-    // once all waves are here the next tile has landed and this stage may be overwritten.
-    if (more) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
-    __syncthreads();
-    if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step(f1);
-    __builtin_amdgcn_sched_barrier(0);
-    hooks(4 * kt + 3);
-  }
-
-  // ---- epilogue, trial by trial: detector, corrector, optional store; deviation counters where
-  // the trial's fault can reach.  Thresholds are the same for every trial (same rows and
-  // columns), so they are formed once; elements outside the problem get T = +Inf and, in ragged
-  // tiles, a zeroed accumulator (clamped staging rows made them copies of the last row).
-  const int row_base = m0 + wm * WTM + 4 * lhi;       // + 32*i + 8*q + e
-  const int col_base = n0 + wn * WTN + l32;           // + 32*j
-  const bool ragged = m0 + BM > p.M || n0 + BN > p.N;
-  f32x16 T[TM * TN];
-  static_for<TM * TN>([&](auto tt) {
-    constexpr int i = tt / TN, j = tt % TN;
-    const int col = col_base + 32 * j;
-    const float cbj = p.cb[min(col, p.N - 1)];
+  // ---- epilogue of the current item, trial by trial: detector, corrector, optional store;
+  // deviation counters where the trial's fault can reach.  Thresholds are the same for every
+  // trial (same rows and columns), so they are formed once; elements outside the problem get
+  // T = +Inf and, in ragged tiles, a zeroed accumulator (clamped staging rows made them copies
+  // of the last row).  kra4 / cbj were fetched when the item started.
+  f32x4 kra4[TM][4];
+  float cbj[TN];
+  auto fetch_threshold_inputs = [&]() {                 // arrays are padded: no guards
+    const int row_base = cur.m0 + wm * WTM + 4 * lhi;
+    const int col_base = cur.n0 + wn * WTN + l32;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int row = row_base + 32 * i + 8 * q + e;
-        const float t = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
-        T[tt][4 * q + e] = (row < p.M && col < p.N) ? t : __builtin_inff();
+      for (int q = 0; q < 4; ++q)
+        kra4[i][q] = *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) cbj[j] = p.cb[min(col_base + 32 * j, p.N - 1)];
+  };
+  auto epilogue = [&]() {
+    const int m0 = cur.m0, n0 = cur.n0;
+    const int row_base = m0 + wm * WTM + 4 * lhi;       // + 32*i + 8*q + e
+    const int col_base = n0 + wn * WTN + l32;           // + 32*j
+    const bool ragged = m0 + BM > p.M || n0 + BN > p.N;
+    auto thresholds = [&](auto tt) {
+      constexpr int i = tt / TN, j = tt % TN;
+      const int col = col_base + 32 * j;
+      f32x16 T;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = row_base + 32 * i + 8 * q + e;
+          const float t = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[i][q][e], cbj[j]), p.gamma);
+          T[4 * q + e] = (row < p.M && col < p.N) ? t : __builtin_inff();
+        }
       }
-    }
-  });
-  if (ragged) {
-    static_for<R * TM * TN>([&](auto t) {
-      constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
-      f32x16 a = acc[r][i][j];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-        a[v] = (row < p.M && col_base + 32 * j < p.N) ? a[v] : 0.0f;
-      }
-      acc[r][i][j] = a;
-    });
-  }
-  static_for<R>([&](auto rr) {
-    constexpr int r = rr;
-    if (r < n_act) {
-      const bool aff = (affected >> r) & 1u;
-      fi_trial_result* res = p.results + trial[r];
-      float* cout = p.c_out ? p.c_out + (size_t)trial[r] * (size_t)p.M * (size_t)p.N : nullptr;
-      uint32_t n_flag = 0;                             // wave-uniform: popcounts of lane masks
-      uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
-      float mx_pre = 0.0f, mx_post = 0.0f;
-      static_for<TM * TN>([&](auto tt) {
-        constexpr int i = tt / TN, j = tt % TN;
-        const f32x16 t = acc[r][i][j];
-        const int col = col_base + 32 * j;
+      return T;
+    };
+    if (ragged) {
+      static_for<R * TM * TN>([&](auto t) {
+        constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+        f32x16 a = acc[r][i][j];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-          const float c = t[v];
-          const bool flag = !(fabsf(c) <= T[tt][v]);
-          n_flag += (uint32_t)__builtin_popcountll(__ballot(flag));
-          if (cout) {
-            float cc = c;
-            if (flag) {
-              if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
-              else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
+          a[v] = (row < p.M && col_base + 32 * j < p.N) ? a[v] : 0.0f;
+        }
+        acc[r][i][j] = a;
+      });
+    }
+    // Detector and corrector on every element of every trial: one compare per element, flags
+    // counted as popcounts of lane masks (wave-uniform).
+    uint32_t n_flag[R];
+    static_for<R>([&](auto rr) { n_flag[rr] = 0; });
+    static_for<TM * TN>([&](auto tt) {
+      constexpr int i = tt / TN, j = tt % TN;
+      const f32x16 T = thresholds(tt);
+      const int col = col_base + 32 * j;
+      static_for<R>([&](auto rr) {
+        constexpr int r = rr;
+        if (r < n_act) {
+          const f32x16 t = acc[r][i][j];
+          float* cout = p.c_out ? p.c_out + (size_t)trial[r] * (size_t)p.M * (size_t)p.N : nullptr;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+            const float c = t[v];
+            const bool flag = !(fabsf(c) <= T[v]);
+            n_flag[r] += (uint32_t)__builtin_popcountll(__ballot(flag));
+            if (cout) {
+              float cc = c;
+              if (flag) {
+                if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+                else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
+              }
+              if (row < p.M && col < p.N) cout[(size_t)row * p.N + col] = cc;
             }
-            if (row < p.M && col < p.N) cout[(size_t)row * p.N + col] = cc;
           }
         }
-        if (aff) {
+      });
+    });
+    static_for<R>([&](auto rr) {
+      constexpr int r = rr;
+      if (r < n_act && n_flag[r] != 0 && lane == 0) atomicAdd(&p.results[trial[r]].n_flagged, n_flag[r]);
+    });
+    // Deviation counters of the trials whose fault lies in this tile (rare).
+    if (affected == 0) return;
+    static_for<R>([&](auto rr) {
+      constexpr int r = rr;
+      if ((affected >> r) & 1u) {
+        fi_trial_result* res = p.results + trial[r];
+        uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
+        float mx_pre = 0.0f, mx_post = 0.0f;
+        static_for<TM * TN>([&](auto tt) {
+          constexpr int i = tt / TN, j = tt % TN;
+          const f32x16 T = thresholds(tt);
+          const f32x16 t = acc[r][i][j];
+          const int col = col_base + 32 * j;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
@@ -297,7 +312,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
               const size_t idx = (size_t)row * p.N + col;
               const float cs = p.c_star[idx];
               const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
-              const float Tv = T[tt][v];
+              const float Tv = T[v];
               const bool flag = !(fabsf(c) <= Tv);
               float cc = c;
               if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
@@ -316,10 +331,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
               n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
             }
           }
-        }
-      });
-      if (n_flag != 0 && lane == 0) atomicAdd(&res->n_flagged, n_flag);
-      if (aff) {
+        });
         uint32_t sum;
         sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&res->n_bitdiff, sum);
         sum = wave_sum(n_pre);  if (lane == 0 && sum) atomicAdd(&res->n_dev_pre, sum);
@@ -331,8 +343,85 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         sum = wave_max(__float_as_uint(mx_post));
         if (lane == 0 && sum) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_post), sum);
       }
+    });
+  };
+
+  // ---- start-up of the first item (the only exposed one)
+  locate(w_cur, cur);
+  desc_cur = load_desc(cur.grp);
+  issue_tile(cur, 0, 0);
+  uint32_t w_nxt = w_cur + gridDim.x;
+  bool has_next = w_nxt < n_work;
+  if (has_next) {
+    locate(w_nxt, nxt);
+    desc_nxt = load_desc(nxt.grp);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  __syncthreads();
+  Frags f0, f1;
+  read_frags(f0, smem, 0);
+  int stage = 0;
+  const int nkt = p.K / BK;
+
+  // ---- items.  Within one: double-buffered LDS, one barrier per k-tile.  The barrier sits
+  // before the last of the four MFMA steps of a tile: by then a wave holds the tile's last
+  // fragments in registers, so right after the barrier it reads the first fragments of the next
+  // tile (of this item or the next) while R*TM*TN MFMAs are still to issue - the LDS latency
+  // that follows a barrier is covered by work instead of idling the pipe.
+  for (;;) {
+    decode();
+    if constexpr (EARLY_T) fetch_threshold_inputs();
+    static_for<R * TM * TN>([&](auto t) {
+      acc[t / (TM * TN)][(t / TN) % TM][t % TN] =
+          f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    });
+
+    for (int kt = 0; kt < nkt; ++kt) {
+      const bool last = kt + 1 == nkt;
+      const bool more = !last || has_next;              // a tile follows in the other stage
+      if (!last) issue_tile(cur, kt + 1, stage ^ 1);
+      else if (has_next) issue_tile(nxt, 0, stage ^ 1);
+      const uint8_t* s = smem + stage * STAGE;
+      read_frags(f1, s, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_step(f0);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(f0, s, 2);
+      hooks(4 * kt);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_step(f1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(f1, s, 3);
+      hooks(4 * kt + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_step(f0);
+      __builtin_amdgcn_sched_barrier(0);
+      hooks(4 * kt + 2);
+      // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
+      // once all waves are here the next tile has landed and this stage may be overwritten.
+      if (more) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
+      __syncthreads();
+      if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_step(f1);
+      __builtin_amdgcn_sched_barrier(0);
+      hooks(4 * kt + 3);
+      stage ^= 1;
     }
-  });
+
+    if constexpr (!EARLY_T) fetch_threshold_inputs();
+    epilogue();
+    if (!has_next) break;                                // uniform: every wave leaves here
+    cur = nxt;
+    desc_cur = desc_nxt;
+    w_cur = w_nxt;
+    w_nxt = w_cur + gridDim.x;
+    has_next = w_nxt < n_work;
+    if (has_next) {
+      locate(w_nxt, nxt);
+      desc_nxt = load_desc(nxt.grp);
+    }
+  }
 }
 
 }  // namespace fi
