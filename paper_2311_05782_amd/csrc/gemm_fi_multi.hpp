@@ -256,37 +256,47 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         acc[r][i][j] = a;
       });
     }
-    // Detector and corrector on every element of every trial: one compare per element, flags
-    // counted as popcounts of lane masks (wave-uniform).
+    // Detector (and corrector, when outputs are wanted) on every element of every trial.  Without
+    // outputs the common case costs one compare and one scalar OR per element: lane masks of
+    // the flags are merged, and only a trial-tile with any flag set is counted exactly.
     uint32_t n_flag[R];
     static_for<R>([&](auto rr) { n_flag[rr] = 0; });
-    static_for<TM * TN>([&](auto tt) {
-      constexpr int i = tt / TN, j = tt % TN;
-      const f32x16 T = thresholds(tt);
-      const int col = col_base + 32 * j;
-      static_for<R>([&](auto rr) {
-        constexpr int r = rr;
-        if (r < n_act) {
-          const f32x16 t = acc[r][i][j];
-          float* cout = p.c_out ? p.c_out + (size_t)trial[r] * (size_t)p.M * (size_t)p.N : nullptr;
+    auto detect = [&](auto with_out) __attribute__((always_inline)) {
+      constexpr bool OUT = decltype(with_out)::value;
+      static_for<TM * TN>([&](auto tt) {
+        constexpr int i = tt / TN, j = tt % TN;
+        const f32x16 T = thresholds(tt);
+        const int col = col_base + 32 * j;
+        static_for<R>([&](auto rr) {
+          constexpr int r = rr;
+          if (r < n_act) {
+            const f32x16 t = acc[r][i][j];
+            uint64_t any = 0;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-            const float c = t[v];
-            const bool flag = !(fabsf(c) <= T[v]);
-            n_flag[r] += (uint32_t)__builtin_popcountll(__ballot(flag));
-            if (cout) {
-              float cc = c;
-              if (flag) {
-                if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
-                else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
+            for (int v = 0; v < 16; ++v) any |= __ballot(!(fabsf(t[v]) <= T[v]));
+            if (any != 0) {
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                n_flag[r] += (uint32_t)__builtin_popcountll(__ballot(!(fabsf(t[v]) <= T[v])));
+            }
+            if constexpr (OUT) {
+              float* cout = p.c_out + (size_t)trial[r] * (size_t)p.M * (size_t)p.N;
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+                float cc = t[v];
+                if (!(fabsf(cc) <= T[v])) {
+                  if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+                  else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
+                }
+                if (row < p.M && col < p.N) cout[(size_t)row * p.N + col] = cc;
               }
-              if (row < p.M && col < p.N) cout[(size_t)row * p.N + col] = cc;
             }
           }
-        }
+        });
       });
-    });
+    };
+    if (p.c_out) detect(std::true_type{}); else detect(std::false_type{});
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
       if (r < n_act && n_flag[r] != 0 && lane == 0) atomicAdd(&p.results[trial[r]].n_flagged, n_flag[r]);
