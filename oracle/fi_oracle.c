@@ -83,28 +83,92 @@ static void load_b_col(const orc_problem* p, const uint16_t* B, int j, float* ou
   for (int k = 0; k < p->K; ++k) out[k] = dec(b_word(p, B, k, j), p->fmt);
 }
 
+/* ------------------------------------ binary32 -> FP16 / BF16, nearest-even
+ * The paper's fault lives in "the result of a multiplication operation"
+ * (Sec. IV-C) and its detectors read "the register that stores the result of
+ * the BF16 multiplication" (Sec. VI-A): the product is held in the operand
+ * format.  This is the IEEE round-to-nearest-even conversion written out case
+ * by case: NaN, overflow to infinity at the midpoint above the largest finite
+ * value, the subnormal range as a fixed-point grid, normal numbers as
+ * exponent + rounded significand (a carry out of the significand bumps the
+ * exponent). */
+uint16_t orc_round16(float x, int fmt) {
+  uint32_t w32 = word_of(x);
+  uint16_t sign = (uint16_t)((w32 >> 16) & 0x8000u);
+  float ax = fabsf(x);
+  if (fmt == ORC_BF16) {
+    /* 8 exponent bits as binary32: keep the top 16 bits, round on the 16 dropped ones. */
+    if (isnan(x)) return (uint16_t)(sign | 0x7FC0u);
+    uint32_t mag = w32 & 0x7FFFFFFFu;
+    uint32_t keep = mag >> 16, drop = mag & 0xFFFFu;
+    if (drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) keep += 1;   /* may carry up to Inf */
+    return (uint16_t)(sign | keep);
+  }
+  /* FP16: 5 exponent bits (bias 15), 10 fraction bits. */
+  if (isnan(x)) return (uint16_t)(sign | 0x7E00u);
+  if (ax >= 65520.0f) return (uint16_t)(sign | 0x7C00u);       /* halfway to 65536 ties to even = Inf */
+  if (ax < 0x1p-14f) {
+    /* subnormal grid: multiples of 2^-24; scaling by 2^24 is exact */
+    float q = rintf(ax * 0x1p24f);                                /* ties to even */
+    return (uint16_t)(sign | (uint16_t)q);                        /* q == 1024 is the smallest normal */
+  }
+  int e2;
+  float m = frexpf(ax, &e2);                                      /* ax = m * 2^e2, m in [0.5, 1) */
+  int e = e2 - 1;                                                 /* ax = (2m) * 2^e, 2m in [1, 2) */
+  float frac = rintf((2.0f * m - 1.0f) * 1024.0f);                /* exact scaling, ties to even */
+  int q = (int)frac;
+  if (q == 1024) { q = 0; e += 1; }
+  return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)q);
+}
+
 /* --------------------------------- O2 / O3: blocked FP32 dot product
  * Sec. IV-C: low-precision products accumulated into one FP32 number.
  * acc starts at +0; k ascends; each product is rounded once to binary32
  * (exact for FP16 and, inside the binary32 range, for BF16), each addition is
- * rounded once, no fused multiply-add.  If fault_s >= 0 the accumulator word
- * is XORed with mask immediately after the last addition of k-block fault_s
- * (Sec. III-E: the corrupted value lands in the MMA destination register and
- * the following MMAs accumulate onto it). */
-static float dot_blocked(const float* a, const float* b, int K, int kb,
-                         int fault_s, uint32_t mask,
+ * rounded once, no fused multiply-add.
+ *
+ * Accumulator fault (acc_s >= 0): the accumulator word is XORed with acc_mask
+ * immediately after the last addition of k-block acc_s (Sec. III-E: the
+ * corrupted value lands in the MMA destination register and the following
+ * MMAs accumulate onto it).
+ *
+ * Product-term fault (prod_k >= 0), the paper's own model (Sec. III-E "write-
+ * back", Eq. 1-2; Sec. IV-A: a term of one MMA instruction, 16 terms for FP16
+ * and BF16): the MMA step is the group of 16 consecutive k holding prod_k.
+ * After its last addition the destination holds re_sum.  re = the product
+ * a*b rounded to the operand format, re_err = the same 16-bit word XOR
+ * prod_mask; then re' = re_sum - re and re'_sum = re' + re_err, each rounded
+ * once in binary32, replace the destination. */
+typedef struct {
+  int acc_s;  uint32_t acc_mask;
+  int prod_k; uint32_t prod_mask; int fmt;
+} elem_fault;
+static const elem_fault NO_FAULT = {-1, 0, -1, 0, 0};
+
+static float dot_blocked(const float* a, const float* b, int K, int kb, elem_fault ef,
                          uint32_t* word_before, uint32_t* word_after) {
   float acc = 0.0f;
   int S = K / kb;
+  int step_last = ef.prod_k >= 0 ? (ef.prod_k / 16) * 16 + 15 : -1;
   for (int s = 0; s < S; ++s) {
     for (int k = s * kb; k < (s + 1) * kb; ++k) {
       float prod = a[k] * b[k];
       acc = acc + prod;
+      if (k == step_last) {
+        float exact = a[ef.prod_k] * b[ef.prod_k];
+        uint16_t w = orc_round16(exact, ef.fmt);
+        float re = dec(w, ef.fmt);
+        float re_err = dec((uint16_t)(w ^ (ef.prod_mask & 0xFFFFu)), ef.fmt);
+        if (word_before) *word_before = word_of(acc);
+        float re_prime = acc - re;
+        acc = re_prime + re_err;
+        if (word_after) *word_after = word_of(acc);
+      }
     }
-    if (s == fault_s) {
+    if (s == ef.acc_s) {
       uint32_t w = word_of(acc);
       if (word_before) *word_before = w;
-      w ^= mask;
+      w ^= ef.acc_mask;
       if (word_after) *word_after = w;
       acc = float_of(w);
     }
@@ -129,7 +193,7 @@ float orc_dot(const orc_problem* p, const uint16_t* A, const uint16_t* B, int i,
   float* b = (float*)malloc(sizeof(float) * (size_t)p->K);
   load_a_row(p, A, i, a);
   load_b_col(p, B, j, b);
-  float c = dot_blocked(a, b, p->K, p->kb, -1, 0, NULL, NULL);
+  float c = dot_blocked(a, b, p->K, p->kb, NO_FAULT, NULL, NULL);
   free(a);
   free(b);
   return c;
@@ -143,10 +207,10 @@ int orc_threads(void) {
 #endif
 }
 
-/* Whole-matrix O2 with an optional accumulator fault at (fi, fj, fs).
+/* Whole-matrix O2 with an optional fault ef in element (fi, fj).
  * Af is M x K, Bt is N x K (column j of B stored as row j), both decoded. */
 static void gemm_decoded(int M, int N, int K, int kb, const float* Af, const float* Bt,
-                         int fi, int fj, int fs, uint32_t mask,
+                         int fi, int fj, elem_fault ef,
                          float* C, double* R, double* S,
                          uint32_t* word_before, uint32_t* word_after) {
 #ifdef _OPENMP
@@ -157,7 +221,7 @@ static void gemm_decoded(int M, int N, int K, int kb, const float* Af, const flo
       const float* a = Af + (size_t)i * K;
       const float* b = Bt + (size_t)j * K;
       int here = (i == fi && j == fj);
-      C[(size_t)i * N + j] = dot_blocked(a, b, K, kb, here ? fs : -1, mask,
+      C[(size_t)i * N + j] = dot_blocked(a, b, K, kb, here ? ef : NO_FAULT,
                                          here ? word_before : NULL, here ? word_after : NULL);
       if (R || S) {
         double r, s;
@@ -185,7 +249,7 @@ int orc_gemm(const orc_problem* p, const uint16_t* A, const uint16_t* B,
   float *Af, *Bt;
   int rc = decode_operands(p, A, B, &Af, &Bt);
   if (rc) return rc;
-  gemm_decoded(p->M, p->N, p->K, p->kb, Af, Bt, -1, -1, -1, 0, C, R, S, NULL, NULL);
+  gemm_decoded(p->M, p->N, p->K, p->kb, Af, Bt, -1, -1, NO_FAULT, C, R, S, NULL, NULL);
   free(Af);
   free(Bt);
   return 0;
@@ -321,8 +385,19 @@ static int site_valid(const orc_problem* p, const orc_fault* f) {
              f->kblock < (uint32_t)(p->K / p->kb);
     case ORC_SITE_A: return f->row < (uint32_t)p->M && f->col < (uint32_t)p->K;
     case ORC_SITE_B: return f->row < (uint32_t)p->K && f->col < (uint32_t)p->N;
+    case ORC_SITE_PRODUCT:
+      return f->row < (uint32_t)p->M && f->col < (uint32_t)p->N && f->kblock < (uint32_t)p->K;
     default: return 0;
   }
+}
+
+/* The fault of one output element: accumulator flip after k-block `kblock`, or a
+ * product-term fault on the product with k = `kblock`. */
+static elem_fault element_fault(const orc_problem* p, const orc_fault* f) {
+  elem_fault ef = NO_FAULT;
+  if (f->kind == ORC_SITE_ACC) { ef.acc_s = (int)f->kblock; ef.acc_mask = f->xor_mask; }
+  if (f->kind == ORC_SITE_PRODUCT) { ef.prod_k = (int)f->kblock; ef.prod_mask = f->xor_mask; ef.fmt = p->fmt; }
+  return ef;
 }
 
 /* ----------------------------------------------------- O3-O6: one trial */
@@ -343,26 +418,26 @@ static int trial_full(const orc_problem* p, const uint16_t* A, const uint16_t* B
   orc_rowcol_absmax(p, A, B, ra, cb);     /* statistics of the GOLDEN operands */
   float ra_max = vec_max(ra, M), cb_max = vec_max(cb, N);
 
-  gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, -1, 0, Cstar, NULL, S, NULL, NULL);
+  gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, NO_FAULT, Cstar, NULL, S, NULL, NULL);
 
   /* The faulty execution: every element is recomputed with the fault in place. */
-  if (f->kind == ORC_SITE_ACC) {
-    gemm_decoded(M, N, K, p->kb, Af, Bt, (int)f->row, (int)f->col, (int)f->kblock,
-                 f->xor_mask, Cf, NULL, NULL, &rec->site_word_before, &rec->site_word_after);
+  if (f->kind == ORC_SITE_ACC || f->kind == ORC_SITE_PRODUCT) {
+    gemm_decoded(M, N, K, p->kb, Af, Bt, (int)f->row, (int)f->col, element_fault(p, f),
+                 Cf, NULL, NULL, &rec->site_word_before, &rec->site_word_after);
   } else if (f->kind == ORC_SITE_A) {
     uint16_t w = a_word(p, A, (int)f->row, (int)f->col);
     uint16_t wf = (uint16_t)(w ^ (f->xor_mask & 0xFFFFu));
     rec->site_word_before = w;
     rec->site_word_after = wf;
     Af[(size_t)f->row * K + f->col] = dec(wf, p->fmt);
-    gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, -1, 0, Cf, NULL, NULL, NULL, NULL);
+    gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, NO_FAULT, Cf, NULL, NULL, NULL, NULL);
   } else if (f->kind == ORC_SITE_B) {
     uint16_t w = b_word(p, B, (int)f->row, (int)f->col);
     uint16_t wf = (uint16_t)(w ^ (f->xor_mask & 0xFFFFu));
     rec->site_word_before = w;
     rec->site_word_after = wf;
     Bt[(size_t)f->col * K + f->row] = dec(wf, p->fmt);
-    gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, -1, 0, Cf, NULL, NULL, NULL, NULL);
+    gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, NO_FAULT, Cf, NULL, NULL, NULL, NULL);
   } else {
     memcpy(Cf, Cstar, sizeof(float) * mn);
   }
@@ -390,12 +465,12 @@ static int trial_affected(const orc_problem* p, const uint16_t* A, const uint16_
   float* a = (float*)malloc(sizeof(float) * (size_t)K);
   float* b = (float*)malloc(sizeof(float) * (size_t)K);
   float* g = (float*)malloc(sizeof(float) * (size_t)K);   /* golden copy of the faulted vector */
-  if (f->kind == ORC_SITE_ACC) {
+  if (f->kind == ORC_SITE_ACC || f->kind == ORC_SITE_PRODUCT) {
     int i = (int)f->row, j = (int)f->col;
     load_a_row(p, A, i, a);
     load_b_col(p, B, j, b);
-    float c_star = dot_blocked(a, b, K, p->kb, -1, 0, NULL, NULL);
-    float c_f = dot_blocked(a, b, K, p->kb, (int)f->kblock, f->xor_mask,
+    float c_star = dot_blocked(a, b, K, p->kb, NO_FAULT, NULL, NULL);
+    float c_f = dot_blocked(a, b, K, p->kb, element_fault(p, f),
                             &rec->site_word_before, &rec->site_word_after);
     double R, S;
     dot_double(a, b, K, &R, &S);
@@ -411,8 +486,8 @@ static int trial_affected(const orc_problem* p, const uint16_t* A, const uint16_
     a[kf] = dec(wf, p->fmt);
     for (int j = 0; j < p->N; ++j) {
       load_b_col(p, B, j, b);
-      float c_star = dot_blocked(g, b, K, p->kb, -1, 0, NULL, NULL);
-      float c_f = dot_blocked(a, b, K, p->kb, -1, 0, NULL, NULL);
+      float c_star = dot_blocked(g, b, K, p->kb, NO_FAULT, NULL, NULL);
+      float c_f = dot_blocked(a, b, K, p->kb, NO_FAULT, NULL, NULL);
       double R, S;
       dot_double(g, b, K, &R, &S);
       account(rec, c_f, c_star, S, threshold_at(p, ra, cb, ra_max, cb_max, i, j), policy);
@@ -428,8 +503,8 @@ static int trial_affected(const orc_problem* p, const uint16_t* A, const uint16_
     b[kf] = dec(wf, p->fmt);
     for (int i = 0; i < p->M; ++i) {
       load_a_row(p, A, i, a);
-      float c_star = dot_blocked(a, g, K, p->kb, -1, 0, NULL, NULL);
-      float c_f = dot_blocked(a, b, K, p->kb, -1, 0, NULL, NULL);
+      float c_star = dot_blocked(a, g, K, p->kb, NO_FAULT, NULL, NULL);
+      float c_f = dot_blocked(a, b, K, p->kb, NO_FAULT, NULL, NULL);
       double R, S;
       dot_double(a, g, K, &R, &S);
       account(rec, c_f, c_star, S, threshold_at(p, ra, cb, ra_max, cb_max, i, j), policy);
@@ -532,7 +607,7 @@ static uint32_t unif(uint32_t n, uint64_t u) {
 int orc_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials,
                       const orc_problem* p, int kind_mode, int nbits, orc_fault* out) {
   if (check_problem(p) || !out) return 1;
-  if (kind_mode < 0 || kind_mode > 3) return 1;
+  if (kind_mode < 0 || kind_mode > 4) return 1;
   if (nbits < 1 || nbits > 16) return 1;
   uint32_t S = (uint32_t)(p->K / p->kb);
   for (uint32_t n = 0; n < n_trials; ++n) {
@@ -547,6 +622,7 @@ int orc_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials,
       case ORC_KIND_ALL_ACC: kind = ORC_SITE_ACC; break;
       case ORC_KIND_ALL_A: kind = ORC_SITE_A; break;
       case ORC_KIND_ALL_B: kind = ORC_SITE_B; break;
+      case ORC_KIND_ALL_PRODUCT: kind = ORC_SITE_PRODUCT; break;
       default: kind = (t % 2 == 0) ? ORC_SITE_ACC : ORC_SITE_A; break;
     }
     orc_fault f;
@@ -557,6 +633,13 @@ int orc_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials,
       f.col = unif((uint32_t)p->N, u1);
       f.kblock = unif(S, u2);
       width = 32;
+    } else if (kind == ORC_SITE_PRODUCT) {
+      /* Sec. IV-A: an MMA instruction, one of its results, one of its 16 terms - uniform
+       * over (i, j, k) - and a random bit(s) of the 16-bit product. */
+      f.row = unif((uint32_t)p->M, u0);
+      f.col = unif((uint32_t)p->N, u1);
+      f.kblock = unif((uint32_t)p->K, u2);
+      width = 16;
     } else if (kind == ORC_SITE_A) {
       uint32_t s = unif(S, u1), kk = unif((uint32_t)p->kb, u2);
       f.row = unif((uint32_t)p->M, u0);

@@ -35,12 +35,13 @@ extern "C" {
 #endif
 
 enum { ORC_FP16 = 0, ORC_BF16 = 1 };
-enum { ORC_SITE_NONE = 0, ORC_SITE_ACC = 1, ORC_SITE_A = 2, ORC_SITE_B = 3 };
+enum { ORC_SITE_NONE = 0, ORC_SITE_ACC = 1, ORC_SITE_A = 2, ORC_SITE_B = 3, ORC_SITE_PRODUCT = 4 };
 enum { ORC_CORRECT_NONE = 0, ORC_CORRECT_ZERO = 1, ORC_CORRECT_RECOMPUTE = 2 };
 enum { ORC_BOUND_ROWCOL = 0, ORC_BOUND_GLOBAL = 1 };
 enum { ORC_MASKED = 0, ORC_SDC = 1, ORC_DETECTED = 2 };
 enum { ORC_MODE_FULL = 0, ORC_MODE_AFFECTED = 1 };
-enum { ORC_KIND_ALL_ACC = 0, ORC_KIND_ALL_A = 1, ORC_KIND_ALL_B = 2, ORC_KIND_MIX_ACC_A = 3 };
+enum { ORC_KIND_ALL_ACC = 0, ORC_KIND_ALL_A = 1, ORC_KIND_ALL_B = 2, ORC_KIND_MIX_ACC_A = 3,
+       ORC_KIND_ALL_PRODUCT = 4 };
 
 /* Problem: A is M x K (row i at A + i*lda, K contiguous).  B is K x N
  * mathematically; b_layout 0 stores it as N rows of K (b_kj at B[j*ldb+k]),
@@ -55,7 +56,11 @@ typedef struct {
 } orc_problem;
 
 /* One fault.  ACC: (row=i, col=j, kblock=s, 32-bit mask).
- * A: (row=i, col=k, low 16 bits of mask).  B: (row=k, col=j, low 16 bits). */
+ * A: (row=i, col=k, low 16 bits of mask).  B: (row=k, col=j, low 16 bits).
+ * PRODUCT (the paper's own model, Sec. III-E, Sec. IV-A): (row=i, col=j,
+ * kblock=k, low 16 bits of mask): the product a_ik*b_kj, held in the operand
+ * format, has its word XORed; after the 16-term MMA step containing k the
+ * destination is rewritten as (re_sum - re) + re_err in binary32. */
 typedef struct {
   uint32_t kind, row, col, kblock, xor_mask;
 } orc_fault;
@@ -78,6 +83,10 @@ typedef struct {
 
 /* O1: exact value of a 16-bit pattern, held in a float. */
 float orc_decode16(uint16_t w, int fmt);
+
+/* binary32 -> FP16 / BF16 word, round to nearest even (the format a product is held in,
+ * Sec. IV-C, Sec. VI-A). */
+uint16_t orc_round16(float x, int fmt);
 void  orc_decode_array(const uint16_t* in, size_t n, int fmt, float* out);
 
 /* O2: blocked FP32 dot product of row i of A and column j of B, no fault. */

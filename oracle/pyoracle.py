@@ -14,12 +14,12 @@ _SRC = os.path.join(_HERE, "fi_oracle.c")
 _LIB = os.path.join(_HERE, "libfi_oracle.so")
 
 FP16, BF16 = 0, 1
-SITE_NONE, SITE_ACC, SITE_A, SITE_B = 0, 1, 2, 3
+SITE_NONE, SITE_ACC, SITE_A, SITE_B, SITE_PRODUCT = 0, 1, 2, 3, 4
 CORRECT_NONE, CORRECT_ZERO, CORRECT_RECOMPUTE = 0, 1, 2
 BOUND_ROWCOL, BOUND_GLOBAL = 0, 1
 MASKED, SDC, DETECTED = 0, 1, 2
 MODE_FULL, MODE_AFFECTED = 0, 1
-KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A = 0, 1, 2, 3
+KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A, KIND_ALL_PRODUCT = 0, 1, 2, 3, 4
 
 
 class Problem(C.Structure):
@@ -64,6 +64,8 @@ def lib():
         PP = C.POINTER(Problem)
         L.orc_decode16.restype = C.c_float
         L.orc_decode16.argtypes = [C.c_uint16, C.c_int]
+        L.orc_round16.restype = C.c_uint16
+        L.orc_round16.argtypes = [C.c_float, C.c_int]
         L.orc_decode_array.restype = None
         L.orc_decode_array.argtypes = [u16p, C.c_size_t, C.c_int, f32p]
         L.orc_dot.restype = C.c_float
@@ -113,6 +115,11 @@ def problem(M, N, K, kb, fmt, b_layout=0, bound_mode=BOUND_ROWCOL, gamma=DEFAULT
 
 def decode16(w, fmt):
     return float(np.float32(lib().orc_decode16(int(w), fmt)))
+
+
+def round16(x, fmt):
+    """binary32 value -> FP16 / BF16 word, round to nearest even."""
+    return int(lib().orc_round16(float(np.float32(x)), fmt))
 
 
 def decode_array(words, fmt):
