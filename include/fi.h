@@ -50,11 +50,12 @@ enum {
 };
 
 enum { FI_FP16 = 0, FI_BF16 = 1 };
-enum { FI_SITE_NONE = 0, FI_SITE_ACC = 1, FI_SITE_A = 2, FI_SITE_B = 3 };
+enum { FI_SITE_NONE = 0, FI_SITE_ACC = 1, FI_SITE_A = 2, FI_SITE_B = 3, FI_SITE_PRODUCT = 4 };
 enum { FI_CORRECT_NONE = 0, FI_CORRECT_ZERO = 1, FI_CORRECT_RECOMPUTE = 2 };
 enum { FI_BOUND_ROWCOL = 0, FI_BOUND_GLOBAL = 1 };
 enum { FI_MASKED = 0, FI_SDC = 1, FI_DETECTED = 2 };
-enum { FI_KIND_ALL_ACC = 0, FI_KIND_ALL_A = 1, FI_KIND_ALL_B = 2, FI_KIND_MIX_ACC_A = 3 };
+enum { FI_KIND_ALL_ACC = 0, FI_KIND_ALL_A = 1, FI_KIND_ALL_B = 2, FI_KIND_MIX_ACC_A = 3,
+       FI_KIND_ALL_PRODUCT = 4 };
 
 /* One fault (Sec. IV-A: one target, a random bit or bits, one fault per trial).
  *   ACC : row = i, col = j, kblock = s; xor_mask applies to the 32-bit
@@ -63,6 +64,11 @@ enum { FI_KIND_ALL_ACC = 0, FI_KIND_ALL_A = 1, FI_KIND_ALL_B = 2, FI_KIND_MIX_AC
  *   A   : row = i, col = k; the low 16 bits of xor_mask apply to a_ik for
  *         every use in this trial (kblock is ignored).
  *   B   : row = k, col = j; same for b_kj.
+ *   PRODUCT : the paper's own fault (Sec. III-E write-back, Eq. 1-2; Sec. IV-A one term of
+ *         one 16-term MMA step): row = i, col = j, kblock = k.  re = a_ik * b_kj rounded to
+ *         the operand format, re_err = the same 16-bit word XOR the low 16 bits of
+ *         xor_mask.  Right after the 16-wide MMA step that holds k, the accumulator of
+ *         element (i, j) becomes fl32(fl32(acc - re) + re_err).
  *   NONE: a fault-free trial.
  * A site outside the problem makes the trial run fault-free with
  * fi_trial_result.status = 1. */
@@ -83,8 +89,8 @@ typedef struct {
   uint32_t n_dev_post;       /* same, after correction                              */
   float    max_dev_pre;      /* max |c - C*| before correction (+Inf for NaN/Inf)   */
   float    max_dev_post;     /* ... after correction                                */
-  uint32_t site_word_before; /* ACC: accumulator word at the injection point;       */
-  uint32_t site_word_after;  /*      A/B: the 16-bit operand word                   */
+  uint32_t site_word_before; /* ACC, PRODUCT: accumulator word at the injection     */
+  uint32_t site_word_after;  /*   point (Sec. V-B's re_sum, re'_sum); A/B: the operand word */
   uint32_t n_border_T;       /* changed elements within max(2 tau, T/64) of T       */
   uint32_t n_border_tau;     /* changed elements with tau/2 <= |c - C*| <= 2 tau    */
   uint32_t status;           /* 0 ok, 1 site out of range (trial ran fault-free)    */
@@ -170,9 +176,9 @@ fi_status fi_classify(fi_plan* plan, const fi_trial_result* d_results, uint32_t 
 
 /* Host-side site selection (Sec. IV-A: uniform target, random bit(s)).
  * Trial t = first_trial + n draws from SplitMix64 seeded with seed + t*2^32:
- * u0 -> row (A: i; B: column j), u1, u2 -> (column, k-block) for ACC or
- * (k-block, offset in block) for operands, u3 -> position of an nbits-wide
- * run of ones; unif(n, u) = floor((u >> 32) * n / 2^32).
+ * u0 -> row (A: i; B: column j), u1, u2 -> (column, k-block) for ACC,
+ * (column, k) for PRODUCT, (k-block, offset in block) for operands, u3 ->
+ * position of an nbits-wide run of ones in the 32-bit (ACC) or 16-bit word; unif(n, u) = floor((u >> 32) * n / 2^32).
  * h_out is HOST memory for n_trials faults.  No device is needed. */
 fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials,
                            const fi_plan_desc* desc, uint32_t kind_mode, uint32_t nbits,

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "fi.h"
+#include "gemm_fi.hpp"
 
 namespace fi {
 
@@ -18,17 +19,6 @@ __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t step = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += step) p[i] = v;
-}
-
-// Exact value of a 16-bit operand word as a float (Sec. II-A formats).
-template <int DT>
-__device__ __forceinline__ float decode16(uint32_t w) {
-  if constexpr (DT == FI_BF16) {
-    return __uint_as_float(w << 16);
-  } else {
-    unsigned short h = (unsigned short)w;
-    return (float)__builtin_bit_cast(_Float16, h);
-  }
 }
 
 // out[r] = scale * max_k |x_rk| for the rows of a K-contiguous 16-bit matrix:
@@ -172,16 +162,21 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
   }
 }
 
-// Splits a batch: trials the multi-trial GEMM kernel can take (no fault, or an accumulator
-// flip; out-of-range sites count as "no fault" and get status 1 in their zeroed record) go to
-// the front of perm in list order, all others (operand faults) behind them.
-// counts = {front, back}.  For front position q, desc[5q..5q+4] = {trial, row, col, step, mask}:
-// step = the 16-wide MFMA step after which the accumulator flips, (s+1)*kb/16 - 1, or -1 for no
-// fault.  desc is padded with fault-free entries up to the next multiple of 8 positions.
+// Splits a batch: trials the multi-trial GEMM kernel can take (no fault, an accumulator flip or
+// a product-term fault; out-of-range sites count as "no fault" and get status 1 in their zeroed
+// record) go to the front of perm in list order, all others (operand faults) behind them.
+// counts = {front, back}.  For front position q, desc[6q .. 6q+5] = {trial, row, col, event,
+// w0, w1}: event = -1 for no fault, else the 16-wide MFMA step after which the accumulator
+// changes - (s+1)*kb/16 - 1 for a flip with w0 = the XOR mask; k/16, with bit 30 set, for a
+// product-term fault with w0, w1 = the words of re and re_err (Sec. III-E).  desc is padded
+// with fault-free entries up to the next multiple of 8 positions.  B is [N][ldb], k contiguous.
 // One workgroup; each thread owns a contiguous chunk of the list.
+template <int DT>
 __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* __restrict__ f, uint32_t n,
                                                                uint32_t M, uint32_t N, uint32_t K, uint32_t kb,
-                                                               uint32_t* __restrict__ perm,
+                                                               const uint16_t* __restrict__ A,
+                                                               const uint16_t* __restrict__ B, uint32_t lda,
+                                                               uint32_t ldb, uint32_t* __restrict__ perm,
                                                                uint32_t* __restrict__ counts,
                                                                uint32_t* __restrict__ desc,
                                                                fi_trial_result* __restrict__ results) {
@@ -189,9 +184,11 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
   __shared__ uint32_t total_fast;
   const uint32_t chunk = (n + 1023) / 1024;
   const uint32_t lo = min(threadIdx.x * chunk, n), hi = min(lo + chunk, n);
-  // 0: operand fault (other kernel); 1: runs fault-free; 2: accumulator flip; 3: bad site
+  // 0: operand fault (other kernel); 1: runs fault-free; 2: accumulator flip; 3: bad site;
+  // 4: product-term fault
   auto kind_of = [&](const fi_fault& x) -> int {
     if (x.kind == FI_SITE_ACC) return (x.row < M && x.col < N && x.kblock < K / kb) ? 2 : 3;
+    if (x.kind == FI_SITE_PRODUCT) return (x.row < M && x.col < N && x.kblock < K) ? 4 : 3;
     if (x.kind == FI_SITE_A) return (x.row < M && x.col < K) ? 0 : 3;
     if (x.kind == FI_SITE_B) return (x.row < K && x.col < N) ? 0 : 3;
     return x.kind == FI_SITE_NONE ? 1 : 3;
@@ -215,18 +212,26 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
     const fi_fault x = f[t];
     const int k = kind_of(x);
     if (k == 0) { perm[ps++] = t; continue; }
-    uint32_t* d = desc + (size_t)pf * 5;
+    uint32_t* d = desc + (size_t)pf * 6;
     d[0] = t; d[1] = x.row; d[2] = x.col;
-    d[3] = k == 2 ? (x.kblock + 1) * kb / 16 - 1 : 0xFFFFFFFFu;
-    d[4] = x.xor_mask;
+    if (k == 2) {
+      d[3] = (x.kblock + 1) * kb / 16 - 1; d[4] = x.xor_mask; d[5] = 0;
+    } else if (k == 4) {
+      float re, re_err;
+      product_fault_terms<DT>(A[(size_t)x.row * lda + x.kblock], B[(size_t)x.col * ldb + x.kblock], x.xor_mask,
+                              re, re_err);
+      d[3] = (x.kblock / 16) | 0x40000000u; d[4] = __float_as_uint(re); d[5] = __float_as_uint(re_err);
+    } else {
+      d[3] = 0xFFFFFFFFu; d[4] = 0; d[5] = 0;
+    }
     if (k == 3) results[t].status = 1;
     perm[pf++] = t;
   }
   if (threadIdx.x < 8) {
     const uint32_t q = n_fast + threadIdx.x;
     if (q < ((n_fast + 7u) & ~7u)) {
-      uint32_t* d = desc + (size_t)q * 5;
-      d[0] = 0; d[1] = 0; d[2] = 0; d[3] = 0xFFFFFFFFu; d[4] = 0;
+      uint32_t* d = desc + (size_t)q * 6;
+      d[0] = 0; d[1] = 0; d[2] = 0; d[3] = 0xFFFFFFFFu; d[4] = 0; d[5] = 0;
     }
   }
 }

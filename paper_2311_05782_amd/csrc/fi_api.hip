@@ -437,8 +437,14 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
       plan->perm_cap = n_trials;
     }
     uint32_t* counts = plan->perm + plan->perm_cap;
-    hipLaunchKernelGGL(fi::partition_trials_kernel, dim3(1), dim3(1024), 0, s, d_faults, n_trials, plan->d.M,
-                       plan->d.N, plan->d.K, plan->d.k_block, plan->perm, counts, plan->desc, d_results);
+    if (plan->d.dtype == FI_BF16)
+      hipLaunchKernelGGL(fi::partition_trials_kernel<FI_BF16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
+                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->perm,
+                         counts, plan->desc, d_results);
+    else
+      hipLaunchKernelGGL(fi::partition_trials_kernel<FI_FP16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
+                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->perm,
+                         counts, plan->desc, d_results);
     FI_HIP(hipGetLastError());
     a.perm = plan->perm;
     a.part_counts = counts;
@@ -511,7 +517,7 @@ fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trial
   fi_status st = check_desc(desc, nullptr);
   if (st != FI_OK) return st;
   if (!h_out) return fail(FI_INVALID_ARG, "h_out is NULL");
-  if (kind_mode > FI_KIND_MIX_ACC_A) return fail(FI_INVALID_ARG, "unknown kind_mode %u", kind_mode);
+  if (kind_mode > FI_KIND_ALL_PRODUCT) return fail(FI_INVALID_ARG, "unknown kind_mode %u", kind_mode);
   if (nbits < 1 || nbits > 16) return fail(FI_INVALID_ARG, "nbits must be in 1..16");
   const uint32_t nblocks = desc->K / desc->k_block;
   for (uint32_t n = 0; n < n_trials; ++n) {
@@ -523,6 +529,7 @@ fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trial
     uint32_t kind = kind_mode == FI_KIND_ALL_ACC ? FI_SITE_ACC
                   : kind_mode == FI_KIND_ALL_A   ? FI_SITE_A
                   : kind_mode == FI_KIND_ALL_B   ? FI_SITE_B
+                  : kind_mode == FI_KIND_ALL_PRODUCT ? FI_SITE_PRODUCT
                   : ((t & 1) ? FI_SITE_A : FI_SITE_ACC);
     f.kind = kind;
     uint32_t width = 16;
@@ -531,6 +538,10 @@ fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trial
       f.col = scale_to(desc->N, u[1]);
       f.kblock = scale_to(nblocks, u[2]);
       width = 32;
+    } else if (kind == FI_SITE_PRODUCT) {
+      f.row = scale_to(desc->M, u[0]);
+      f.col = scale_to(desc->N, u[1]);
+      f.kblock = scale_to(desc->K, u[2]);          // the term: k, uniform over all MMA steps and terms
     } else {
       const uint32_t s = scale_to(nblocks, u[1]);
       const uint32_t k = s * desc->k_block + scale_to(desc->k_block, u[2]);

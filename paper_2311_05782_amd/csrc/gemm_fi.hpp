@@ -81,6 +81,63 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
   }
 }
 
+// Exact value of a 16-bit operand word as a float (Sec. II-A formats).
+template <int DT>
+__device__ __forceinline__ float decode16(uint32_t w) {
+  if constexpr (DT == FI_BF16) {
+    return __uint_as_float(w << 16);
+  } else {
+    unsigned short h = (unsigned short)w;
+    return (float)__builtin_bit_cast(_Float16, h);
+  }
+}
+
+// binary32 -> FP16 / BF16 word, round to nearest even, in integer arithmetic (no dependence on
+// the wave's denormal or rounding modes).  This is the format a product is held in by the
+// paper's fault model (Sec. IV-C: the result of a multiplication operation).
+template <int DT>
+__device__ __forceinline__ uint32_t round16(float x) {
+  const uint32_t b = __float_as_uint(x);
+  const uint32_t sign = (b >> 16) & 0x8000u;
+  const uint32_t mag = b & 0x7FFFFFFFu;
+  if constexpr (DT == FI_BF16) {
+    if (mag > 0x7F800000u) return sign | 0x7FC0u;
+    return sign | ((mag + 0x7FFFu + ((mag >> 16) & 1u)) >> 16);          // a carry may reach Inf
+  } else {
+    if (mag > 0x7F800000u) return sign | 0x7E00u;
+    if (mag >= 0x477FF000u) return sign | 0x7C00u;                       // >= 65520: Inf
+    if (mag < 0x38800000u) {                                             // below 2^-14: subnormal grid
+      if (mag <= 0x33000000u) return sign;                               // <= 2^-25 (tie to even): 0
+      const uint32_t e = mag >> 23;                                      // 102 .. 112
+      const uint32_t m = (mag & 0x7FFFFFu) | 0x800000u;                  // value = m * 2^(e - 150)
+      const uint32_t shift = 126u - e;                                   // multiples of 2^-24
+      uint32_t q = m >> shift;
+      const uint32_t rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1u);
+      if (rem > half || (rem == half && (q & 1u))) ++q;
+      return sign | q;
+    }
+    const uint32_t e = (mag >> 23) - 112u;                               // FP16 biased exponent
+    const uint32_t m = mag & 0x7FFFFFu;
+    uint32_t h = (e << 10) | (m >> 13);
+    const uint32_t rem = m & 0x1FFFu;
+    if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h;              // a carry bumps the exponent
+    return sign | h;
+  }
+}
+
+// Product-term fault (Sec. III-E): re = a*b held in the operand format, re_err = its word XOR mask.
+template <int DT>
+__device__ __forceinline__ void product_fault_terms(uint32_t a_word, uint32_t b_word, uint32_t mask,
+                                                    float& re, float& re_err) {
+  const uint32_t w = round16<DT>(__fmul_rn(decode16<DT>(a_word), decode16<DT>(b_word)));
+  re = decode16<DT>(w);
+  re_err = decode16<DT>((w ^ mask) & 0xFFFFu);
+}
+// The write-back of Eq. (1)-(2): two binary32 operations, each rounded once.
+__device__ __forceinline__ float write_back(float re_sum, float re, float re_err) {
+  return __fadd_rn(__fsub_rn(re_sum, re), re_err);
+}
+
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Keeps every
 // accumulator index a constant from the front end on, whatever the optimiser's unrolling does.
 template <int... I, typename F>
@@ -181,6 +238,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   // ---- this trial's fault, and what it means for this workgroup and wave (all uniform)
   uint32_t fkind = FI_SITE_NONE, frow = 0, fcol = 0, fmask = 0;
   int hook_kt = -1;         // owning wave: flip the accumulator after this k-tile
+  int fk = 0;               // product-term fault: k of the term
   int kshift = 0;           // this workgroup's k-tiles start at -kshift (see below)
   int sel_t = 0, sel_v = 0, sel_lane = -1;
   bool affected = false;    // this tile can differ from the fault-free result
@@ -191,6 +249,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     bool valid = true;
     if (fkind == FI_SITE_ACC) {
       valid = frow < (uint32_t)p.M && fcol < (uint32_t)p.N && f.kblock < (uint32_t)(p.K / p.kb);
+    } else if (fkind == FI_SITE_PRODUCT) {
+      valid = frow < (uint32_t)p.M && fcol < (uint32_t)p.N && f.kblock < (uint32_t)p.K;
     } else if (fkind == FI_SITE_A) {
       valid = frow < (uint32_t)p.M && fcol < (uint32_t)p.K;
     } else if (fkind == FI_SITE_B) {
@@ -202,7 +262,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
       if (tile == 0 && tid == 0) p.results[trial].status = 1;
       fkind = FI_SITE_NONE;
     }
-    if (fkind == FI_SITE_ACC) {
+    if (fkind == FI_SITE_ACC || fkind == FI_SITE_PRODUCT) {
       const int li = (int)frow - m0, lj = (int)fcol - n0;
       if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
         affected = true;
@@ -212,7 +272,9 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
         // part below 0 read as zeros.  The sequence of 16-wide MFMA steps over real data is
         // unchanged (steps over zeros leave the +0 accumulators as they are), so every other
         // element of the tile still equals the fault-free result bit for bit.
-        const int hook_k = ((int)f.kblock + 1) * p.kb;
+        // A product-term fault is written back after the 16-wide MMA step holding its k.
+        const int hook_k = fkind == FI_SITE_ACC ? ((int)f.kblock + 1) * p.kb : ((int)f.kblock / 16 + 1) * 16;
+        fk = (int)f.kblock;
         kshift = (BK - hook_k % BK) % BK;
         const int wi = li - wm * WTM, wj = lj - wn * WTN;
         if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
@@ -361,8 +423,11 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   // among TM*TN static ones; the register inside the tile's 16 is picked by a dynamic vector
   // index, which stays in registers for a 16-element vector.
   auto accumulator_fault = [&]() {
-    const uint32_t lane_mask = (lane == sel_lane) ? fmask : 0u;
-    uint32_t before = 0;
+    const bool product = fkind == FI_SITE_PRODUCT;
+    float re = 0.0f, re_err = 0.0f;
+    if (product)
+      product_fault_terms<DT>(p.A[(size_t)frow * p.lda + fk], p.B[(size_t)fcol * p.ldb + fk], fmask, re, re_err);
+    uint32_t before = 0, after = 0;
     static_for<TM * TN>([&](auto tt) {
       constexpr int i = tt / TN, j = tt % TN;
       if (tt == sel_t) {
@@ -371,15 +436,17 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
         for (int v = 0; v < 16; ++v) {
           const bool here = v == sel_v;                       // uniform
           const uint32_t w = __float_as_uint(t[v]);
+          const uint32_t nw = product ? __float_as_uint(write_back(t[v], re, re_err)) : (w ^ fmask);
           before = here ? w : before;
-          t[v] = __uint_as_float(w ^ (here ? lane_mask : 0u));
+          after = here ? nw : after;
+          t[v] = __uint_as_float((here && lane == sel_lane) ? nw : w);
         }
         acc[i][j] = t;
       }
     });
     if (lane == sel_lane) {
       p.results[trial].site_word_before = before;
-      p.results[trial].site_word_after = before ^ fmask;
+      p.results[trial].site_word_after = after;
     }
   };
 

@@ -8,11 +8,14 @@
 // ds_read_b128 per MFMA both fall by the factor the tile shrinks less than R grows
 // (R = 8 on a 128x64 tile: 3/8 of the bytes per flop of one 256x256 tile per trial).
 //
-// Handles trials whose fault is NONE or an accumulator flip (k-blocks are multiples of the
-// 16-wide MFMA step, so every flip falls between two steps), on problems with K % 64 == 0.
-// The library's partition kernel routes every other trial (operand faults) to gemm_fi_kernel
-// and writes, for the trials this kernel takes, one 5-word descriptor each in list order:
-// {trial, row, col, MFMA step after which the accumulator flips or -1, xor mask}.
+// Handles trials whose fault is NONE, an accumulator flip (k-blocks are multiples of the
+// 16-wide MFMA step, so every flip falls between two steps) or the paper's product-term fault
+// (Sec. III-E: written back after the 16-term step holding the term), on problems with
+// K % 64 == 0.  The library's partition kernel routes every other trial (operand faults) to
+// gemm_fi_kernel and writes, for the trials this kernel takes, one 6-word descriptor each in
+// list order: {trial, row, col, event, w0, w1} - event = the MFMA step after which the
+// accumulator changes or -1; a flip has w0 = the XOR mask; a product-term fault has bit 30 of
+// event set and w0, w1 = the words of re and re_err.
 //
 // Work item = (output tile, group of R trials).  The register budget (R*TM*TN*16 accumulator
 // VGPRs per lane) admits one workgroup per CU, so nothing would hide a workgroup's start-up
@@ -29,7 +32,7 @@
 
 namespace fi {
 
-constexpr int kMultiDescWords = 5;   // trial, row, col, hook step, xor mask
+constexpr int kMultiDescWords = 6;   // trial, row, col, event, w0, w1
 
 template <int DT, int R, int BM, int BN, int WM, int WN>
 __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmArgs p) {
@@ -146,8 +149,9 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       constexpr int r = rr;
       trial[r] = (int)desc_field(r, 0);
       hook_step[r] = -1;
-      const int hs = (int)desc_field(r, 3);
-      if (r < n_act && hs >= 0) {
+      const int ev = (int)desc_field(r, 3);
+      const int hs = ev & 0xFFFF;
+      if (r < n_act && ev >= 0) {
         const int li = (int)desc_field(r, 1) - cur.m0, lj = (int)desc_field(r, 2) - cur.n0;
         if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
           affected |= 1u << r;
@@ -165,13 +169,14 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   auto accumulator_fault = [&](auto rr) {
     constexpr int r = rr;
     const int wi = (int)desc_field(r, 1) - cur.m0 - wm * WTM, wj = (int)desc_field(r, 2) - cur.n0 - wn * WTN;
-    const uint32_t xor_mask = desc_field(r, 4);
+    const bool product = ((desc_field(r, 3) >> 30) & 1u) != 0;      // else an XOR of the word
+    const uint32_t w0 = desc_field(r, 4), w1 = desc_field(r, 5);
+    const float re = __uint_as_float(w0), re_err = __uint_as_float(w1);
     const int ri = wi & 31, rj = wj & 31;
     const int sel_t = (wi >> 5) * TN + (wj >> 5);
     const int sel_v = 4 * (ri >> 3) + (ri & 3);
     const int sel_lane = rj + 32 * ((ri >> 2) & 1);
-    const uint32_t lane_mask = (lane == sel_lane) ? xor_mask : 0u;
-    uint32_t before = 0;
+    uint32_t before = 0, after = 0;
     static_for<TM * TN>([&](auto tt) {
       constexpr int i = tt / TN, j = tt % TN;
       if (tt == sel_t) {
@@ -180,15 +185,17 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         for (int v = 0; v < 16; ++v) {
           const bool here = v == sel_v;
           const uint32_t w = __float_as_uint(t[v]);
+          const uint32_t nw = product ? __float_as_uint(write_back(t[v], re, re_err)) : (w ^ w0);
           before = here ? w : before;
-          t[v] = __uint_as_float(w ^ (here ? lane_mask : 0u));
+          after = here ? nw : after;
+          t[v] = __uint_as_float((here && lane == sel_lane) ? nw : w);
         }
         acc[r][i][j] = t;
       }
     });
     if (lane == sel_lane) {
       p.results[trial[r]].site_word_before = before;
-      p.results[trial[r]].site_word_after = before ^ xor_mask;
+      p.results[trial[r]].site_word_after = after;
     }
     // Leave nothing of this rare path in flight: the compiler places its waits statically, and
     // memory traffic pending here would make every iteration of the main loop wait for it.

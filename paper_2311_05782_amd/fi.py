@@ -16,11 +16,11 @@ LIB_PATH = os.environ.get("FI_LIBRARY") or os.path.join(_HERE, "libfi_gfx950.so"
 
 OK, INVALID_ARG, UNSUPPORTED, OOM, DEVICE, STATE = range(6)
 FP16, BF16 = 0, 1
-SITE_NONE, SITE_ACC, SITE_A, SITE_B = 0, 1, 2, 3
+SITE_NONE, SITE_ACC, SITE_A, SITE_B, SITE_PRODUCT = 0, 1, 2, 3, 4
 CORRECT_NONE, CORRECT_ZERO, CORRECT_RECOMPUTE = 0, 1, 2
 BOUND_ROWCOL, BOUND_GLOBAL = 0, 1
 MASKED, SDC, DETECTED = 0, 1, 2
-KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A = 0, 1, 2, 3
+KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A, KIND_ALL_PRODUCT = 0, 1, 2, 3, 4
 BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 
 # Symbols include/fi.h declares; the loader checks every one.

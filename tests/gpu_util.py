@@ -71,6 +71,24 @@ def compare_records(gpu, ora, faults, exact_words=False, site_tol=0.0):
             bad.append((t, "cls", int(cls_of(gpu[t:t + 1])[0]), int(o["cls"])))
         kind = int(faults["kind"][t])
         if o["valid"] and kind != 0:
+            if kind == 4:
+                # product-term fault: the site words are the accumulator before and after the
+                # write-back (acc - re) + re_err, with the same re and re_err on both sides
+                w = [np.array([x], np.uint32).view(np.float32)[0] for x in
+                     (g["site_word_before"], o["site_word_before"], g["site_word_after"], o["site_word_after"])]
+                gb, ob, ga, oa = [float(x) for x in w]
+                if exact_words:
+                    if int(g["site_word_before"]) != int(o["site_word_before"]) or not (
+                            int(g["site_word_after"]) == int(o["site_word_after"]) or (np.isnan(ga) and np.isnan(oa))):
+                        bad.append((t, "site_words", gb, ob, ga, oa))
+                else:
+                    if not abs(gb - ob) <= site_tol:
+                        bad.append((t, "site_word_before", gb, ob))
+                    same_after = (np.isnan(ga) and np.isnan(oa)) or ga == oa or \
+                        abs(ga - oa) <= site_tol + 1e-6 * max(1.0, abs(oa), abs(ob))
+                    if not same_after:
+                        bad.append((t, "site_word_after", ga, oa))
+                continue
             if kind == 1 and not exact_words:
                 # the two accumulators followed different summation orders: same value to within
                 # the unfaulted tolerance, not the same bits

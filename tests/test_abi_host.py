@@ -42,7 +42,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(fi.PlanDesc) == 48
 
 
-@pytest.mark.parametrize("kind_mode,nbits", [(0, 1), (0, 2), (1, 1), (2, 4), (3, 1)])
+@pytest.mark.parametrize("kind_mode,nbits", [(0, 1), (0, 2), (1, 1), (2, 4), (3, 1), (4, 1), (4, 2), (4, 4)])
 def test_sampler_equals_oracle(kind_mode, nbits):
     for (M, N, K, kb, seed, first) in [(128, 128, 128, 32, 0, 0), (512, 3072, 768, 32, 1, 100),
                                        (3136, 64, 576, 32, 2 ** 63 + 5, 7), (4096, 4096, 4096, 64, 3, 0)]:

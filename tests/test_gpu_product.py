@@ -1,0 +1,115 @@
+"""GPU parity for the paper's product-term fault (Sec. III-E write-back, Eq. 1-2): HIP path
+through the C ABI against the oracle, element by element."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import gpu_util as gu
+from oracle import pyoracle as orc
+from paper_2311_05782_amd import fi, workloads as wl
+from test_gpu_parity import _campaign_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _safe_product_faults(Aw, Bw, fmt, n, seed):
+    """Product-term faults that keep the exact regime exact: operands are even integers, so a
+    non-zero product is an integer of magnitude >= 4 with few significant bits; flipping its
+    sign, one of its two lowest exponent bits or one of its three highest mantissa bits gives a
+    dyadic value whose sum with small integers is exactly representable in every order.  Zero
+    products get the same masks in BF16 (the result is tiny and absorbed by any non-zero sum)
+    and only sign or exponent masks in FP16 (still zero, or 2^-14 .. 2^-13 times a small integer
+    would not be exact: those masks are left out)."""
+    rng = np.random.default_rng(seed)
+    (M, K), N = Aw.shape, Bw.shape[0]
+    mant = 10 if fmt == orc.FP16 else 7
+    masks = [0x8000, 1 << mant, 1 << (mant + 1), 1 << (mant - 1), 1 << (mant - 2), 1 << (mant - 3),
+             (1 << mant) | 0x8000, 3 << (mant - 2)]
+    A = orc.decode_array(Aw.ravel(), fmt).reshape(Aw.shape)
+    B = orc.decode_array(Bw.ravel(), fmt).reshape(Bw.shape)
+    rows = []
+    while len(rows) < n:
+        i, j, k = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(K))
+        m = masks[int(rng.integers(len(masks)))]
+        if A[i, k] * B[j, k] == 0 and fmt == orc.FP16 and m != 0x8000:
+            continue
+        rows.append((orc.SITE_PRODUCT, i, j, k, m))
+    rows += [(orc.SITE_PRODUCT, M - 1, N - 1, K - 1, 0x8000), (orc.SITE_PRODUCT, 0, 0, 0, 0x8000),
+             (orc.SITE_PRODUCT, M - 1, 0, 15, 1 << mant), (orc.SITE_PRODUCT, 0, N - 1, 16, 1 << mant),
+             (orc.SITE_PRODUCT, M, 0, 0, 1), (orc.SITE_PRODUCT, 0, 0, K, 1), (orc.SITE_NONE, 0, 0, 0, 0)]
+    return orc.make_faults(rows)
+
+
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("shape", [(300, 200, 192, 32), (257, 65, 128, 64), (96, 40, 96, 48), (64, 64, 64, 16)])
+def test_exact_regime_product_faults_bit_equal(fmt, cfg, shape):
+    M, N, K, kb = shape
+    if cfg >= 3 and K % 64:
+        pytest.skip("multi-trial tiles need whole 64-wide k-tiles")
+    Aw, Bw = wl.small_integers(M, N, K, fmt, seed=M + N + 1, lim=4, step=2)
+    faults = _safe_product_faults(Aw, Bw, fmt, 30, seed=K + cfg)
+    plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg, group=3)
+    p = orc.problem(M, N, K, kb, fmt)
+    for policy in (orc.CORRECT_NONE, orc.CORRECT_RECOMPUTE):
+        recs, cout = gu.gpu_campaign(plan, faults, policy, want_c=True)
+        ora = orc.campaign(p, Aw, Bw, faults, policy, orc.MODE_AFFECTED)
+        for t in range(len(faults)):
+            o, cf, cc = orc.trial(p, Aw, Bw, faults[t:t + 1], policy, orc.MODE_FULL, want_outputs=True)
+            assert np.array_equal(cout[t].view(np.uint32), cc.view(np.uint32)), (t, faults[t])
+            for name in ("n_flagged", "n_bitdiff", "n_dev_pre", "n_dev_post"):
+                assert int(recs[t][name]) == int(o[name]), (name, t, faults[t])
+        s = gu.compare_records(recs, ora, faults, exact_words=True)
+        assert not s["mismatches"], s["mismatches"][:5]
+        assert s["gpu_counts"] == s["oracle_counts"]
+    plan.destroy()
+
+
+@pytest.mark.parametrize("nbits", [1, 2, 4])
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+def test_product_fault_campaign_random_operands(fmt, nbits):
+    # ReLU-like activations (half zeros) as in the paper's CNNs (Sec. V-B scenario i), 1 / 2 / 4-bit
+    # masks (Sec. IV-C), sites from the product sampler.
+    base = wl.resnet_conv()
+    A, B = wl.gaussian(384, 192, 256, fmt, seed=50 + nbits)
+    Af = orc.decode_array(A.ravel(), fmt).reshape(A.shape)
+    A = wl.to_words(np.maximum(Af, 0), fmt)
+    w = dataclasses.replace(base, name="product_%d" % nbits, M=384, N=192, K=256, kb=32, fmt=fmt, A=A, B=B,
+                            n_trials=3000, kind_mode=fi.KIND_ALL_PRODUCT, nbits=nbits,
+                            policies=(wl.CORRECT_ZERO,), fault_seed=7 + nbits)
+    s = _campaign_parity(w)[wl.CORRECT_ZERO]
+    assert sum(s["gpu_counts"]) == 3000 and s["gpu_counts"][0] > 0 and s["gpu_counts"][2] > 0
+
+
+def test_product_fault_campaign_one_trial_kernel_ragged_k():
+    # K = 96 is not a multiple of the 64-wide k-tile: every trial takes the one-trial kernel.
+    base = wl.tiny()
+    A, B = wl.gaussian(130, 70, 96, orc.BF16, seed=61)
+    w = dataclasses.replace(base, name="product_k96", M=130, N=70, K=96, kb=48, fmt=orc.BF16, A=A, B=B,
+                            n_trials=1200, kind_mode=fi.KIND_ALL_PRODUCT, nbits=1,
+                            policies=(wl.CORRECT_RECOMPUTE,), fault_seed=3)
+    _campaign_parity(w)
+    for cfg in (0, 1, 2):
+        _campaign_parity(dataclasses.replace(w, n_trials=300), cfg=cfg)
+
+
+def test_zero_difference_statistic_fp16_versus_bf16():
+    # Table III's statistic: the share of trials whose destination register is unchanged by the
+    # write-back.  On half-zero activations FP16 turns zeros into non-zeros far more often.
+    share = {}
+    for fmt in (orc.FP16, orc.BF16):
+        A, B = wl.gaussian(256, 128, 256, fmt, seed=70)
+        Af = orc.decode_array(A.ravel(), fmt).reshape(A.shape)
+        A = wl.to_words(np.maximum(Af, 0), fmt)
+        plan = gu.make_plan(A, B, 64, fmt)
+        faults = fi.fi_sample_faults(5, 0, 4000, plan.desc, fi.KIND_ALL_PRODUCT, 1)
+        recs = gu.gpu_campaign(plan, faults, fi.CORRECT_NONE)
+        p = orc.problem(256, 128, 256, 64, fmt)
+        ora = orc.campaign(p, A, B, gu.to_orc_faults(faults), orc.CORRECT_NONE, orc.MODE_AFFECTED)
+        g = float(np.mean(recs["site_word_before"] == recs["site_word_after"]))
+        o = float(np.mean(ora["site_word_before"] == ora["site_word_after"]))
+        assert abs(g - o) < 0.02, (g, o)
+        share[fmt] = g
+        plan.destroy()
+    assert share[orc.BF16] > share[orc.FP16] + 0.1
