@@ -121,6 +121,46 @@ uint16_t orc_round16(float x, int fmt) {
   return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)q);
 }
 
+/* ------------------------ Sec. VI-A: exponent-only checks of a product
+ * They read only the exponent field of the register holding the (possibly
+ * corrupted) product.
+ *   Bound check (BF16): with the exponent's most significant bit set, a 1 in any
+ *     of the next three bits (1eeexxxx) means |value| >= 2^17 = 131072 (the
+ *     paper's Table IV) - not a plausible partial weight/activation product.
+ *     Correction: clear those three bits.
+ *   Range check: m1*m2 < 4 gives e_m <= e_1 + e_2 + 1; with biased fields
+ *     be_m <= be_1 + be_2 - bias + 1 (not below 0: products that underflow have
+ *     field 0).  A larger erroneous exponent is detected.  Correction "max":
+ *     replace it by the bound; "flip": clear its 1 bits starting from the
+ *     rightmost until it no longer exceeds the bound. */
+uint16_t orc_product_check(uint16_t w_err, uint16_t w_a, uint16_t w_b, int fmt, int mode, int* fired) {
+  int mb = fmt == ORC_BF16 ? 7 : 10, eb = fmt == ORC_BF16 ? 8 : 5, bias = fmt == ORC_BF16 ? 127 : 15;
+  unsigned emask = (1u << eb) - 1u;
+  unsigned e = ((unsigned)w_err >> mb) & emask;
+  int hit = 0;
+  if (mode == ORC_PCHECK_BOUND) {
+    if (fmt == ORC_BF16 && (e & 0x80u) && (e & 0x70u)) {
+      hit = 1;
+      e &= ~0x70u;
+    }
+  } else if (mode == ORC_PCHECK_RANGE_MAX || mode == ORC_PCHECK_RANGE_FLIP) {
+    int e1 = (int)(((unsigned)w_a >> mb) & emask), e2 = (int)(((unsigned)w_b >> mb) & emask);
+    int bound = e1 + e2 - bias + 1;
+    if (bound < 0) bound = 0;
+    if ((int)e > bound) {
+      hit = 1;
+      if (mode == ORC_PCHECK_RANGE_MAX) {
+        e = (unsigned)bound;
+      } else {
+        for (int bit = 0; bit < eb && (int)e > bound; ++bit)
+          if ((e >> bit) & 1u) e &= ~(1u << bit);
+      }
+    }
+  }
+  if (fired) *fired = hit;
+  return (uint16_t)(((unsigned)w_err & ~(emask << mb)) | (e << mb));
+}
+
 /* --------------------------------- O2 / O3: blocked FP32 dot product
  * Sec. IV-C: low-precision products accumulated into one FP32 number.
  * acc starts at +0; k ascends; each product is rounded once to binary32
@@ -142,8 +182,10 @@ uint16_t orc_round16(float x, int fmt) {
 typedef struct {
   int acc_s;  uint32_t acc_mask;
   int prod_k; uint32_t prod_mask; int fmt;
+  int check;          /* ORC_PCHECK_*: exponent-only check applied to re_err (Sec. VI-A) */
+  uint32_t* fired;    /* where to note that it fired, or NULL */
 } elem_fault;
-static const elem_fault NO_FAULT = {-1, 0, -1, 0, 0};
+static const elem_fault NO_FAULT = {-1, 0, -1, 0, 0, 0, NULL};
 
 static float dot_blocked(const float* a, const float* b, int K, int kb, elem_fault ef,
                          uint32_t* word_before, uint32_t* word_after) {
@@ -158,7 +200,15 @@ static float dot_blocked(const float* a, const float* b, int K, int kb, elem_fau
         float exact = a[ef.prod_k] * b[ef.prod_k];
         uint16_t w = orc_round16(exact, ef.fmt);
         float re = dec(w, ef.fmt);
-        float re_err = dec((uint16_t)(w ^ (ef.prod_mask & 0xFFFFu)), ef.fmt);
+        uint16_t w_err = (uint16_t)(w ^ (ef.prod_mask & 0xFFFFu));
+        if (ef.check != ORC_PCHECK_NONE) {
+          /* the operand words: decoded operands convert back exactly */
+          int hit = 0;
+          w_err = orc_product_check(w_err, orc_round16(a[ef.prod_k], ef.fmt), orc_round16(b[ef.prod_k], ef.fmt),
+                                    ef.fmt, ef.check, &hit);
+          if (ef.fired) *ef.fired = (uint32_t)hit;
+        }
+        float re_err = dec(w_err, ef.fmt);
         if (word_before) *word_before = word_of(acc);
         float re_prime = acc - re;
         acc = re_prime + re_err;
@@ -393,8 +443,10 @@ static int site_valid(const orc_problem* p, const orc_fault* f) {
 
 /* The fault of one output element: accumulator flip after k-block `kblock`, or a
  * product-term fault on the product with k = `kblock`. */
-static elem_fault element_fault(const orc_problem* p, const orc_fault* f) {
+static elem_fault element_fault(const orc_problem* p, const orc_fault* f, orc_record* rec) {
   elem_fault ef = NO_FAULT;
+  ef.check = p->product_check;
+  ef.fired = rec ? &rec->product_flag : NULL;
   if (f->kind == ORC_SITE_ACC) { ef.acc_s = (int)f->kblock; ef.acc_mask = f->xor_mask; }
   if (f->kind == ORC_SITE_PRODUCT) { ef.prod_k = (int)f->kblock; ef.prod_mask = f->xor_mask; ef.fmt = p->fmt; }
   return ef;
@@ -422,7 +474,7 @@ static int trial_full(const orc_problem* p, const uint16_t* A, const uint16_t* B
 
   /* The faulty execution: every element is recomputed with the fault in place. */
   if (f->kind == ORC_SITE_ACC || f->kind == ORC_SITE_PRODUCT) {
-    gemm_decoded(M, N, K, p->kb, Af, Bt, (int)f->row, (int)f->col, element_fault(p, f),
+    gemm_decoded(M, N, K, p->kb, Af, Bt, (int)f->row, (int)f->col, element_fault(p, f, rec),
                  Cf, NULL, NULL, &rec->site_word_before, &rec->site_word_after);
   } else if (f->kind == ORC_SITE_A) {
     uint16_t w = a_word(p, A, (int)f->row, (int)f->col);
@@ -470,7 +522,7 @@ static int trial_affected(const orc_problem* p, const uint16_t* A, const uint16_
     load_a_row(p, A, i, a);
     load_b_col(p, B, j, b);
     float c_star = dot_blocked(a, b, K, p->kb, NO_FAULT, NULL, NULL);
-    float c_f = dot_blocked(a, b, K, p->kb, element_fault(p, f),
+    float c_f = dot_blocked(a, b, K, p->kb, element_fault(p, f, rec),
                             &rec->site_word_before, &rec->site_word_after);
     double R, S;
     dot_double(a, b, K, &R, &S);

@@ -40,6 +40,8 @@ enum { ORC_CORRECT_NONE = 0, ORC_CORRECT_ZERO = 1, ORC_CORRECT_RECOMPUTE = 2 };
 enum { ORC_BOUND_ROWCOL = 0, ORC_BOUND_GLOBAL = 1 };
 enum { ORC_MASKED = 0, ORC_SDC = 1, ORC_DETECTED = 2 };
 enum { ORC_MODE_FULL = 0, ORC_MODE_AFFECTED = 1 };
+/* Exponent-only checks of an erroneous product (Sec. VI-A). */
+enum { ORC_PCHECK_NONE = 0, ORC_PCHECK_BOUND = 1, ORC_PCHECK_RANGE_MAX = 2, ORC_PCHECK_RANGE_FLIP = 3 };
 enum { ORC_KIND_ALL_ACC = 0, ORC_KIND_ALL_A = 1, ORC_KIND_ALL_B = 2, ORC_KIND_MIX_ACC_A = 3,
        ORC_KIND_ALL_PRODUCT = 4 };
 
@@ -53,6 +55,7 @@ typedef struct {
   int bound_mode;
   float gamma;          /* slack factor on the bound, >= 1 */
   long lda, ldb;        /* leading dimensions in elements */
+  int product_check;    /* ORC_PCHECK_*: applied to the erroneous product of a PRODUCT fault */
 } orc_problem;
 
 /* One fault.  ACC: (row=i, col=j, kblock=s, 32-bit mask).
@@ -79,6 +82,8 @@ typedef struct {
   uint32_t n_border_tau;      /* affected elements inside the guard band around tau */
   uint32_t valid;             /* 0: site out of range, trial ran fault-free */
   uint32_t cls;               /* ORC_MASKED / ORC_SDC / ORC_DETECTED */
+  uint32_t product_flag;      /* PRODUCT fault: 1 if the exponent-only check fired */
+  uint32_t reserved;
 } orc_record;
 
 /* O1: exact value of a 16-bit pattern, held in a float. */
@@ -87,6 +92,12 @@ float orc_decode16(uint16_t w, int fmt);
 /* binary32 -> FP16 / BF16 word, round to nearest even (the format a product is held in,
  * Sec. IV-C, Sec. VI-A). */
 uint16_t orc_round16(float x, int fmt);
+
+/* Sec. VI-A: exponent-only detection and correction of an erroneous product word w_err given
+ * the two operand words.  Returns the corrected word (w_err itself when nothing fires or mode
+ * is NONE); *fired = 1 if the detection criterion was violated.  BoundCheck is defined for
+ * BF16 only (the paper's Table IV) and never fires for FP16. */
+uint16_t orc_product_check(uint16_t w_err, uint16_t w_a, uint16_t w_b, int fmt, int mode, int* fired);
 void  orc_decode_array(const uint16_t* in, size_t n, int fmt, float* out);
 
 /* O2: blocked FP32 dot product of row i of A and column j of B, no fault. */

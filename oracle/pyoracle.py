@@ -25,7 +25,7 @@ KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A, KIND_ALL_PRODUCT = 0, 1, 2
 class Problem(C.Structure):
     _fields_ = [("M", C.c_int), ("N", C.c_int), ("K", C.c_int), ("kb", C.c_int),
                 ("fmt", C.c_int), ("b_layout", C.c_int), ("bound_mode", C.c_int),
-                ("gamma", C.c_float), ("lda", C.c_long), ("ldb", C.c_long)]
+                ("gamma", C.c_float), ("lda", C.c_long), ("ldb", C.c_long), ("product_check", C.c_int)]
 
 
 FAULT_DTYPE = np.dtype([("kind", "<u4"), ("row", "<u4"), ("col", "<u4"),
@@ -36,7 +36,8 @@ RECORD_DTYPE = np.dtype([("max_dev_pre", "<f8"), ("max_dev_post", "<f8"),
                          ("n_dev_pre", "<u4"), ("n_dev_post", "<u4"),
                          ("site_word_before", "<u4"), ("site_word_after", "<u4"),
                          ("n_border_T", "<u4"), ("n_border_tau", "<u4"),
-                         ("valid", "<u4"), ("cls", "<u4")])
+                         ("valid", "<u4"), ("cls", "<u4"), ("product_flag", "<u4"), ("reserved", "<u4")])
+PCHECK_NONE, PCHECK_BOUND, PCHECK_RANGE_MAX, PCHECK_RANGE_FLIP = 0, 1, 2, 3
 
 DEFAULT_GAMMA = 1.0 + 2.0 ** -11
 
@@ -66,6 +67,8 @@ def lib():
         L.orc_decode16.argtypes = [C.c_uint16, C.c_int]
         L.orc_round16.restype = C.c_uint16
         L.orc_round16.argtypes = [C.c_float, C.c_int]
+        L.orc_product_check.restype = C.c_uint16
+        L.orc_product_check.argtypes = [C.c_uint16, C.c_uint16, C.c_uint16, C.c_int, C.c_int, C.POINTER(C.c_int)]
         L.orc_decode_array.restype = None
         L.orc_decode_array.argtypes = [u16p, C.c_size_t, C.c_int, f32p]
         L.orc_dot.restype = C.c_float
@@ -105,12 +108,12 @@ def _u16(a):
 
 
 def problem(M, N, K, kb, fmt, b_layout=0, bound_mode=BOUND_ROWCOL, gamma=DEFAULT_GAMMA,
-            lda=None, ldb=None):
+            lda=None, ldb=None, product_check=0):
     if lda is None:
         lda = K
     if ldb is None:
         ldb = K if b_layout == 0 else N
-    return Problem(M, N, K, kb, fmt, b_layout, bound_mode, gamma, lda, ldb)
+    return Problem(M, N, K, kb, fmt, b_layout, bound_mode, gamma, lda, ldb, product_check)
 
 
 def decode16(w, fmt):
@@ -120,6 +123,13 @@ def decode16(w, fmt):
 def round16(x, fmt):
     """binary32 value -> FP16 / BF16 word, round to nearest even."""
     return int(lib().orc_round16(float(np.float32(x)), fmt))
+
+
+def product_check(w_err, w_a, w_b, fmt, mode):
+    """(corrected word, fired) of the exponent-only check of Sec. VI-A."""
+    fired = C.c_int(0)
+    w = lib().orc_product_check(int(w_err), int(w_a), int(w_b), fmt, mode, C.byref(fired))
+    return int(w), int(fired.value)
 
 
 def decode_array(words, fmt):
