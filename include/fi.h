@@ -54,6 +54,8 @@ enum { FI_SITE_NONE = 0, FI_SITE_ACC = 1, FI_SITE_A = 2, FI_SITE_B = 3, FI_SITE_
 enum { FI_CORRECT_NONE = 0, FI_CORRECT_ZERO = 1, FI_CORRECT_RECOMPUTE = 2 };
 enum { FI_BOUND_ROWCOL = 0, FI_BOUND_GLOBAL = 1 };
 enum { FI_MASKED = 0, FI_SDC = 1, FI_DETECTED = 2 };
+/* Exponent-only checks of the erroneous product of a PRODUCT fault (Sec. VI-A). */
+enum { FI_PCHECK_NONE = 0, FI_PCHECK_BOUND = 1, FI_PCHECK_RANGE_MAX = 2, FI_PCHECK_RANGE_FLIP = 3 };
 enum { FI_KIND_ALL_ACC = 0, FI_KIND_ALL_A = 1, FI_KIND_ALL_B = 2, FI_KIND_MIX_ACC_A = 3,
        FI_KIND_ALL_PRODUCT = 4 };
 
@@ -94,7 +96,7 @@ typedef struct {
   uint32_t n_border_T;       /* changed elements within max(2 tau, T/64) of T       */
   uint32_t n_border_tau;     /* changed elements with tau/2 <= |c - C*| <= 2 tau    */
   uint32_t status;           /* 0 ok, 1 site out of range (trial ran fault-free)    */
-  uint32_t reserved;
+  uint32_t product_flag;     /* PRODUCT fault: 1 if the exponent-only check fired   */
 } fi_trial_result;
 
 /* Problem description.  A is M x K, row i at dA + i*lda (K contiguous).
@@ -143,6 +145,19 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
  * output tile are scheduled next to each other, 1..4096.  Results do not depend on
  * either (every shape accumulates each element in the same order); `stream` is unused. */
 fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, void* stream);
+
+/* Exponent-only detection / correction applied to the erroneous product re_err of every
+ * PRODUCT fault before the write-back (Sec. VI-A; correction only where detection fires,
+ * Sec. VI-B).  It reads the exponent field of the 16-bit product word:
+ *   FI_PCHECK_BOUND      BF16 only (never fires for FP16): exponent 1eeexxxx with a 1 among
+ *                        eee, i.e. |value| >= 2^17; correction clears those three bits;
+ *   FI_PCHECK_RANGE_MAX  exponent field above be_a + be_b - bias + 1 (not below 0): replaced
+ *                        by that bound;
+ *   FI_PCHECK_RANGE_FLIP same detection; correction clears the field's 1 bits from the
+ *                        rightmost until it no longer exceeds the bound.
+ * fi_trial_result.product_flag says whether it fired.  Default FI_PCHECK_NONE.
+ * INVALID_ARG for an unknown mode. */
+fi_status fi_plan_set_product_check(fi_plan* plan, uint32_t mode);
 
 /* Writes a NUL-terminated description of the kernels the plan launches for a
  * campaign (template shape, threads, trials per workgroup) into h_buf (HOST memory,

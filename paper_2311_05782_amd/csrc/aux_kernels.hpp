@@ -176,7 +176,8 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
                                                                uint32_t M, uint32_t N, uint32_t K, uint32_t kb,
                                                                const uint16_t* __restrict__ A,
                                                                const uint16_t* __restrict__ B, uint32_t lda,
-                                                               uint32_t ldb, uint32_t* __restrict__ perm,
+                                                               uint32_t ldb, int product_check_mode,
+                                                               uint32_t* __restrict__ perm,
                                                                uint32_t* __restrict__ counts,
                                                                uint32_t* __restrict__ desc,
                                                                fi_trial_result* __restrict__ results) {
@@ -218,8 +219,10 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
       d[3] = (x.kblock + 1) * kb / 16 - 1; d[4] = x.xor_mask; d[5] = 0;
     } else if (k == 4) {
       float re, re_err;
+      bool fired;
       product_fault_terms<DT>(A[(size_t)x.row * lda + x.kblock], B[(size_t)x.col * ldb + x.kblock], x.xor_mask,
-                              re, re_err);
+                              product_check_mode, re, re_err, fired);
+      if (fired) results[t].product_flag = 1;
       d[3] = (x.kblock / 16) | 0x40000000u; d[4] = __float_as_uint(re); d[5] = __float_as_uint(re_err);
     } else {
       d[3] = 0xFFFFFFFFu; d[4] = 0; d[5] = 0;

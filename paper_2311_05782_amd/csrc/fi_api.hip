@@ -77,6 +77,7 @@ struct fi_plan {
   uint32_t* desc;          // [(perm_cap + 8) * 5] descriptors of the multi-trial kernel's trials
   uint32_t perm_cap;
   int n_cus;               // compute units of the device: grid of the persistent kernel
+  int product_check;       // FI_PCHECK_*
 };
 
 namespace {
@@ -388,6 +389,14 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
   return FI_OK;
 }
 
+fi_status fi_plan_set_product_check(fi_plan* plan, uint32_t mode) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (mode > FI_PCHECK_RANGE_FLIP) return fail(FI_INVALID_ARG, "unknown product check %u", mode);
+  plan->product_check = (int)mode;
+  return FI_OK;
+}
+
 fi_status fi_plan_describe(const fi_plan* plan, char* h_buf, uint64_t n) {
   fi_status st = check_plan(plan);
   if (st != FI_OK) return st;
@@ -425,6 +434,7 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
   a.results = d_results;
   a.c_out = d_c_out;
   a.policy = (int)policy;
+  a.product_check = plan->product_check;
   if (plan->mcfg >= 0) {
     // Split the batch on the device: trials whose fault leaves the operands alone and lands on a
     // k-tile boundary share staged operands R at a time; the rest take the single-trial kernel.
@@ -439,11 +449,13 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
     uint32_t* counts = plan->perm + plan->perm_cap;
     if (plan->d.dtype == FI_BF16)
       hipLaunchKernelGGL(fi::partition_trials_kernel<FI_BF16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
-                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->perm,
+                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
+                         plan->perm,
                          counts, plan->desc, d_results);
     else
       hipLaunchKernelGGL(fi::partition_trials_kernel<FI_FP16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
-                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->perm,
+                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
+                         plan->perm,
                          counts, plan->desc, d_results);
     FI_HIP(hipGetLastError());
     a.perm = plan->perm;

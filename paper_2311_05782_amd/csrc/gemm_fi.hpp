@@ -61,6 +61,7 @@ struct GemmArgs {
   const float* s_abs;       // [M][N] sum_k |a b|        (campaign)
   float* c_out;             // campaign: nullable [n_trials][M][N]; golden: [M][N]
   int policy;
+  int product_check;        // FI_PCHECK_* applied to the erroneous product of PRODUCT faults
   // Optional split of the batch (both NULL: every trial goes through gemm_fi_kernel in list order).
   // perm[0 .. c0) are the trials the multi-trial kernel takes, perm[c0 .. c0+c1) the others;
   // part_counts = {c0, c1}.
@@ -125,13 +126,46 @@ __device__ __forceinline__ uint32_t round16(float x) {
   }
 }
 
-// Product-term fault (Sec. III-E): re = a*b held in the operand format, re_err = its word XOR mask.
+// Exponent-only check of an erroneous product word (Sec. VI-A).  Bound check (BF16): exponent
+// 1eeexxxx with a 1 among eee means |value| >= 2^17; the three bits are cleared.  Range check:
+// the product's exponent field cannot exceed be_a + be_b - bias + 1 (from m1*m2 < 4); "max"
+// replaces a larger field by the bound, "flip" clears its 1 bits from the right until it fits.
 template <int DT>
-__device__ __forceinline__ void product_fault_terms(uint32_t a_word, uint32_t b_word, uint32_t mask,
-                                                    float& re, float& re_err) {
+__device__ __forceinline__ uint32_t product_check(uint32_t w_err, uint32_t a_word, uint32_t b_word, int mode,
+                                                  bool& fired) {
+  constexpr int MB = DT == FI_BF16 ? 7 : 10, EB = DT == FI_BF16 ? 8 : 5, BIAS = DT == FI_BF16 ? 127 : 15;
+  constexpr uint32_t EMASK = (1u << EB) - 1u;
+  uint32_t e = (w_err >> MB) & EMASK;
+  fired = false;
+  if (mode == FI_PCHECK_BOUND) {
+    if (DT == FI_BF16 && (e & 0x80u) && (e & 0x70u)) { fired = true; e &= ~0x70u; }
+  } else if (mode == FI_PCHECK_RANGE_MAX || mode == FI_PCHECK_RANGE_FLIP) {
+    const int bound = max((int)((a_word >> MB) & EMASK) + (int)((b_word >> MB) & EMASK) - BIAS + 1, 0);
+    if ((int)e > bound) {
+      fired = true;
+      if (mode == FI_PCHECK_RANGE_MAX) {
+        e = (uint32_t)bound;
+      } else {
+#pragma unroll
+        for (int bit = 0; bit < EB; ++bit)
+          if ((int)e > bound) e &= ~(1u << bit);
+      }
+    }
+  }
+  return (w_err & ~(EMASK << MB) & 0xFFFFu) | (e << MB);
+}
+
+// Product-term fault (Sec. III-E): re = a*b held in the operand format, re_err = its word XOR
+// mask, passed through the exponent-only check if one is enabled.
+template <int DT>
+__device__ __forceinline__ void product_fault_terms(uint32_t a_word, uint32_t b_word, uint32_t mask, int check,
+                                                    float& re, float& re_err, bool& fired) {
   const uint32_t w = round16<DT>(__fmul_rn(decode16<DT>(a_word), decode16<DT>(b_word)));
+  uint32_t w_err = (w ^ mask) & 0xFFFFu;
+  fired = false;
+  if (check != FI_PCHECK_NONE) w_err = product_check<DT>(w_err, a_word, b_word, check, fired);
   re = decode16<DT>(w);
-  re_err = decode16<DT>((w ^ mask) & 0xFFFFu);
+  re_err = decode16<DT>(w_err);
 }
 // The write-back of Eq. (1)-(2): two binary32 operations, each rounded once.
 __device__ __forceinline__ float write_back(float re_sum, float re, float re_err) {
@@ -425,8 +459,10 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   auto accumulator_fault = [&]() {
     const bool product = fkind == FI_SITE_PRODUCT;
     float re = 0.0f, re_err = 0.0f;
+    bool fired = false;
     if (product)
-      product_fault_terms<DT>(p.A[(size_t)frow * p.lda + fk], p.B[(size_t)fcol * p.ldb + fk], fmask, re, re_err);
+      product_fault_terms<DT>(p.A[(size_t)frow * p.lda + fk], p.B[(size_t)fcol * p.ldb + fk], fmask,
+                              p.product_check, re, re_err, fired);
     uint32_t before = 0, after = 0;
     static_for<TM * TN>([&](auto tt) {
       constexpr int i = tt / TN, j = tt % TN;
@@ -447,6 +483,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     if (lane == sel_lane) {
       p.results[trial].site_word_before = before;
       p.results[trial].site_word_after = after;
+      if (fired) p.results[trial].product_flag = 1;
     }
   };
 

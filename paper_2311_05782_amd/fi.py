@@ -20,11 +20,13 @@ SITE_NONE, SITE_ACC, SITE_A, SITE_B, SITE_PRODUCT = 0, 1, 2, 3, 4
 CORRECT_NONE, CORRECT_ZERO, CORRECT_RECOMPUTE = 0, 1, 2
 BOUND_ROWCOL, BOUND_GLOBAL = 0, 1
 MASKED, SDC, DETECTED = 0, 1, 2
+PCHECK_NONE, PCHECK_BOUND, PCHECK_RANGE_MAX, PCHECK_RANGE_FLIP = 0, 1, 2, 3
 KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A, KIND_ALL_PRODUCT = 0, 1, 2, 3, 4
 BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 
 # Symbols include/fi.h declares; the loader checks every one.
 EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
+           "fi_plan_set_product_check",
            "fi_gemm_inject_batch", "fi_detect_correct", "fi_classify", "fi_sample_faults",
            "fi_last_error"]
 
@@ -34,7 +36,7 @@ RESULT_DTYPE = np.dtype([("n_flagged", "<u4"), ("n_bitdiff", "<u4"), ("n_dev_pre
                          ("n_dev_post", "<u4"), ("max_dev_pre", "<f4"), ("max_dev_post", "<f4"),
                          ("site_word_before", "<u4"), ("site_word_after", "<u4"),
                          ("n_border_T", "<u4"), ("n_border_tau", "<u4"), ("status", "<u4"),
-                         ("reserved", "<u4")])
+                         ("product_flag", "<u4")])
 assert FAULT_DTYPE.itemsize == 20 and RESULT_DTYPE.itemsize == 48
 
 
@@ -77,6 +79,7 @@ def lib():
     L.fi_plan_buffer.argtypes = [vp, C.c_uint32, C.POINTER(vp)]
     L.fi_plan_tune.argtypes = [vp, C.c_int32, C.c_int32, vp]
     L.fi_plan_describe.argtypes = [vp, C.c_char_p, C.c_uint64]
+    L.fi_plan_set_product_check.argtypes = [vp, C.c_uint32]
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_detect_correct.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_classify.argtypes = [vp, vp, C.c_uint32, vp, vp, vp]
@@ -162,6 +165,9 @@ class Plan:
 
     def tune(self, tile_config=-1, trial_group=-1, stream=None):
         _check(lib().fi_plan_tune(self._h, tile_config, trial_group, _stream(stream)))
+
+    def set_product_check(self, mode):
+        _check(lib().fi_plan_set_product_check(self._h, mode))
 
     def describe(self):
         buf = C.create_string_buffer(512)

@@ -113,3 +113,78 @@ def test_zero_difference_statistic_fp16_versus_bf16():
         share[fmt] = g
         plan.destroy()
     assert share[orc.BF16] > share[orc.FP16] + 0.1
+
+
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+@pytest.mark.parametrize("cfg", [0, 5])
+@pytest.mark.parametrize("mode", [fi.PCHECK_BOUND, fi.PCHECK_RANGE_MAX, fi.PCHECK_RANGE_FLIP])
+def test_exponent_only_checks_exact_regime(fmt, cfg, mode):
+    # Sec. VI-A techniques applied to the erroneous product before the write-back.  Masks hit the
+    # product's exponent bits: uncorrected values would leave the exact regime, corrected ones
+    # (RangeCheck: at most 2^(e1+e2+1); BoundCheck: below 2^17) stay small dyadic numbers.
+    M, N, K, kb = 200, 136, 128, 32
+    Aw, Bw = wl.small_integers(M, N, K, fmt, seed=5, lim=4, step=2)
+    A = orc.decode_array(Aw.ravel(), fmt).reshape(Aw.shape)
+    B = orc.decode_array(Bw.ravel(), fmt).reshape(Bw.shape)
+    rng = np.random.default_rng(mode * 10 + cfg)
+    mant, ebits = (10, 5) if fmt == orc.FP16 else (7, 8)
+    rows = []
+    while len(rows) < 40:
+        i, j, k = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(K))
+        if A[i, k] * B[j, k] == 0:
+            continue
+        bit = mant + int(rng.integers(1, ebits))            # an exponent bit above the lowest
+        w = orc.round16(float(A[i, k] * B[j, k]), fmt)
+        if (w >> bit) & 1:                                     # flipping it down shrinks the value: fine too
+            pass
+        cw, fired = orc.product_check(w ^ (1 << bit), int(Aw[i, k]), int(Bw[j, k]), fmt, mode)
+        if not fired and abs(orc.decode16(cw, fmt)) > 4096:    # uncorrected and huge: outside the exact regime
+            continue
+        rows.append((orc.SITE_PRODUCT, i, j, k, 1 << bit))
+    faults = orc.make_faults(rows)
+    plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg)
+    plan.set_product_check(mode)
+    p = orc.problem(M, N, K, kb, fmt, product_check=mode)
+    recs, cout = gu.gpu_campaign(plan, faults, orc.CORRECT_NONE, want_c=True)
+    ora = orc.campaign(p, Aw, Bw, faults, orc.CORRECT_NONE, orc.MODE_AFFECTED)
+    assert np.array_equal(recs["product_flag"], ora["product_flag"])
+    if not (fmt == orc.FP16 and mode == fi.PCHECK_BOUND):
+        assert recs["product_flag"].sum() > 0
+    for t in range(len(faults)):
+        o, cf, cc = orc.trial(p, Aw, Bw, faults[t:t + 1], orc.CORRECT_NONE, orc.MODE_FULL, want_outputs=True)
+        assert np.array_equal(cout[t].view(np.uint32), cc.view(np.uint32)), (t, faults[t])
+    s = gu.compare_records(recs, ora, faults, exact_words=True)
+    assert not s["mismatches"], s["mismatches"][:5]
+    plan.set_product_check(fi.PCHECK_NONE)
+    recs0 = gu.gpu_campaign(plan, faults, orc.CORRECT_NONE)
+    assert recs0["product_flag"].sum() == 0
+    with pytest.raises(fi.FiError):
+        plan.set_product_check(7)
+    plan.destroy()
+
+
+def test_exponent_only_checks_confine_the_deviation_on_a_campaign():
+    # Fig. 9's claim on synthetic operands: 4-bit faults in BF16 products; with a technique applied
+    # the worst difference is bounded, and GPU and oracle agree trial by trial.
+    fmt = orc.BF16
+    A, B = wl.gaussian(256, 128, 256, fmt, seed=90)
+    plan = gu.make_plan(A, B, 64, fmt)
+    faults = fi.fi_sample_faults(9, 0, 3000, plan.desc, fi.KIND_ALL_PRODUCT, 4)
+    ra, cb, _ = orc.rowcol_absmax(orc.problem(256, 128, 256, 64, fmt), A, B)
+    site_tol = 2.0 ** -12 * 256 * float(ra.max()) * float(cb.max())
+    worst = {}
+    for mode in (fi.PCHECK_NONE, fi.PCHECK_BOUND, fi.PCHECK_RANGE_MAX, fi.PCHECK_RANGE_FLIP):
+        plan.set_product_check(mode)
+        recs = gu.gpu_campaign(plan, faults, fi.CORRECT_NONE)
+        p = orc.problem(256, 128, 256, 64, fmt, product_check=mode)
+        ora = orc.campaign(p, A, B, gu.to_orc_faults(faults), orc.CORRECT_NONE, orc.MODE_AFFECTED)
+        assert np.array_equal(recs["product_flag"], ora["product_flag"])
+        s = gu.compare_records(recs, ora, faults, site_tol=site_tol)
+        assert not s["mismatches"], s["mismatches"][:5]
+        worst[mode] = float(recs["max_dev_pre"].max())
+        print("product check", mode, "fired", int(recs["product_flag"].sum()), "worst deviation", worst[mode],
+              "classes", s["gpu_counts"])
+    assert worst[fi.PCHECK_NONE] > 1e30
+    assert worst[fi.PCHECK_BOUND] < 2.0 ** 18
+    assert worst[fi.PCHECK_RANGE_MAX] < 1e3 and worst[fi.PCHECK_RANGE_FLIP] < 1e3
+    plan.destroy()
