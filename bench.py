@@ -27,8 +27,8 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "1472fa0a6a1b0a7c8c2234a8c40a3c9120101d7610a390ffe77cb61e3cb2ea06",
-    "fetch_bytes": 2.2023e6 * 2.0 * 1024,
+    "sources_sha256": "aa147ebc9b8b5a5e547a49afce527f1e33225f411c05a90e2f7aabc28033ecf9",
+    "fetch_bytes": 2.2017e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }
 
