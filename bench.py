@@ -27,7 +27,7 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "aa147ebc9b8b5a5e547a49afce527f1e33225f411c05a90e2f7aabc28033ecf9",
+    "sources_sha256": "287fcbd9155dfa01586ac1df3e0e56ce7323d74c53cec773ae39e5e5ae07d5dd",
     "fetch_bytes": 2.2017e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }
@@ -88,6 +88,7 @@ def main():
     ap.add_argument("--group", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sources-digest", action="store_true", help="print the kernel sources' digest and exit")
+    ap.add_argument("--detector", action="store_true", help="also time the standalone detector kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference row for HBM byte counters)")
     args = ap.parse_args()
@@ -186,6 +187,29 @@ def main():
                      "flops_per_launch": flops_per_launch, "kernel_ms_avg": round(sum(kern_ms) / len(kern_ms), 3),
                      "kernel_ms_min": round(min(kern_ms), 3)},
     }
+    # The standalone detector / corrector (fi_detect_correct) on materialised outputs of the same
+    # problem: an HBM-bound kernel, 4 bytes read per element, priced against the 8 TB/s roof.
+    if default_run or args.detector:
+        batch = 16
+        c = torch.empty((batch, w.M, w.N), dtype=torch.float32, device="cuda").uniform_(-1.0, 1.0)
+        nfl = torch.zeros(batch, dtype=torch.int32, device="cuda")
+        for _ in range(2):
+            plan.fi_detect_correct(c, batch, policy, None, nfl)
+        dev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for a, b in dev:
+            a.record()
+            plan.fi_detect_correct(c, batch, policy, None, nfl)
+            b.record()
+        torch.cuda.synchronize()
+        dms = [a.elapsed_time(b) for a, b in dev]
+        dbytes = float(batch) * w.M * w.N * 4
+        dgbs = dbytes / (sum(dms) / len(dms) * 1e-3) / 1e9
+        out["detector_roofline"] = {"kernel": "detect_correct_kernel<4> (+ a 1-block counter fill)", "bound": "hbm",
+                                    "achieved": round(dgbs, 1), "peak": 8000.0, "unit": "GB/s",
+                                    "frac": round(dgbs / 8000.0, 4), "bytes_per_launch": dbytes,
+                                    "kernel_ms_avg": round(sum(dms) / len(dms), 4), "batch": batch,
+                                    "flagged": int(nfl.sum().item())}
+        del c
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
         out["cpu_baseline"]["value"] = float("%.4g" % out["cpu_baseline"]["value"])

@@ -113,46 +113,78 @@ __global__ void __launch_bounds__(256) transpose16_kernel(const uint16_t* __rest
 }
 
 // Detector and corrector on materialised outputs (Sec. VI-A detection,
-// Sec. VI-B correction only where detection fired).  grid = (chunks, batch);
-// one thread handles 4 consecutive elements of a row when N % 4 == 0, else 1.
+// Sec. VI-B correction only where detection fired).  HBM-bound: 4 bytes read per element,
+// writes only where a flag is set (plus 1 flag byte per element if asked for).
 // The threshold is built with the same three roundings as the fused epilogue:
 // fl32(fl32(kra_i * cb_j) * gamma).
+//
+// VEC == 4 (N % 4 == 0, 16-byte aligned): grid = (row slices, batch); a workgroup walks rows
+// blockIdx.x, + gridDim.x, ...; per row each thread takes groups of four 16-byte column chunks,
+// issuing the four loads before it looks at any of them (64 bytes in flight per lane), with
+// the column maxima read as 16-byte vectors too.  No division in the loop.
+// VEC == 1: one element per thread, any N and alignment.
 template <int VEC>
 __global__ void __launch_bounds__(256) detect_correct_kernel(
     float* __restrict__ C, int M, int N, const float* __restrict__ kra, const float* __restrict__ cb,
     float gamma, int bound_global, float t_global, int policy, const float* __restrict__ c_star,
     uint8_t* __restrict__ flags, uint32_t* __restrict__ n_flagged) {
   const size_t mn = (size_t)M * N;
-  const size_t per = mn / VEC;
   float* c = C + (size_t)blockIdx.y * mn;
   uint8_t* fl = flags ? flags + (size_t)blockIdx.y * mn : nullptr;
   uint32_t cnt = 0;
-  for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < per; q += (size_t)gridDim.x * 256) {
-    const size_t e0 = q * VEC;
-    const int row = (int)(e0 / (size_t)N), col0 = (int)(e0 % (size_t)N);
-    float v[VEC];
-    if constexpr (VEC == 4) {
-      f32x4_t t = *reinterpret_cast<const f32x4_t*>(c + e0);
-      v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
-    } else {
-      v[0] = c[e0];
-    }
-    const float kr = kra[row];
-    uint32_t fbits = 0;
+  if constexpr (VEC == 4) {
+    const int nv = N / 4;                                   // 16-byte chunks per row
+    for (int row = blockIdx.x; row < M; row += gridDim.x) {
+      const float kr = kra[row];
+      float* crow = c + (size_t)row * N;
+      const float* srow = c_star ? c_star + (size_t)row * N : nullptr;
+      for (int base = 0; base < nv; base += 4 * 256) {
+        f32x4_t v[4], w[4];
+        int cv[4];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      float T = bound_global ? t_global : __fmul_rn(__fmul_rn(kr, cb[col0 + e]), gamma);
-      bool f = !(fabsf(v[e]) <= T);
-      fbits |= (f ? 1u : 0u) << (8 * e);
-      if (f) {
-        cnt += 1;
-        if (policy == FI_CORRECT_ZERO) c[e0 + e] = 0.0f;
-        else if (policy == FI_CORRECT_RECOMPUTE) c[e0 + e] = c_star[e0 + e];
+        for (int u = 0; u < 4; ++u) {
+          cv[u] = base + u * 256 + (int)threadIdx.x;
+          if (cv[u] < nv) {
+            v[u] = *reinterpret_cast<const f32x4_t*>(crow + 4 * cv[u]);
+            w[u] = *reinterpret_cast<const f32x4_t*>(cb + 4 * cv[u]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (cv[u] < nv) {
+            uint32_t fbits = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float T = bound_global ? t_global : __fmul_rn(__fmul_rn(kr, w[u][e]), gamma);
+              const bool f = !(fabsf(v[u][e]) <= T);
+              fbits |= (f ? 1u : 0u) << (8 * e);
+            }
+            if (fbits) {                                    // rare: correct element by element
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                if ((fbits >> (8 * e)) & 1u) {
+                  cnt += 1;
+                  if (policy == FI_CORRECT_ZERO) crow[4 * cv[u] + e] = 0.0f;
+                  else if (policy == FI_CORRECT_RECOMPUTE) crow[4 * cv[u] + e] = srow[4 * cv[u] + e];
+                }
+              }
+            }
+            if (fl) *reinterpret_cast<uint32_t*>(fl + (size_t)row * N + 4 * cv[u]) = fbits;
+          }
+        }
       }
     }
-    if (fl) {
-      if constexpr (VEC == 4) *reinterpret_cast<uint32_t*>(fl + e0) = fbits;
-      else fl[e0] = (uint8_t)fbits;
+  } else {
+    for (size_t e0 = (size_t)blockIdx.x * 256 + threadIdx.x; e0 < mn; e0 += (size_t)gridDim.x * 256) {
+      const int row = (int)(e0 / (size_t)N), col = (int)(e0 % (size_t)N);
+      const float T = bound_global ? t_global : __fmul_rn(__fmul_rn(kra[row], cb[col]), gamma);
+      const bool f = !(fabsf(c[e0]) <= T);
+      if (f) {
+        cnt += 1;
+        if (policy == FI_CORRECT_ZERO) c[e0] = 0.0f;
+        else if (policy == FI_CORRECT_RECOMPUTE) c[e0] = c_star[e0];
+      }
+      if (fl) fl[e0] = f ? 1 : 0;
     }
   }
   if (n_flagged && __ballot(cnt != 0)) {

@@ -495,9 +495,9 @@ fi_status fi_detect_correct(fi_plan* plan, float* d_c, uint32_t batch, uint32_t 
   const size_t mn = (size_t)d.M * d.N;
   const bool vec = (d.N % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_c) & 15u) == 0) &&
                    (!d_flags || (reinterpret_cast<uintptr_t>(d_flags) & 3u) == 0);
-  const size_t per = vec ? mn / 4 : mn;
-  size_t gx = (per + 255) / 256;
-  if (gx > 4096) gx = 4096;
+  // vector path: workgroups stride over rows; scalar path: over elements
+  size_t gx = vec ? (size_t)d.M : (mn + 255) / 256;
+  if (gx > 2048) gx = 2048;
   dim3 grid((unsigned)gx, batch);
   if (vec) {
     hipLaunchKernelGGL(fi::detect_correct_kernel<4>, grid, dim3(256), 0, s, d_c, (int)d.M, (int)d.N, plan->kra,
