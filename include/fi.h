@@ -189,6 +189,19 @@ fi_status fi_detect_correct(fi_plan* plan, float* d_c, uint32_t batch, uint32_t 
 fi_status fi_classify(fi_plan* plan, const fi_trial_result* d_results, uint32_t n_trials,
                       uint8_t* d_class, uint64_t* d_counts, void* stream);
 
+/* Log2-binned histogram of a per-trial deviation (Sec. V-B "numeric deviation analysis", Fig. 7;
+ * Fig. 9), from which the empirical CDF follows by a running sum.
+ *   FI_HIST_SITE     |re'_sum - re_sum|: the change of the destination register, in binary32 from
+ *                    the two site words (accumulator and product-term faults only);
+ *   FI_HIST_DEV_PRE  the trial's largest output deviation before correction (max_dev_pre);
+ *   FI_HIST_DEV_POST after correction.
+ * Bin = biased exponent field of that binary32 value: 0 for zero (and subnormal), b for
+ * [2^(b-127), 2^(b-126)), 255 for Inf or NaN.  Trials with status != 0 are skipped.
+ * d_hist is [256] counters, overwritten.  Errors: INVALID_ARG (NULLs, n_trials == 0, which). */
+enum { FI_HIST_SITE = 0, FI_HIST_DEV_PRE = 1, FI_HIST_DEV_POST = 2 };
+fi_status fi_deviation_histogram(fi_plan* plan, const fi_fault* d_faults, const fi_trial_result* d_results,
+                                 uint32_t n_trials, uint32_t which, uint64_t* d_hist, void* stream);
+
 /* Host-side site selection (Sec. IV-A: uniform target, random bit(s)).
  * Trial t = first_trial + n draws from SplitMix64 seeded with seed + t*2^32:
  * u0 -> row (A: i; B: column j), u1, u2 -> (column, k-block) for ACC,

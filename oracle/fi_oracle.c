@@ -644,6 +644,23 @@ void orc_classify(const orc_record* recs, int n, uint8_t* cls, uint64_t counts[3
  * for a B-operand fault, times the position of an nbits-wide burst.  Draws
  * come from SplitMix64 (Steele, Lea, Flood 2014) keyed by the trial index so
  * any trial can be regenerated alone. */
+void orc_deviation_histogram(const orc_record* recs, const orc_fault* faults, int n, int which,
+                             uint64_t hist[256]) {
+  for (int b = 0; b < 256; ++b) hist[b] = 0;
+  for (int t = 0; t < n; ++t) {
+    if (!recs[t].valid) continue;
+    float d;
+    if (which == ORC_HIST_SITE) {
+      if (faults[t].kind != ORC_SITE_ACC && faults[t].kind != ORC_SITE_PRODUCT) continue;
+      d = fabsf(float_of(recs[t].site_word_after) - float_of(recs[t].site_word_before));
+    } else {
+      d = (float)(which == ORC_HIST_DEV_PRE ? recs[t].max_dev_pre : recs[t].max_dev_post);
+    }
+    unsigned bin = (word_of(d) >> 23) & 0xFFu;   /* d >= 0 or NaN: the sign bit is dropped by the mask */
+    hist[bin] += 1;
+  }
+}
+
 uint64_t orc_splitmix64_next(uint64_t* state) {
   *state += 0x9E3779B97F4A7C15ull;
   uint64_t z = *state;

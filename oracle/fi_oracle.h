@@ -86,6 +86,18 @@ typedef struct {
   uint32_t reserved;
 } orc_record;
 
+/* Sec. V-B "numeric deviation analysis" (Fig. 7) and Fig. 9: log2-binned histogram of a
+ * per-trial deviation, from which the empirical CDF follows by a running sum.
+ *   which 0: |re'_sum - re_sum|, the change of the destination register, computed in binary32
+ *            from the two site words (accumulator and product-term faults only);
+ *   which 1: the trial's largest output deviation before correction, 2: after correction
+ *            (rounded to binary32).
+ * bin = biased exponent field of that binary32 value: 0 for zero (and subnormal), b for
+ * [2^(b-127), 2^(b-126)), 255 for Inf or NaN.  Trials with an invalid site are skipped. */
+enum { ORC_HIST_SITE = 0, ORC_HIST_DEV_PRE = 1, ORC_HIST_DEV_POST = 2 };
+void orc_deviation_histogram(const orc_record* recs, const orc_fault* faults, int n, int which,
+                             uint64_t hist[256]);
+
 /* O1: exact value of a 16-bit pattern, held in a float. */
 float orc_decode16(uint16_t w, int fmt);
 

@@ -85,6 +85,8 @@ def lib():
         L.orc_trial.argtypes = [PP, u16p, u16p, vp, C.c_int, C.c_int, f32p, f32p, vp]
         L.orc_campaign.restype = C.c_int
         L.orc_campaign.argtypes = [PP, u16p, u16p, vp, C.c_int, C.c_int, C.c_int, vp]
+        L.orc_deviation_histogram.restype = None
+        L.orc_deviation_histogram.argtypes = [vp, vp, C.c_int, C.c_int, vp]
         L.orc_classify.restype = None
         L.orc_classify.argtypes = [vp, C.c_int, vp, vp]
         L.orc_splitmix64_next.restype = C.c_uint64
@@ -217,6 +219,19 @@ def campaign(p, A, B, faults, policy, mode=MODE_AFFECTED):
     if rc:
         raise ValueError("orc_campaign failed: %d" % rc)
     return recs
+
+
+HIST_SITE, HIST_DEV_PRE, HIST_DEV_POST = 0, 1, 2
+
+
+def deviation_histogram(recs, faults, which):
+    """256 log2 bins (binary32 exponent field) of a per-trial deviation; see fi_oracle.h."""
+    recs = np.ascontiguousarray(recs)
+    faults = np.ascontiguousarray(faults)
+    assert recs.dtype == RECORD_DTYPE and faults.dtype == FAULT_DTYPE and len(recs) == len(faults)
+    hist = np.zeros(256, np.uint64)
+    lib().orc_deviation_histogram(_ptr(recs), _ptr(faults), len(recs), which, _ptr(hist))
+    return hist
 
 
 def classify(recs):

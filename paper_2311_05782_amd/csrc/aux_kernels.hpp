@@ -271,6 +271,32 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
   }
 }
 
+// Log2-binned histogram of a per-trial deviation (Sec. V-B, Fig. 7 / Fig. 9): the bin is the
+// exponent field of the binary32 value.  One workgroup, counts gathered in LDS.
+__global__ void __launch_bounds__(1024) deviation_histogram_kernel(const fi_fault* __restrict__ f,
+                                                                  const fi_trial_result* __restrict__ r,
+                                                                  uint32_t n, int which,
+                                                                  unsigned long long* __restrict__ hist) {
+  __shared__ uint32_t bins[256];
+  if (threadIdx.x < 256) bins[threadIdx.x] = 0;
+  __syncthreads();
+  for (uint32_t t = threadIdx.x; t < n; t += 1024) {
+    const fi_trial_result x = r[t];
+    if (x.status != 0) continue;
+    float d;
+    if (which == FI_HIST_SITE) {
+      const uint32_t kind = f[t].kind;
+      if (kind != FI_SITE_ACC && kind != FI_SITE_PRODUCT) continue;
+      d = __fsub_rn(__uint_as_float(x.site_word_after), __uint_as_float(x.site_word_before));
+    } else {
+      d = which == FI_HIST_DEV_PRE ? x.max_dev_pre : x.max_dev_post;
+    }
+    atomicAdd(&bins[(__float_as_uint(d) >> 23) & 0xFFu], 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x < 256) hist[threadIdx.x] = bins[threadIdx.x];
+}
+
 // Outcome per trial and campaign totals, one workgroup, no atomics:
 // DETECTED if anything was flagged, else SDC if anything deviates beyond the
 // tolerance, else MASKED.

@@ -524,6 +524,19 @@ fi_status fi_classify(fi_plan* plan, const fi_trial_result* d_results, uint32_t 
   return FI_OK;
 }
 
+fi_status fi_deviation_histogram(fi_plan* plan, const fi_fault* d_faults, const fi_trial_result* d_results,
+                                 uint32_t n_trials, uint32_t which, uint64_t* d_hist, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_faults || !d_results || !d_hist) return fail(FI_INVALID_ARG, "d_faults, d_results and d_hist must be non-NULL");
+  if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
+  if (which > FI_HIST_DEV_POST) return fail(FI_INVALID_ARG, "unknown histogram quantity %u", which);
+  hipLaunchKernelGGL(fi::deviation_histogram_kernel, dim3(1), dim3(1024), 0, as_stream(stream), d_faults, d_results,
+                     n_trials, (int)which, reinterpret_cast<unsigned long long*>(d_hist));
+  FI_HIP(hipGetLastError());
+  return FI_OK;
+}
+
 fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trials, const fi_plan_desc* desc,
                            uint32_t kind_mode, uint32_t nbits, fi_fault* h_out) {
   fi_status st = check_desc(desc, nullptr);

@@ -21,12 +21,13 @@ CORRECT_NONE, CORRECT_ZERO, CORRECT_RECOMPUTE = 0, 1, 2
 BOUND_ROWCOL, BOUND_GLOBAL = 0, 1
 MASKED, SDC, DETECTED = 0, 1, 2
 PCHECK_NONE, PCHECK_BOUND, PCHECK_RANGE_MAX, PCHECK_RANGE_FLIP = 0, 1, 2, 3
+HIST_SITE, HIST_DEV_PRE, HIST_DEV_POST = 0, 1, 2
 KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A, KIND_ALL_PRODUCT = 0, 1, 2, 3, 4
 BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 
 # Symbols include/fi.h declares; the loader checks every one.
 EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
-           "fi_plan_set_product_check",
+           "fi_plan_set_product_check", "fi_deviation_histogram",
            "fi_gemm_inject_batch", "fi_detect_correct", "fi_classify", "fi_sample_faults",
            "fi_last_error"]
 
@@ -83,6 +84,7 @@ def lib():
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_detect_correct.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_classify.argtypes = [vp, vp, C.c_uint32, vp, vp, vp]
+    L.fi_deviation_histogram.argtypes = [vp, vp, vp, C.c_uint32, C.c_uint32, vp, vp]
     L.fi_sample_faults.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.POINTER(PlanDesc), C.c_uint32,
                                    C.c_uint32, vp]
     for name in EXPORTS:
@@ -177,6 +179,10 @@ class Plan:
     def fi_gemm_inject_batch(self, d_faults, n_trials, policy, d_results, d_c_out=None, stream=None):
         _check(lib().fi_gemm_inject_batch(self._h, _dptr(d_faults), n_trials, policy, _dptr(d_results),
                                           _dptr(d_c_out), _stream(stream)))
+
+    def fi_deviation_histogram(self, d_faults, d_results, n_trials, which, d_hist, stream=None):
+        _check(lib().fi_deviation_histogram(self._h, _dptr(d_faults), _dptr(d_results), n_trials, which,
+                                            _dptr(d_hist), _stream(stream)))
 
     def fi_detect_correct(self, d_c, batch, policy, d_flags=None, d_n_flagged=None, stream=None):
         _check(lib().fi_detect_correct(self._h, _dptr(d_c), batch, policy, _dptr(d_flags),

@@ -188,3 +188,41 @@ def test_exponent_only_checks_confine_the_deviation_on_a_campaign():
     assert worst[fi.PCHECK_BOUND] < 2.0 ** 18
     assert worst[fi.PCHECK_RANGE_MAX] < 1e3 and worst[fi.PCHECK_RANGE_FLIP] < 1e3
     plan.destroy()
+
+
+def test_deviation_histogram_kernel():
+    # Fig. 7 / Fig. 9 analogue: log2-binned per-trial differences.  The kernel must bin its own
+    # records exactly as the definition says; against the oracle's campaign the histograms agree up
+    # to trials that sit on a bin edge or whose low accumulator bits differ.
+    import torch
+    fmt = orc.BF16
+    A, B = wl.gaussian(128, 128, 128, fmt, seed=95)
+    plan = gu.make_plan(A, B, 64, fmt)
+    n = 5000
+    faults = fi.fi_sample_faults(2, 0, n, plan.desc, fi.KIND_ALL_PRODUCT, 2)
+    faults[7]["row"] = 10 ** 6                                   # an invalid site: skipped
+    d_f = fi.to_device(faults)
+    d_r = fi.empty_results(n)
+    plan.fi_gemm_inject_batch(d_f, n, fi.CORRECT_ZERO, d_r)
+    recs = fi.results_to_host(d_r)
+    p = orc.problem(128, 128, 128, 64, fmt)
+    ofaults = gu.to_orc_faults(faults)
+    ora = orc.campaign(p, A, B, ofaults, orc.CORRECT_ZERO, orc.MODE_AFFECTED)
+    d_h = torch.zeros(256, dtype=torch.int64, device="cuda")
+    for which in (fi.HIST_SITE, fi.HIST_DEV_PRE, fi.HIST_DEV_POST):
+        plan.fi_deviation_histogram(d_f, d_r, n, which, d_h)
+        h = d_h.cpu().numpy().astype(np.uint64)
+        # the same records through the oracle's histogram (its record layout)
+        mine = np.zeros(n, orc.RECORD_DTYPE)
+        for k in ("site_word_before", "site_word_after", "max_dev_pre", "max_dev_post"):
+            mine[k] = recs[k]
+        mine["valid"] = (recs["status"] == 0)
+        assert np.array_equal(h, orc.deviation_histogram(mine, ofaults, which)), which
+        assert int(h.sum()) == n - 1
+        ho = orc.deviation_histogram(ora, ofaults, which)
+        assert int(np.abs(h.astype(np.int64) - ho.astype(np.int64)).sum()) <= 0.02 * n, which
+        print("histogram", which, "zero bin", int(h[0]), "Inf/NaN bin", int(h[255]),
+              "median bin", int(np.searchsorted(np.cumsum(h), h.sum() / 2)))
+    with pytest.raises(fi.FiError):
+        plan.fi_deviation_histogram(d_f, d_r, n, 3, d_h)
+    plan.destroy()

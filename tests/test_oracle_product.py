@@ -220,3 +220,53 @@ def test_product_site_sampler_ranges_and_spread():
     a = orc.sample_faults(11, 100, 50, p, orc.KIND_ALL_PRODUCT, 1)
     b = orc.sample_faults(11, 0, 150, p, orc.KIND_ALL_PRODUCT, 1)[100:]
     assert (a == b).all()
+
+
+# ------------------------------------------------------------ deviation histogram (Fig. 7 / Fig. 9)
+
+def test_deviation_histogram_bins_are_binary32_exponents():
+    recs = np.zeros(9, orc.RECORD_DTYPE)
+    faults = orc.make_faults([(orc.SITE_ACC, 0, 0, 0, 1)] * 6 + [(orc.SITE_PRODUCT, 0, 0, 0, 1), (orc.SITE_A, 0, 0, 0, 1),
+                              (orc.SITE_ACC, 0, 0, 0, 1)])
+    recs["valid"] = 1
+    recs["valid"][8] = 0                                           # invalid site: skipped everywhere
+    pairs = [(17.0, 17.0), (17.0, 15.0), (1.0, 4.0), (1.0, np.inf), (0.0, 2.0 ** -130), (2.0 ** 100, -2.0 ** 100),
+             (15.0, 15.000030517578125), (3.0, 5.0), (1.0, 2.0)]
+    for t, (b, a) in enumerate(pairs):
+        recs["site_word_before"][t] = np.array([b], np.float32).view(np.uint32)[0]
+        recs["site_word_after"][t] = np.array([a], np.float32).view(np.uint32)[0]
+    recs["max_dev_pre"] = [0.0, 0.75, 1.0, np.inf, 1e-50, 3.0, 1e39, 2.0, 8.0]
+    recs["max_dev_post"] = 0.0
+    h = orc.deviation_histogram(recs, faults, orc.HIST_SITE)
+    # diffs: 0 | 2 | 3 | Inf | subnormal | 2^101 | 2^-15 ; the operand trial and the invalid one are skipped
+    want = {0: 2, 128: 2, 255: 1, 127 + 101: 1, 127 - 15: 1}
+    assert {int(b): int(c) for b, c in enumerate(h) if c} == want
+    h = orc.deviation_histogram(recs, faults, orc.HIST_DEV_PRE)
+    # 0 | 0.75 | 1 | Inf | 1e-50 -> 0 in binary32 | 3 | 1e39 -> Inf in binary32 | 2
+    assert {int(b): int(c) for b, c in enumerate(h) if c} == {0: 2, 126: 1, 127: 1, 128: 2, 255: 2}
+    assert int(orc.deviation_histogram(recs, faults, orc.HIST_DEV_POST)[0]) == 8
+
+
+def test_deviation_histogram_of_a_campaign_matches_frexp_binning():
+    fmt = orc.BF16
+    Aw, Bw = wl.gaussian(24, 16, 64, fmt, seed=91)
+    p = orc.problem(24, 16, 64, 16, fmt)
+    faults = orc.sample_faults(3, 0, 1500, p, orc.KIND_ALL_PRODUCT, 2)
+    recs = orc.campaign(p, Aw, Bw, faults, orc.CORRECT_ZERO, orc.MODE_AFFECTED)
+    h = orc.deviation_histogram(recs, faults, orc.HIST_SITE)
+    b = recs["site_word_before"].view(np.float32)
+    a = recs["site_word_after"].view(np.float32)
+    with np.errstate(all="ignore"):
+        d = np.abs(a - b).astype(np.float32)
+    want = np.zeros(256, np.uint64)
+    for x in d.tolist():
+        if not np.isfinite(x):
+            want[255] += 1
+        elif x < 2.0 ** -126:
+            want[0] += 1
+        else:
+            m, e = np.frexp(x)                       # x = m * 2^e, m in [0.5, 1): floor(log2 x) = e - 1
+            want[e - 1 + 127] += 1
+    assert np.array_equal(h, want) and int(h.sum()) == 1500
+    # the ECDF reaches 1 and the zero-difference share is Table III's statistic
+    assert int(h[0]) == int((recs["site_word_before"] == recs["site_word_after"]).sum() + ((d > 0) & (d < 2.0 ** -126)).sum())
