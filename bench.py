@@ -86,8 +86,10 @@ def main():
     ap.add_argument("--trials", type=int, default=0, help="trials per batch (default: the workload's)")
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--group", type=int, default=-1)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="headline measurement only: no CPU baseline, detector or other-campaign timings")
     ap.add_argument("--sources-digest", action="store_true", help="print the kernel sources' digest and exit")
+    ap.add_argument("--campaigns", action="store_true", help="also time the four other campaigns")
     ap.add_argument("--detector", action="store_true", help="also time the standalone detector kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference row for HBM byte counters)")
@@ -189,7 +191,8 @@ def main():
     }
     # The standalone detector / corrector (fi_detect_correct) on materialised outputs of the same
     # problem: an HBM-bound kernel, 4 bytes read per element, priced against the 8 TB/s roof.
-    if default_run or args.detector:
+    extras = default_run and not args.no_cpu_baseline      # the full default run; profiles use the bare one
+    if extras or args.detector:
         batch = 16
         c = torch.empty((batch, w.M, w.N), dtype=torch.float32, device="cuda").uniform_(-1.0, 1.0)
         nfl = torch.zeros(batch, dtype=torch.int32, device="cuda")
@@ -210,6 +213,29 @@ def main():
                                     "kernel_ms_avg": round(sum(dms) / len(dms), 4), "batch": batch,
                                     "flagged": int(nfl.sum().item())}
         del c
+    # The other campaigns (parity-test configurations), a few launches each: context, not the metric.
+    if extras or args.campaigns:
+        others = {}
+        for name in ("tiny128", "bert_linear", "resnet_conv", "detector_stress"):
+            ww = wl.ALL[name]()
+            pl = fi.Plan(fi.plan_desc(ww.M, ww.N, ww.K, ww.kb, ww.fmt), fi.words_to_device(ww.A), fi.words_to_device(ww.B))
+            ff = fi.to_device(fi.fi_sample_faults(ww.fault_seed, 0, ww.n_trials, pl.desc, ww.kind_mode, ww.nbits))
+            rr = fi.empty_results(ww.n_trials)
+            for _ in range(2):
+                pl.fi_gemm_inject_batch(ff, ww.n_trials, ww.policies[0], rr)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(5):
+                pl.fi_gemm_inject_batch(ff, ww.n_trials, ww.policies[0], rr)
+                pl.fi_classify(rr, ww.n_trials, d_cls[:1].new_empty(ww.n_trials), d_cnt)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t1) / 5
+            others[name] = {"shape": "%dx%dx%d %s kb %d" % (ww.M, ww.N, ww.K, "bf16" if ww.fmt == wl.BF16 else "fp16", ww.kb),
+                            "trials": ww.n_trials, "ms_per_batch": round(dt * 1e3, 3),
+                            "trials_per_s": round(ww.n_trials / dt, 1),
+                            "tflops": round(ww.flops_per_trial * ww.n_trials / dt / 1e12, 2)}
+            pl.destroy()
+        out["other_campaigns"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
         out["cpu_baseline"]["value"] = float("%.4g" % out["cpu_baseline"]["value"])
