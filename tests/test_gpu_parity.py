@@ -300,3 +300,48 @@ def test_standalone_detector_equals_fused_epilogue_and_oracle(N):
     plan.fi_detect_correct(d_c, len(faults), wl.CORRECT_ZERO)
     torch.cuda.synchronize()
     plan.destroy()
+
+
+def test_campaign_calls_replay_correctly_from_a_hip_graph():
+    # The library clears records and counters with kernels, not memsets, so its calls can be
+    # captured.  Replays are interleaved with eager work and synchronisations and every replay is
+    # checked against the eager result.
+    import torch
+    w = wl.tiny()
+    plan = gu.make_plan(w.A, w.B, w.kb, w.fmt)
+    n = 256
+    faults = fi.fi_sample_faults(5, 0, n, plan.desc, fi.KIND_ALL_ACC, 1)
+    d_f = fi.to_device(faults)
+    d_r = fi.empty_results(n)
+    d_cls = torch.empty(n, dtype=torch.uint8, device="cuda")
+    d_cnt = torch.empty(3, dtype=torch.int64, device="cuda")
+    plan.fi_gemm_inject_batch(d_f, n, fi.CORRECT_ZERO, d_r)           # eager: also sizes the plan's scratch
+    plan.fi_classify(d_r, n, d_cls, d_cnt)
+    torch.cuda.synchronize()
+    want_r = fi.results_to_host(d_r).copy()
+    want_cnt = d_cnt.cpu().numpy().copy()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            s = torch.cuda.current_stream().cuda_stream
+            plan.fi_gemm_inject_batch(d_f, n, fi.CORRECT_ZERO, d_r, stream=s)
+            plan.fi_classify(d_r, n, d_cls, d_cnt, stream=s)
+    for rep in range(4):
+        d_r.zero_(); d_cnt.fill_(-1)                                   # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = fi.results_to_host(d_r)
+        assert got.tobytes() == want_r.tobytes(), rep
+        assert np.array_equal(d_cnt.cpu().numpy(), want_cnt), rep
+        # a different fault list through the same graph (the list lives in device memory)
+        if rep == 1:
+            faults2 = fi.fi_sample_faults(6, 0, n, plan.desc, fi.KIND_ALL_ACC, 1)
+            d_f.copy_(fi.to_device(faults2))
+            plan.fi_gemm_inject_batch(d_f, n, fi.CORRECT_ZERO, d_r)
+            plan.fi_classify(d_r, n, d_cls, d_cnt)
+            torch.cuda.synchronize()
+            want_r = fi.results_to_host(d_r).copy()
+            want_cnt = d_cnt.cpu().numpy().copy()
+    plan.destroy()
