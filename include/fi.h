@@ -78,8 +78,9 @@ typedef struct {
   uint32_t kind, row, col, kblock, xor_mask;
 } fi_fault;
 
-/* Per-trial record.  "Affected" elements are those in the output tiles a fault
- * can reach; all other elements are bit-identical to the fault-free result.
+/* Per-trial record.  "Affected" elements are those a fault can reach: the element
+ * itself (ACC, PRODUCT), its output row (A) or its output column (B); all other
+ * elements are bit-identical to the fault-free result.
  *   tau_ij = 2^-12 * sum_k |a_ik * b_kj| is the deviation a trial may show and
  *   still count as masked (Sec. V-B: small mantissa changes are absorbed
  *   during accumulation).  Deviations are taken against the plan's own

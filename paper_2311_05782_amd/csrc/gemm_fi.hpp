@@ -579,7 +579,10 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-            if (row < p.M && col < p.N) {
+            // Only what the fault can reach differs from the fault-free result: the element
+            // itself, or its output row (A fault) / column (B fault).
+            const bool reach = (fkind == FI_SITE_B || row == (int)frow) && (fkind == FI_SITE_A || col == (int)fcol);
+            if (row < p.M && col < p.N && reach) {
               const float c = t[v];
               const size_t idx = (size_t)row * p.N + col;
               const float cs = p.c_star[idx];

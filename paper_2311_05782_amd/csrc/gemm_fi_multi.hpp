@@ -314,6 +314,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       constexpr int r = rr;
       if ((affected >> r) & 1u) {
         fi_trial_result* res = p.results + trial[r];
+        const int site_row = (int)desc_field(r, 1), site_col = (int)desc_field(r, 2);
         uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
         float mx_pre = 0.0f, mx_post = 0.0f;
         static_for<TM * TN>([&](auto tt) {
@@ -324,7 +325,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-            if (row < p.M && col < p.N) {
+            // only the faulted element can differ from the fault-free result
+            if (row == site_row && col == site_col) {
               const float c = t[v];
               const size_t idx = (size_t)row * p.N + col;
               const float cs = p.c_star[idx];
