@@ -345,3 +345,43 @@ def test_campaign_calls_replay_correctly_from_a_hip_graph():
             want_r = fi.results_to_host(d_r).copy()
             want_cnt = d_cnt.cpu().numpy().copy()
     plan.destroy()
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 64, 64), (1, 70, 128, 32), (33, 1, 64, 16), (5, 3, 16, 16), (129, 65, 4096, 64)])
+def test_degenerate_and_extreme_shapes(shape):
+    # One row, one column, a single 16-wide k-step, a long K; batches of 1, 7 and 9 trials (less
+    # than, and one more than, a group of 8), every fault kind; exact regime, bit for bit.
+    M, N, K, kb = shape
+    fmt = orc.BF16
+    Aw, Bw = wl.small_integers(M, N, K, fmt, seed=K + M, lim=2, step=2)
+    p = orc.problem(M, N, K, kb, fmt)
+    rng = np.random.default_rng(M * 7 + N)
+    rows = []
+    for t in range(9):
+        kind = [orc.SITE_ACC, orc.SITE_PRODUCT, orc.SITE_A, orc.SITE_B, orc.SITE_NONE][t % 5]
+        i, j, k = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(K))
+        if kind == orc.SITE_ACC:
+            rows.append((kind, i, j, int(rng.integers(K // kb)), 1 << int(rng.integers(20, 32))))
+        elif kind == orc.SITE_PRODUCT:
+            rows.append((kind, i, j, k, 0x8000))
+        elif kind == orc.SITE_A:
+            rows.append((kind, i, k, 0, 0x8000))
+        elif kind == orc.SITE_B:
+            rows.append((kind, k, j, 0, 0x8000))
+        else:
+            rows.append((kind, 0, 0, 0, 0))
+    faults = orc.make_faults(rows)
+    plan = gu.make_plan(Aw, Bw, kb, fmt)
+    gold = orc.gemm(p, Aw, Bw)
+    assert np.array_equal(plan.buffer_to_host(fi.BUF_C_STAR).view(np.uint32), gold.view(np.uint32))
+    for n in (1, 7, 9):
+        recs, cout = gu.gpu_campaign(plan, faults[:n], orc.CORRECT_RECOMPUTE, want_c=True)
+        ora = orc.campaign(p, Aw, Bw, faults[:n], orc.CORRECT_RECOMPUTE, orc.MODE_AFFECTED)
+        for t in range(n):
+            o, cf, cc = orc.trial(p, Aw, Bw, faults[t:t + 1], orc.CORRECT_RECOMPUTE, orc.MODE_FULL, want_outputs=True)
+            nan = np.isnan(cc)
+            assert np.array_equal(np.isnan(cout[t]), nan)
+            assert np.array_equal(cout[t][~nan].view(np.uint32), cc[~nan].view(np.uint32)), (t, faults[t])
+        s = gu.compare_records(recs, ora, faults[:n], exact_words=True)
+        assert not s["mismatches"], s["mismatches"][:5]
+    plan.destroy()
