@@ -27,7 +27,7 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "0ad3e536050a796a23807c2a1e6fc33808e0b7b0012a7b5c32cad0d886aa36ee",
+    "sources_sha256": "d9a9336b0aa65a4f412ba8a2f4cc6745967b707417ba6efb5d2833af4659fdcc",
     "fetch_bytes": 2.2017e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }
@@ -213,6 +213,19 @@ def main():
                                     "kernel_ms_avg": round(sum(dms) / len(dms), 4), "batch": batch,
                                     "flagged": int(nfl.sum().item())}
         del c
+    # The affected-tiles-only campaign on the same batch: a different product (only what a fault can
+    # reach is computed), reported as trials per second and never against the MFMA roof.
+    if extras or args.campaigns:
+        for _ in range(2):
+            plan.fi_gemm_inject_batch_affected(d_f, n_trials, policy, d_r)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(10):
+            plan.fi_gemm_inject_batch_affected(d_f, n_trials, policy, d_r)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t1) / 10
+        out["affected_only"] = {"entry_point": "fi_gemm_inject_batch_affected", "trials_per_s": round(n_trials / dt, 1),
+                                "ms_per_batch": round(dt * 1e3, 4)}
     # The other campaigns (parity-test configurations), a few launches each: context, not the metric.
     if extras or args.campaigns:
         others = {}
@@ -234,6 +247,14 @@ def main():
                             "trials": ww.n_trials, "ms_per_batch": round(dt * 1e3, 3),
                             "trials_per_s": round(ww.n_trials / dt, 1),
                             "tflops": round(ww.flops_per_trial * ww.n_trials / dt / 1e12, 2)}
+            for _ in range(2):
+                pl.fi_gemm_inject_batch_affected(ff, ww.n_trials, ww.policies[0], rr)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(5):
+                pl.fi_gemm_inject_batch_affected(ff, ww.n_trials, ww.policies[0], rr)
+            torch.cuda.synchronize()
+            others[name]["affected_only_trials_per_s"] = round(5 * ww.n_trials / (time.perf_counter() - t1), 1)
             pl.destroy()
         out["other_campaigns"] = others
     if not args.no_cpu_baseline:

@@ -176,6 +176,17 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
                                uint32_t policy, fi_trial_result* d_results, float* d_c_out,
                                void* stream);
 
+/* The same campaign restricted to what a fault can reach: for each trial only the output
+ * tiles holding the faulted element (ACC, PRODUCT), its output row (A) or its output column
+ * (B) are computed; every other element of a trial equals the fault-free result bit for bit
+ * and, for gamma at or above the default, cannot be flagged.  d_results[t] then equals the
+ * record fi_gemm_inject_batch writes.  This is a different product - trials per second, not
+ * matrix-core throughput: a trial costs 2*K (element) to 2*N*K or 2*M*K (row, column) useful
+ * flops instead of 2*M*N*K - and its rate is never reported against the MFMA roof.
+ * Errors as fi_gemm_inject_batch. */
+fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
+                                        uint32_t policy, fi_trial_result* d_results, void* stream);
+
 /* The detector / corrector alone on materialised outputs (Sec. VI-A/B):
  * d_c is [batch][M][N], corrected in place; d_flags is NULL or
  * [batch][M][N] bytes (1 = flagged); d_n_flagged is NULL or [batch] counters,

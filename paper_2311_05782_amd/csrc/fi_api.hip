@@ -70,6 +70,7 @@ struct fi_plan {
   float* scratch;          // 4 floats + 1 word
   float t_global;
   int cfg;                 // index into kCfg
+  int cfg_affected;        // index into kCfg for the affected-tiles-only campaign
   int mcfg;                // index into kMulti, or -1: every trial through the single-trial kernel
   int group;               // trials sharing a tile back to back
   int device;
@@ -131,10 +132,10 @@ int pick_cfg(const fi_plan_desc& d) {
   return 1;
 }
 
-GemmArgs base_args(const fi_plan* p) {
+GemmArgs base_args(const fi_plan* p, int cfg = -1) {
   GemmArgs a;
   memset(&a, 0, sizeof(a));
-  const TileCfg c = kCfg[p->cfg];
+  const TileCfg c = kCfg[cfg >= 0 ? cfg : p->cfg];
   a.A = p->A; a.B = p->B; a.lda = (uint32_t)p->d.lda; a.ldb = p->ldb;
   a.M = (int)p->d.M; a.N = (int)p->d.N; a.K = (int)p->d.K; a.kb = (int)p->d.k_block;
   a.tiles_m = (a.M + c.bm - 1) / c.bm;
@@ -330,6 +331,7 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   p->d = d;
   p->d.gamma = gamma;
   p->cfg = pick_cfg(d);
+  p->cfg_affected = d.N <= 64 ? 2 : 1;   // small tiles: only the reached part is of interest
   p->mcfg = pick_multi(d);
   p->group = 32;
   (void)hipGetDevice(&p->device);
@@ -384,7 +386,7 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
   // C* does not depend on the tile shape: every shape feeds each output element the same
   // sequence of 16-wide MFMA steps in ascending k.
   if (tile_config >= kNumCfg) plan->mcfg = tile_config - kNumCfg;
-  else if (tile_config >= 0) { plan->cfg = tile_config; plan->mcfg = -1; }
+  else if (tile_config >= 0) { plan->cfg = tile_config; plan->cfg_affected = tile_config; plan->mcfg = -1; }
   (void)stream;
   return FI_OK;
 }
@@ -475,6 +477,32 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
     FI_HIP(launch_multi((int)plan->d.dtype, plan->mcfg, m, (int)mblocks, s));
   }
   FI_HIP(launch_gemm<fi::MODE_CAMPAIGN>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
+  return FI_OK;
+}
+
+fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
+                                        uint32_t policy, fi_trial_result* d_results, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_faults || !d_results) return fail(FI_INVALID_ARG, "d_faults and d_results must be non-NULL");
+  if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
+  if (policy > FI_CORRECT_RECOMPUTE) return fail(FI_INVALID_ARG, "unknown correction policy %u", policy);
+  GemmArgs a = base_args(plan, plan->cfg_affected);
+  const uint64_t slots = (uint64_t)(a.tiles_m > a.tiles_n ? a.tiles_m : a.tiles_n);
+  const uint64_t blocks = slots * n_trials;
+  if (blocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
+  hipStream_t s = as_stream(stream);
+  const size_t words = (size_t)n_trials * (sizeof(fi_trial_result) / 4);
+  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3((unsigned)((words + 255) / 256 > 1024 ? 1024 : (words + 255) / 256)),
+                     dim3(256), 0, s, reinterpret_cast<uint32_t*>(d_results), words, 0u);
+  FI_HIP(hipGetLastError());
+  a.n_trials = (int)n_trials;
+  a.group = plan->group;
+  a.faults = d_faults;
+  a.results = d_results;
+  a.policy = (int)policy;
+  a.product_check = plan->product_check;
+  FI_HIP(launch_gemm<fi::MODE_AFFECTED>((int)plan->d.dtype, plan->cfg_affected, a, (int)blocks, s));
   return FI_OK;
 }
 

@@ -41,7 +41,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
-enum { MODE_CAMPAIGN = 0, MODE_GOLDEN = 1 };
+// CAMPAIGN: every tile of every trial.  GOLDEN: the plan's fault-free pass.  AFFECTED: only the
+// tiles a trial's fault can reach (one workgroup slot per trial and candidate tile).
+enum { MODE_CAMPAIGN = 0, MODE_GOLDEN = 1, MODE_AFFECTED = 2 };
 
 struct GemmArgs {
   const uint16_t* A;        // [M][lda]
@@ -263,6 +265,34 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     if (n_mine == 0 || !work_of_block(p.tiles_m * p.tiles_n, n_mine, p.group, tile, trial))
       return;                                          // uniform, before any barrier
     if (p.perm) trial = (int)p.perm[p.part_counts[0] + (uint32_t)trial];
+  } else if constexpr (MODE == MODE_AFFECTED) {
+    // Slot q of trial t: an accumulator or product-term fault reaches one tile (slot 0), an A
+    // fault the tiles_n tiles of its tile row, a B fault the tiles_m tiles of its tile column.
+    // The grid holds max(tiles_m, tiles_n) slots per trial, slot-major: consecutive workgroup
+    // ids are the same slot of consecutive trials, so the working ones spread over all XCDs.
+    trial = (int)(blockIdx.x % (uint32_t)p.n_trials);
+    const int q = (int)(blockIdx.x / (uint32_t)p.n_trials);
+    const fi_fault f = p.faults[trial];
+    if (f.kind == FI_SITE_ACC || f.kind == FI_SITE_PRODUCT) {
+      const bool valid = f.row < (uint32_t)p.M && f.col < (uint32_t)p.N &&
+                         f.kblock < (uint32_t)(f.kind == FI_SITE_ACC ? p.K / p.kb : p.K);
+      if (!valid && q == 0 && tid == 0) p.results[trial].status = 1;
+      if (!valid || q != 0) return;
+      tile = (int)(f.row / BM) * p.tiles_n + (int)(f.col / BN);
+    } else if (f.kind == FI_SITE_A) {
+      const bool valid = f.row < (uint32_t)p.M && f.col < (uint32_t)p.K;
+      if (!valid && q == 0 && tid == 0) p.results[trial].status = 1;
+      if (!valid || q >= p.tiles_n) return;
+      tile = (int)(f.row / BM) * p.tiles_n + q;
+    } else if (f.kind == FI_SITE_B) {
+      const bool valid = f.row < (uint32_t)p.K && f.col < (uint32_t)p.N;
+      if (!valid && q == 0 && tid == 0) p.results[trial].status = 1;
+      if (!valid || q >= p.tiles_m) return;
+      tile = q * p.tiles_n + (int)(f.col / BN);
+    } else {
+      if (f.kind != FI_SITE_NONE && q == 0 && tid == 0) p.results[trial].status = 1;
+      return;                                            // nothing can differ
+    }
   } else {
     work_of_block(p.tiles_m * p.tiles_n, p.n_trials, p.group, tile, trial);
   }
@@ -277,7 +307,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   int sel_t = 0, sel_v = 0, sel_lane = -1;
   bool affected = false;    // this tile can differ from the fault-free result
   int opfault_kt = -1;      // k-tile in which this workgroup stages a faulted operand word
-  if constexpr (MODE == MODE_CAMPAIGN) {
+  if constexpr (MODE != MODE_GOLDEN) {
     const fi_fault f = p.faults[trial];
     fkind = f.kind; frow = f.row; fcol = f.col; fmask = f.xor_mask;
     bool valid = true;
@@ -403,7 +433,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
         if (!((k0 + ch) >= 0 && (k0 + ch) < p.K)) *reinterpret_cast<u32x4*>(sB + c * 1024) = zero4;
       }
     }
-    if constexpr (MODE == MODE_CAMPAIGN) {
+    if constexpr (MODE != MODE_GOLDEN) {
       if (kt == opfault_kt) {
         const bool isA = fkind == FI_SITE_A;
         const int kk = (isA ? (int)fcol : (int)frow) - kt * BK;            // 0..63 (kshift is 0 here)
@@ -527,7 +557,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     __builtin_amdgcn_sched_barrier(0);
     mma_step(f1);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (MODE == MODE_CAMPAIGN) {
+    if constexpr (MODE != MODE_GOLDEN) {
       if (kt == hook_kt) accumulator_fault();   // one wave of one workgroup per trial
     }
   }

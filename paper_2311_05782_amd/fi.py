@@ -28,7 +28,7 @@ BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 # Symbols include/fi.h declares; the loader checks every one.
 EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
            "fi_plan_set_product_check", "fi_deviation_histogram",
-           "fi_gemm_inject_batch", "fi_detect_correct", "fi_classify", "fi_sample_faults",
+           "fi_gemm_inject_batch", "fi_gemm_inject_batch_affected", "fi_detect_correct", "fi_classify", "fi_sample_faults",
            "fi_last_error"]
 
 FAULT_DTYPE = np.dtype([("kind", "<u4"), ("row", "<u4"), ("col", "<u4"), ("kblock", "<u4"),
@@ -82,6 +82,7 @@ def lib():
     L.fi_plan_describe.argtypes = [vp, C.c_char_p, C.c_uint64]
     L.fi_plan_set_product_check.argtypes = [vp, C.c_uint32]
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
+    L.fi_gemm_inject_batch_affected.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp]
     L.fi_detect_correct.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_classify.argtypes = [vp, vp, C.c_uint32, vp, vp, vp]
     L.fi_deviation_histogram.argtypes = [vp, vp, vp, C.c_uint32, C.c_uint32, vp, vp]
@@ -183,6 +184,10 @@ class Plan:
     def fi_deviation_histogram(self, d_faults, d_results, n_trials, which, d_hist, stream=None):
         _check(lib().fi_deviation_histogram(self._h, _dptr(d_faults), _dptr(d_results), n_trials, which,
                                             _dptr(d_hist), _stream(stream)))
+
+    def fi_gemm_inject_batch_affected(self, d_faults, n_trials, policy, d_results, stream=None):
+        _check(lib().fi_gemm_inject_batch_affected(self._h, _dptr(d_faults), n_trials, policy, _dptr(d_results),
+                                                   _stream(stream)))
 
     def fi_detect_correct(self, d_c, batch, policy, d_flags=None, d_n_flagged=None, stream=None):
         _check(lib().fi_detect_correct(self._h, _dptr(d_c), batch, policy, _dptr(d_flags),

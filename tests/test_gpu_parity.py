@@ -385,3 +385,32 @@ def test_degenerate_and_extreme_shapes(shape):
         s = gu.compare_records(recs, ora, faults[:n], exact_words=True)
         assert not s["mismatches"], s["mismatches"][:5]
     plan.destroy()
+
+
+@pytest.mark.parametrize("name", ["tiny128", "bert_linear", "resnet_conv", "detector_stress"])
+def test_affected_tiles_only_campaign_gives_the_same_records(name):
+    # Computing only what a fault can reach must reproduce the full campaign's records exactly
+    # (same kernels, same accumulation order); it is timed as trials per second only.
+    import time
+    import torch
+    w = wl.ALL[name]()
+    n = min(w.n_trials, 4096)
+    for cfg in ((None,) if name != "tiny128" else (None, 0, 1, 2)):
+        plan = gu.make_plan(w.A, w.B, w.kb, w.fmt)
+        faults = fi.fi_sample_faults(w.fault_seed, 0, n, plan.desc, w.kind_mode if name != "resnet_conv" else fi.KIND_ALL_B,
+                                     w.nbits)
+        faults[3]["row"] = 10 ** 7                                  # an invalid site
+        d_f = fi.to_device(faults)
+        full = gu.gpu_campaign(plan, faults, w.policies[0])
+        if cfg is not None:
+            plan.tune(cfg)
+        d_r = fi.empty_results(n)
+        plan.fi_gemm_inject_batch_affected(d_f, n, w.policies[0], d_r)
+        part = fi.results_to_host(d_r)
+        assert part.tobytes() == full.tobytes(), [t for t in range(n) if part[t] != full[t]][:5]
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        for _ in range(3):
+            plan.fi_gemm_inject_batch_affected(d_f, n, w.policies[0], d_r)
+        torch.cuda.synchronize()
+        print(name, "affected-only: %.0f trials/s" % (3 * n / (time.perf_counter() - t0)))
+        plan.destroy()
