@@ -27,7 +27,7 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "d9a9336b0aa65a4f412ba8a2f4cc6745967b707417ba6efb5d2833af4659fdcc",
+    "sources_sha256": "",
     "fetch_bytes": 2.2017e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }
@@ -98,7 +98,7 @@ def main():
         print(kernel_sources_digest())
         return
     if args.gpus != 1:
-        print("bench.py measures one GPU: campaigns shard by trial with no exchange, and this build "
+        print("bench.py measures one GPU: campaigns shard by trial with no exchange, and this library "
               "runs on a single MI355X.  Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 

@@ -138,9 +138,10 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
  *   0..2  one trial per workgroup on a 256x256, 128x128 or 256x64 output tile
  *         (every fault kind, any K);
  *   3..5  R trials per workgroup sharing one staged operand tile: R=4 on 128x128,
- *         R=2 on 128x128, R=8 on 128x64 (the default when K % 64 == 0).  These take
- *         the fault-free trials and the accumulator faults; the library routes the
- *         operand-fault trials of the batch to the one-trial kernel.
+ *         R=2 on 128x128, R=8 on 128x64 (the default when K % 64 == 0).  The batch is
+ *         split on the device into the trials whose fault leaves the operands alone
+ *         and the operand-fault trials; the latter run in a second instantiation that
+ *         feeds the faulted trial a patched copy of the fragment registers.
  *         FI_UNSUPPORTED if K % 64 != 0.
  * trial_group: -1 keep, else how many trials (groups of R trials) of the same
  * output tile are scheduled next to each other, 1..4096.  Results do not depend on

@@ -201,7 +201,9 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
 // w0, w1}: event = -1 for no fault, else the 16-wide MFMA step after which the accumulator
 // changes - (s+1)*kb/16 - 1 for a flip with w0 = the XOR mask; k/16, with bit 30 set, for a
 // product-term fault with w0, w1 = the words of re and re_err (Sec. III-E).  desc is padded
-// with fault-free entries up to the next multiple of 8 positions.  B is [N][ldb], k contiguous.
+// with fault-free entries up to the next multiple of 8 positions.  The operand faults' descriptors
+// follow from that position on: event = k/16 with bit 29 set, w0 = the 16-bit mask, w1 = kind;
+// their site words (the operand word before and after) are written here.  B is [N][ldb], k contiguous.
 // One workgroup; each thread owns a contiguous chunk of the list.
 template <int DT>
 __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* __restrict__ f, uint32_t n,
@@ -244,7 +246,18 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
   for (uint32_t t = lo; t < hi; ++t) {
     const fi_fault x = f[t];
     const int k = kind_of(x);
-    if (k == 0) { perm[ps++] = t; continue; }
+    if (k == 0) {
+      // operand fault: second part of the batch; its descriptors start at the next multiple of 8
+      const bool isA = x.kind == FI_SITE_A;
+      const uint32_t kk = isA ? x.col : x.row, m16 = x.xor_mask & 0xFFFFu;
+      uint32_t* d = desc + ((size_t)((n_fast + 7u) & ~7u) + (ps - n_fast)) * 6;
+      d[0] = t; d[1] = x.row; d[2] = x.col; d[3] = (kk / 16) | 0x20000000u; d[4] = m16; d[5] = x.kind;
+      const uint32_t w = isA ? A[(size_t)x.row * lda + x.col] : B[(size_t)x.col * ldb + x.row];
+      results[t].site_word_before = w;
+      results[t].site_word_after = w ^ m16;
+      perm[ps++] = t;
+      continue;
+    }
     uint32_t* d = desc + (size_t)pf * 6;
     d[0] = t; d[1] = x.row; d[2] = x.col;
     if (k == 2) {
@@ -262,9 +275,12 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
     if (k == 3) results[t].status = 1;
     perm[pf++] = t;
   }
-  if (threadIdx.x < 8) {
-    const uint32_t q = n_fast + threadIdx.x;
-    if (q < ((n_fast + 7u) & ~7u)) {
+  if (threadIdx.x < 16) {
+    // fault-free padding behind each part, up to the next multiple of 8 positions
+    const uint32_t base2 = (n_fast + 7u) & ~7u, n_slow = n - n_fast;
+    const uint32_t q = threadIdx.x < 8 ? n_fast + threadIdx.x : base2 + n_slow + (threadIdx.x - 8);
+    const uint32_t end = threadIdx.x < 8 ? base2 : base2 + ((n_slow + 7u) & ~7u);
+    if (q < end) {
       uint32_t* d = desc + (size_t)q * 6;
       d[0] = 0; d[1] = 0; d[2] = 0; d[3] = 0xFFFFFFFFu; d[4] = 0; d[5] = 0;
     }

@@ -103,10 +103,17 @@ hipError_t launch_gemm(int dtype, int cfg, const GemmArgs& a, int n_blocks, hipS
   return hipErrorInvalidValue;
 }
 
+// Two launches: the plain instantiation on the first part of the batch (no fault, accumulator
+// flips, product-term faults), the operand-patching one on the second part (operand faults).
+// Each finds its trial count on the device and exits at once if it is zero.
 template <int DT, int MC>
 hipError_t launch_multi_cfg(const GemmArgs& a, int n_blocks, hipStream_t s) {
   constexpr MultiCfg c = kMulti[MC];
-  hipLaunchKernelGGL((fi::gemm_fi_multi_kernel<DT, c.r, c.bm, c.bn, c.wm, c.wn>), dim3(n_blocks),
+  hipLaunchKernelGGL((fi::gemm_fi_multi_kernel<DT, c.r, c.bm, c.bn, c.wm, c.wn, false>), dim3(n_blocks),
+                     dim3(c.wm * c.wn * 64), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((fi::gemm_fi_multi_kernel<DT, c.r, c.bm, c.bn, c.wm, c.wn, true>), dim3(n_blocks),
                      dim3(c.wm * c.wn * 64), 0, s, a);
   return hipGetLastError();
 }
@@ -407,8 +414,8 @@ fi_status fi_plan_describe(const fi_plan* plan, char* h_buf, uint64_t n) {
   const char* dt = plan->d.dtype == FI_BF16 ? "bf16" : "fp16";
   if (plan->mcfg >= 0) {
     const MultiCfg m = kMulti[plan->mcfg];
-    snprintf(h_buf, n, "gemm_fi_multi_kernel<%s, R=%d, %dx%d, %d threads> + gemm_fi_kernel<%s, %dx%d, %d threads> "
-             "for trials it cannot take", dt, m.r, m.bm, m.bn, m.wm * m.wn * 64, dt, c.bm, c.bn, c.wm * c.wn * 64);
+    snprintf(h_buf, n, "gemm_fi_multi_kernel<%s, R=%d, %dx%d, %d threads, persistent> (a second, operand-patching "
+             "instantiation for operand faults)", dt, m.r, m.bm, m.bn, m.wm * m.wn * 64);
   } else {
     snprintf(h_buf, n, "gemm_fi_kernel<%s, %dx%d, %d threads>", dt, c.bm, c.bn, c.wm * c.wn * 64);
   }
@@ -438,14 +445,15 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
   a.policy = (int)policy;
   a.product_check = plan->product_check;
   if (plan->mcfg >= 0) {
-    // Split the batch on the device: trials whose fault leaves the operands alone and lands on a
-    // k-tile boundary share staged operands R at a time; the rest take the single-trial kernel.
+    // R trials at a time share staged operands.  The batch is split on the device into the trials
+    // whose fault leaves the operands alone and the operand-fault trials; each part has its own
+    // instantiation of the kernel.
     if (plan->perm_cap < n_trials) {
       if (plan->perm) (void)hipFree(plan->perm);     // waits for work that may still read it
       if (plan->desc) (void)hipFree(plan->desc);
       plan->perm = nullptr; plan->desc = nullptr; plan->perm_cap = 0;
       FI_HIP(hipMalloc(&plan->perm, ((size_t)n_trials + 2) * sizeof(uint32_t)));
-      FI_HIP(hipMalloc(&plan->desc, ((size_t)n_trials + 8) * fi::kMultiDescWords * sizeof(uint32_t)));
+      FI_HIP(hipMalloc(&plan->desc, ((size_t)n_trials + 16) * fi::kMultiDescWords * sizeof(uint32_t)));
       plan->perm_cap = n_trials;
     }
     uint32_t* counts = plan->perm + plan->perm_cap;
@@ -475,6 +483,7 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
     const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8);
     const uint64_t mblocks = items < cus ? items : cus;
     FI_HIP(launch_multi((int)plan->d.dtype, plan->mcfg, m, (int)mblocks, s));
+    return FI_OK;
   }
   FI_HIP(launch_gemm<fi::MODE_CAMPAIGN>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
   return FI_OK;

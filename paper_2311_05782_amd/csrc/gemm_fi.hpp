@@ -64,12 +64,11 @@ struct GemmArgs {
   float* c_out;             // campaign: nullable [n_trials][M][N]; golden: [M][N]
   int policy;
   int product_check;        // FI_PCHECK_* applied to the erroneous product of PRODUCT faults
-  // Optional split of the batch (both NULL: every trial goes through gemm_fi_kernel in list order).
-  // perm[0 .. c0) are the trials the multi-trial kernel takes, perm[c0 .. c0+c1) the others;
-  // part_counts = {c0, c1}.
+  // For the multi-trial kernel: the batch split in two parts (trials that leave the operands
+  // alone, operand-fault trials): part_counts = {c0, c1}, perm = the trial order, desc = 6 words
+  // per trial in that order, see gemm_fi_multi.hpp.
   const uint32_t* perm;
   const uint32_t* part_counts;
-  // For the multi-trial kernel: 5 words per position of perm[0 .. c0), see gemm_fi_multi.hpp.
   const uint32_t* desc;
 };
 
@@ -259,13 +258,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   const int l32 = lane & 31, lhi = lane >> 5;
 
   int tile, trial;
-  if constexpr (MODE == MODE_CAMPAIGN) {
-    // With a permutation: only the trials the multi-trial kernel left, positions c0 .. c0+c1.
-    const int n_mine = p.perm ? (int)p.part_counts[1] : p.n_trials;
-    if (n_mine == 0 || !work_of_block(p.tiles_m * p.tiles_n, n_mine, p.group, tile, trial))
-      return;                                          // uniform, before any barrier
-    if (p.perm) trial = (int)p.perm[p.part_counts[0] + (uint32_t)trial];
-  } else if constexpr (MODE == MODE_AFFECTED) {
+  if constexpr (MODE == MODE_AFFECTED) {
     // Slot q of trial t: an accumulator or product-term fault reaches one tile (slot 0), an A
     // fault the tiles_n tiles of its tile row, a B fault the tiles_m tiles of its tile column.
     // The grid holds max(tiles_m, tiles_n) slots per trial, slot-major: consecutive workgroup

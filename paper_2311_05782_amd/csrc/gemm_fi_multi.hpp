@@ -11,11 +11,17 @@
 // Handles trials whose fault is NONE, an accumulator flip (k-blocks are multiples of the
 // 16-wide MFMA step, so every flip falls between two steps) or the paper's product-term fault
 // (Sec. III-E: written back after the 16-term step holding the term), on problems with
-// K % 64 == 0.  The library's partition kernel routes every other trial (operand faults) to
-// gemm_fi_kernel and writes, for the trials this kernel takes, one 6-word descriptor each in
-// list order: {trial, row, col, event, w0, w1} - event = the MFMA step after which the
-// accumulator changes or -1; a flip has w0 = the XOR mask; a product-term fault has bit 30 of
-// event set and w0, w1 = the words of re and re_err.
+// K % 64 == 0.  The library's partition kernel splits a batch into these trials and the
+// operand-fault trials and writes one 6-word descriptor per trial in list order:
+// {trial, row, col, event, w0, w1} - event = the MFMA step of the event or -1; a flip has
+// w0 = the XOR mask; a product-term fault has bit 30 of event set and w0, w1 = the words of re
+// and re_err; an operand fault has bit 29 set, w0 = the 16-bit mask, w1 = FI_SITE_A / _B.
+//
+// Operand faults run in a second instantiation (OPS = true) of the same kernel: the staged
+// tile is shared and stays clean; at the one MFMA step that consumes the faulted word, the
+// waves whose fragment holds it feed THAT trial a patched copy of the fragment registers - the
+// same MFMA inputs a trial of its own would have staged.  The extra code sits in the k-loop,
+// which costs the plain instantiation's speed (-14 % measured), hence two instantiations.
 //
 // Work item = (output tile, group of R trials).  The register budget (R*TM*TN*16 accumulator
 // VGPRs per lane) admits one workgroup per CU, so nothing would hide a workgroup's start-up
@@ -34,7 +40,7 @@ namespace fi {
 
 constexpr int kMultiDescWords = 6;   // trial, row, col, event, w0, w1
 
-template <int DT, int R, int BM, int BN, int WM, int WN>
+template <int DT, int R, int BM, int BN, int WM, int WN, bool OPS>
 __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmArgs p) {
   constexpr int BK = 64;
   constexpr int NW = WM * WN;
@@ -60,7 +66,9 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   const int l32 = lane & 31, lhi = lane >> 5;
 
   // ---- work list: n_tiles x ceil(n_fast / R) items, walked with the grid as stride
-  const int n_fast = (int)p.part_counts[0];
+  // OPS: the second part of the batch; its descriptors follow the first part's, padded to 8.
+  const int n_fast = (int)p.part_counts[OPS ? 1 : 0];
+  const uint32_t* const desc = p.desc + (OPS ? (size_t)((p.part_counts[0] + 7u) & ~7u) * kMultiDescWords : 0);
   const int n_groups = (n_fast + R - 1) / R;
   const uint32_t n_work = (uint32_t)(p.tiles_m * p.tiles_n) * (uint32_t)n_groups;
   uint32_t w_cur = blockIdx.x;
@@ -104,7 +112,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   };
   // A group's R descriptors, one word per lane; fields are picked out with v_readlane.
   auto load_desc = [&](int grp) -> uint32_t {
-    return lane < R * kMultiDescWords ? p.desc[(size_t)grp * (R * kMultiDescWords) + lane] : 0u;
+    return lane < R * kMultiDescWords ? desc[(size_t)grp * (R * kMultiDescWords) + lane] : 0u;
   };
 
   // ---- fragments and accumulators
@@ -135,8 +143,10 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   uint32_t desc_cur, desc_nxt = 0;                       // lane-distributed descriptor words
   int n_act = 0;                                         // trials in this group
   int trial[R], hook_step[R];                            // hook_step: -1 unless this wave owns the site
-  uint32_t affected = 0;                                 // bit r: this tile holds trial r's site
-  int next_hook = NO_HOOK;                               // earliest pending hook step of this wave
+  uint32_t affected = 0;                                 // bit r: this tile can differ from C*
+  int next_hook = NO_HOOK;                               // earliest pending accumulator event of this wave
+  uint32_t is_operand = 0;                               // bit r: trial r's event is an operand patch (OPS)
+  int next_pre = NO_HOOK;                                // earliest pending operand patch of this wave (OPS)
 
   auto desc_field = [&](int r, int field) -> uint32_t {
     return (uint32_t)__builtin_amdgcn_readlane((int)desc_cur, r * kMultiDescWords + field);
@@ -145,6 +155,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     n_act = min(R, n_fast - cur.grp * R);
     affected = 0;
     next_hook = NO_HOOK;
+    is_operand = 0;
+    next_pre = NO_HOOK;
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
       trial[r] = (int)desc_field(r, 0);
@@ -153,7 +165,20 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       const int hs = ev & 0xFFFF;
       if (r < n_act && ev >= 0) {
         const int li = (int)desc_field(r, 1) - cur.m0, lj = (int)desc_field(r, 2) - cur.n0;
-        if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
+        if (OPS && ((ev >> 29) & 1)) {
+          // A: row i = desc row, every tile of that tile row differs; B: column j = desc col.
+          const bool isA = desc_field(r, 5) == FI_SITE_A;
+          const int l = isA ? li : lj;
+          if (l >= 0 && l < (isA ? BM : BN)) {
+            affected |= 1u << r;
+            const int wl = isA ? l - wm * WTM : l - wn * WTN;
+            if (wl >= 0 && wl < (isA ? WTM : WTN)) {
+              hook_step[r] = hs;
+              is_operand |= 1u << r;
+              next_pre = min(next_pre, hs);
+            }
+          }
+        } else if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
           affected |= 1u << r;
           const int wi = li - wm * WTM, wj = lj - wn * WTN;
           if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
@@ -206,10 +231,59 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     if (g == next_hook) {
       int later = NO_HOOK;
       static_for<R>([&](auto rr) {
-        if (hook_step[rr] == g) accumulator_fault(rr);
-        else if (hook_step[rr] > g) later = min(later, hook_step[rr]);
+        constexpr int r = rr;
+        if (!((is_operand >> r) & 1u)) {
+          if (hook_step[r] == g) accumulator_fault(rr);
+          else if (hook_step[r] > g) later = min(later, hook_step[r]);
+        }
       });
       next_hook = later;
+    }
+  };
+  // MFMA step g of the item with operand patches (OPS): a trial whose faulted word is consumed
+  // here gets a copy of the fragment with that 16-bit word XORed (lane l holds row/column
+  // l % 32, k = 8*(l/32) .. +7 of the step, two k per register, even k in the low half).
+  auto mma_patched = [&](const Frags& f, int g) __attribute__((always_inline)) {
+    int later = NO_HOOK;
+    static_for<R>([&](auto rr) {
+      constexpr int r = rr;
+      Frags q = f;
+      if ((is_operand >> r) & 1u) {
+        if (hook_step[r] == g) {
+          const bool isA = desc_field(r, 5) == FI_SITE_A;
+          const int k = (int)(isA ? desc_field(r, 2) : desc_field(r, 1));
+          const int wl = isA ? (int)desc_field(r, 1) - cur.m0 - wm * WTM : (int)desc_field(r, 2) - cur.n0 - wn * WTN;
+          const int sel_lane = (wl & 31) + 32 * ((k >> 3) & 1);
+          const int sel_w = (k & 7) >> 1;
+          const uint32_t x = (lane == sel_lane) ? (desc_field(r, 4) & 0xFFFFu) << (16 * (k & 1)) : 0u;
+          if (isA) {
+            static_for<TM>([&](auto ii) {
+#pragma unroll
+              for (int w = 0; w < 4; ++w) q.a[ii][w] ^= (ii == (wl >> 5) && w == sel_w) ? x : 0u;
+            });
+          } else {
+            static_for<TN>([&](auto jj) {
+#pragma unroll
+              for (int w = 0; w < 4; ++w) q.b[jj][w] ^= (jj == (wl >> 5) && w == sel_w) ? x : 0u;
+            });
+          }
+        } else if (hook_step[r] > g) {
+          later = min(later, hook_step[r]);
+        }
+      }
+      static_for<TM * TN>([&](auto t) {
+        constexpr int i = t / TN, j = t % TN;
+        acc[r][i][j] = mfma_32x32x16<DT>(q.a[i], q.b[j], acc[r][i][j]);
+      });
+    });
+    next_pre = later;
+  };
+  auto mma_at = [&](const Frags& f, int g) __attribute__((always_inline)) {
+    if constexpr (OPS) {
+      if (g == next_pre) mma_patched(f, g);
+      else mma_step(f);
+    } else {
+      mma_step(f);
     }
   };
 
@@ -315,6 +389,10 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       if ((affected >> r) & 1u) {
         fi_trial_result* res = p.results + trial[r];
         const int site_row = (int)desc_field(r, 1), site_col = (int)desc_field(r, 2);
+        // what the fault can reach: the element, or (OPS) its output row (A) / column (B)
+        const bool op = OPS && ((desc_field(r, 3) >> 29) & 1u);
+        const bool need_row = !op || desc_field(r, 5) == FI_SITE_A;
+        const bool need_col = !op || desc_field(r, 5) == FI_SITE_B;
         uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
         float mx_pre = 0.0f, mx_post = 0.0f;
         static_for<TM * TN>([&](auto tt) {
@@ -325,8 +403,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-            // only the faulted element can differ from the fault-free result
-            if (row == site_row && col == site_col) {
+            if ((!need_row || row == site_row) && (!need_col || col == site_col) && row < p.M && col < p.N) {
               const float c = t[v];
               const size_t idx = (size_t)row * p.N + col;
               const float cs = p.c_star[idx];
@@ -403,17 +480,17 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       const uint8_t* s = smem + stage * STAGE;
       read_frags(f1, s, 1);
       __builtin_amdgcn_sched_barrier(0);
-      mma_step(f0);
+      mma_at(f0, 4 * kt);
       __builtin_amdgcn_sched_barrier(0);
       read_frags(f0, s, 2);
       hooks(4 * kt);
       __builtin_amdgcn_sched_barrier(0);
-      mma_step(f1);
+      mma_at(f1, 4 * kt + 1);
       __builtin_amdgcn_sched_barrier(0);
       read_frags(f1, s, 3);
       hooks(4 * kt + 1);
       __builtin_amdgcn_sched_barrier(0);
-      mma_step(f0);
+      mma_at(f0, 4 * kt + 2);
       __builtin_amdgcn_sched_barrier(0);
       hooks(4 * kt + 2);
       // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
@@ -422,7 +499,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       __syncthreads();
       if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
       __builtin_amdgcn_sched_barrier(0);
-      mma_step(f1);
+      mma_at(f1, 4 * kt + 3);
       __builtin_amdgcn_sched_barrier(0);
       hooks(4 * kt + 3);
       stage ^= 1;
