@@ -472,38 +472,47 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
           f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     });
 
-    for (int kt = 0; kt < nkt; ++kt) {
-      const bool last = kt + 1 == nkt;
-      const bool more = !last || has_next;              // a tile follows in the other stage
-      if (!last) issue_tile(cur, kt + 1, stage ^ 1);
-      else if (has_next) issue_tile(nxt, 0, stage ^ 1);
-      const uint8_t* s = smem + stage * STAGE;
-      read_frags(f1, s, 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mma_at(f0, 4 * kt);
-      __builtin_amdgcn_sched_barrier(0);
-      read_frags(f0, s, 2);
-      hooks(4 * kt);
-      __builtin_amdgcn_sched_barrier(0);
-      mma_at(f1, 4 * kt + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      read_frags(f1, s, 3);
-      hooks(4 * kt + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mma_at(f0, 4 * kt + 2);
-      __builtin_amdgcn_sched_barrier(0);
-      hooks(4 * kt + 2);
-      // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
-      // once all waves are here the next tile has landed and this stage may be overwritten.
-      if (more) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
-      __syncthreads();
-      if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      mma_at(f1, 4 * kt + 3);
-      __builtin_amdgcn_sched_barrier(0);
-      hooks(4 * kt + 3);
-      stage ^= 1;
-    }
+    // The k-loop exists twice: waves with no accumulator event in this item (nearly all) run a
+    // copy free of event checks; the others run the copy with the hooks.  Both execute the same
+    // barriers, so waves of one workgroup may take different copies.
+    auto k_loop = [&](auto with_events) __attribute__((always_inline)) {
+      constexpr bool EV = decltype(with_events)::value;
+      for (int kt = 0; kt < nkt; ++kt) {
+        const bool last = kt + 1 == nkt;
+        const bool more = !last || has_next;              // a tile follows in the other stage
+        if (!last) issue_tile(cur, kt + 1, stage ^ 1);
+        else if (has_next) issue_tile(nxt, 0, stage ^ 1);
+        const uint8_t* s = smem + stage * STAGE;
+        read_frags(f1, s, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_at(f0, 4 * kt);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(f0, s, 2);
+        if constexpr (EV) hooks(4 * kt);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_at(f1, 4 * kt + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(f1, s, 3);
+        if constexpr (EV) hooks(4 * kt + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_at(f0, 4 * kt + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (EV) hooks(4 * kt + 2);
+        // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
+        // once all waves are here the next tile has landed and this stage may be overwritten.
+        if (more) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
+        __syncthreads();
+        if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_at(f1, 4 * kt + 3);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (EV) hooks(4 * kt + 3);
+        stage ^= 1;
+      }
+
+    };
+    if (!OPS && next_hook == NO_HOOK) k_loop(std::false_type{});
+    else k_loop(std::true_type{});
 
     if constexpr (!EARLY_T) fetch_threshold_inputs();
     epilogue();
