@@ -137,6 +137,19 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
     });
   };
+  // The same with `mid` (a fragment read for the next step) issued after the first few MFMAs:
+  // the read lands under the rest of the burst instead of being waited for in front of it.
+  auto mma_step_mid = [&](const Frags& f, auto&& mid) __attribute__((always_inline)) {
+    static_for<R * TM * TN>([&](auto t) {
+      constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+      if constexpr (t == (R * TM * TN >= 8 ? 4 : R * TM * TN / 2)) {
+        __builtin_amdgcn_sched_barrier(0);
+        mid();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
+    });
+  };
 
   // ---- state of the current item
   Item cur, nxt;
@@ -483,9 +496,13 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         if (!last) issue_tile(cur, kt + 1, stage ^ 1);
         else if (has_next) issue_tile(nxt, 0, stage ^ 1);
         const uint8_t* s = smem + stage * STAGE;
-        read_frags(f1, s, 1);
         __builtin_amdgcn_sched_barrier(0);
-        mma_at(f0, 4 * kt);
+        if (OPS && 4 * kt == next_pre) {
+          read_frags(f1, s, 1);
+          mma_patched(f0, 4 * kt);
+        } else {
+          mma_step_mid(f0, [&]() { read_frags(f1, s, 1); });
+        }
         __builtin_amdgcn_sched_barrier(0);
         read_frags(f0, s, 2);
         if constexpr (EV) hooks(4 * kt);
