@@ -142,7 +142,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   auto mma_step_mid = [&](const Frags& f, auto&& mid) __attribute__((always_inline)) {
     static_for<R * TM * TN>([&](auto t) {
       constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
-      if constexpr (t == (R * TM * TN >= 8 ? 4 : R * TM * TN / 2)) {
+      if constexpr (t == (R * TM * TN >= 8 ? 2 : 1)) {
         __builtin_amdgcn_sched_barrier(0);
         mid();
         __builtin_amdgcn_sched_barrier(0);
@@ -488,45 +488,46 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     // The k-loop exists twice: waves with no accumulator event in this item (nearly all) run a
     // copy free of event checks; the others run the copy with the hooks.  Both execute the same
     // barriers, so waves of one workgroup may take different copies.
-    auto k_loop = [&](auto with_events) __attribute__((always_inline)) {
+    // One k-tile.  Every fragment read is issued inside the MFMA burst of the step before the
+    // one that uses it (after the first few MFMAs), so a wave never waits for a read it has just
+    // issued; the barrier sits before the last step, whose fragments the wave already holds, and
+    // the first fragments of the next tile are read inside that last burst.  LAST: the k-tile that
+    // ends an item - the tile loading into the other stage then belongs to the next item.
+    auto k_tile = [&](auto with_events, auto is_last, int kt) __attribute__((always_inline)) {
       constexpr bool EV = decltype(with_events)::value;
-      for (int kt = 0; kt < nkt; ++kt) {
-        const bool last = kt + 1 == nkt;
-        const bool more = !last || has_next;              // a tile follows in the other stage
-        if (!last) issue_tile(cur, kt + 1, stage ^ 1);
-        else if (has_next) issue_tile(nxt, 0, stage ^ 1);
-        const uint8_t* s = smem + stage * STAGE;
+      constexpr bool LAST = decltype(is_last)::value;
+      const bool more = !LAST || has_next;                // a tile follows in the other stage
+      if constexpr (!LAST) issue_tile(cur, kt + 1, stage ^ 1);
+      else if (has_next) issue_tile(nxt, 0, stage ^ 1);
+      const uint8_t* s = smem + stage * STAGE;
+      const uint8_t* s_other = smem + (stage ^ 1) * STAGE;
+      auto step = [&](const Frags& f, int g, auto&& mid) __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
-        if (OPS && 4 * kt == next_pre) {
-          read_frags(f1, s, 1);
-          mma_patched(f0, 4 * kt);
+        if (OPS && g == next_pre) {
+          mid();
+          mma_patched(f, g);
         } else {
-          mma_step_mid(f0, [&]() { read_frags(f1, s, 1); });
+          mma_step_mid(f, mid);
         }
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(f0, s, 2);
-        if constexpr (EV) hooks(4 * kt);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_at(f1, 4 * kt + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(f1, s, 3);
-        if constexpr (EV) hooks(4 * kt + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_at(f0, 4 * kt + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (EV) hooks(4 * kt + 2);
-        // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
-        // once all waves are here the next tile has landed and this stage may be overwritten.
-        if (more) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
-        __syncthreads();
-        if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_at(f1, 4 * kt + 3);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (EV) hooks(4 * kt + 3);
-        stage ^= 1;
-      }
-
+        if constexpr (EV) hooks(g);
+      };
+      step(f0, 4 * kt, [&]() { read_frags(f1, s, 1); });
+      step(f1, 4 * kt + 1, [&]() { read_frags(f0, s, 2); });
+      step(f0, 4 * kt + 2, [&]() { read_frags(f1, s, 3); });
+      // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
+      // once all waves are here the next tile has landed and this stage may be overwritten.
+      if (more) __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads have landed
+      __syncthreads();
+      step(f1, 4 * kt + 3, [&]() { if (more) read_frags(f0, s_other, 0); });
+      stage ^= 1;
+    };
+    // The k-loop exists twice: waves with no accumulator event in this item (nearly all) run a
+    // copy free of event checks; the others run the copy with the hooks.  Both execute the same
+    // barriers, so waves of one workgroup may take different copies.
+    auto k_loop = [&](auto with_events) __attribute__((always_inline)) {
+      for (int kt = 0; kt + 1 < nkt; ++kt) k_tile(with_events, std::false_type{}, kt);
+      k_tile(with_events, std::true_type{}, nkt - 1);
     };
     if (!OPS && next_hook == NO_HOOK) k_loop(std::false_type{});
     else k_loop(std::true_type{});
