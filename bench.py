@@ -27,8 +27,8 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "",
-    "fetch_bytes": 2.2017e6 * 2.0 * 1024,
+    "sources_sha256": "8f6b66148c755e308d0601723e81d03859988276c68f1c2dd4c238f8c3a12a64",
+    "fetch_bytes": 2.17157e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }
 
