@@ -469,9 +469,16 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
 #pragma unroll
     for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(s + b_rd + j * 4096 + slot);
   };
-  auto mma_step = [&](const Frags& f) {
+  // One MFMA step; `mid` (the fragment read for the next step) is issued after the first two
+  // MFMAs, so it lands under the rest of the burst and is never waited for right after its issue.
+  auto mma_step = [&](const Frags& f, auto&& mid) __attribute__((always_inline)) {
     static_for<TM * TN>([&](auto t) {
       constexpr int i = t / TN, j = t % TN;
+      if constexpr (t == (TM * TN >= 8 ? 2 : 1)) {
+        __builtin_amdgcn_sched_barrier(0);
+        mid();
+        __builtin_amdgcn_sched_barrier(0);
+      }
       acc[i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[i][j]);
     });
   };
@@ -519,9 +526,9 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   fix_tile(0, 0);
   __syncthreads();
 
-  // One barrier per k-tile, placed before the last of the four MFMA steps: the wave already
-  // holds that step's fragments, so right after the barrier it reads the first fragments of the
-  // next tile while TM*TN MFMAs of this tile are still to issue.
+  // One barrier per k-tile, placed before the last of the four MFMA steps (the wave already
+  // holds that step's fragments); every fragment read is issued inside the MFMA burst of the step
+  // before the one that uses it, the next tile's first read inside the last burst.
   Frags f0, f1;
   read_frags(f0, smem, 0);
   for (int kt = 0; kt < nkt; ++kt) {
@@ -529,26 +536,20 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     const bool more = kt + 1 < nkt;
     if (more) issue_tile(kt + 1, stage ^ 1);
     const uint8_t* s = smem + stage * STAGE;
-    read_frags(f1, s, 1);
+    const uint8_t* s_other = smem + (stage ^ 1) * STAGE;
     __builtin_amdgcn_sched_barrier(0);
-    mma_step(f0);
+    mma_step(f0, [&]() { read_frags(f1, s, 1); });
     __builtin_amdgcn_sched_barrier(0);
-    read_frags(f0, s, 2);
+    mma_step(f1, [&]() { read_frags(f0, s, 2); });
     __builtin_amdgcn_sched_barrier(0);
-    mma_step(f1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(f1, s, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step(f0);
+    mma_step(f0, [&]() { read_frags(f1, s, 3); });
     __builtin_amdgcn_sched_barrier(0);
     if (more) {
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads have landed
       fix_tile(kt + 1, stage ^ 1);
     }
     __syncthreads();
-    if (more) read_frags(f0, smem + (stage ^ 1) * STAGE, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mma_step(f1);
+    mma_step(f1, [&]() { if (more) read_frags(f0, s_other, 0); });
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (MODE != MODE_GOLDEN) {
       if (kt == hook_kt) accumulator_fault();   // one wave of one workgroup per trial
