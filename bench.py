@@ -27,7 +27,7 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "ddb1fb6a92da7658002babb542e8e24feff72c9f0c915dd10afb65e2f60f1500",
+    "sources_sha256": "",
     "fetch_bytes": 2.17157e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }

@@ -493,9 +493,13 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     // issued; the barrier sits before the last step, whose fragments the wave already holds, and
     // the first fragments of the next tile are read inside that last burst.  LAST: the k-tile that
     // ends an item - the tile loading into the other stage then belongs to the next item.
-    auto k_tile = [&](auto with_events, auto is_last, int kt) __attribute__((always_inline)) {
+    auto k_tile = [&](auto with_events, auto is_last, auto stage_c, int kt) __attribute__((always_inline)) {
       constexpr bool EV = decltype(with_events)::value;
       constexpr bool LAST = decltype(is_last)::value;
+      // stage_c: 0 or 1 when the LDS stage is known at compile time (the addresses of the
+      // fragment reads then fold into immediates), -1 to use the running variable.
+      constexpr int SC = decltype(stage_c)::value;
+      if constexpr (SC >= 0) stage = SC;
       const bool more = !LAST || has_next;                // a tile follows in the other stage
       if constexpr (!LAST) issue_tile(cur, kt + 1, stage ^ 1);
       else if (has_next) issue_tile(nxt, 0, stage ^ 1);
@@ -526,8 +530,21 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     // copy free of event checks; the others run the copy with the hooks.  Both execute the same
     // barriers, so waves of one workgroup may take different copies.
     auto k_loop = [&](auto with_events) __attribute__((always_inline)) {
-      for (int kt = 0; kt + 1 < nkt; ++kt) k_tile(with_events, std::false_type{}, kt);
-      k_tile(with_events, std::true_type{}, nkt - 1);
+      using dyn = std::integral_constant<int, -1>;
+      using st0 = std::integral_constant<int, 0>;
+      using st1 = std::integral_constant<int, 1>;
+      if ((nkt & 1) == 0 && stage == 0) {
+        // an even number of k-tiles: every item starts in stage 0 and the stages alternate statically
+        for (int kt = 0; kt + 2 < nkt; kt += 2) {
+          k_tile(with_events, std::false_type{}, st0{}, kt);
+          k_tile(with_events, std::false_type{}, st1{}, kt + 1);
+        }
+        k_tile(with_events, std::false_type{}, st0{}, nkt - 2);
+        k_tile(with_events, std::true_type{}, st1{}, nkt - 1);
+      } else {
+        for (int kt = 0; kt + 1 < nkt; ++kt) k_tile(with_events, std::false_type{}, dyn{}, kt);
+        k_tile(with_events, std::true_type{}, dyn{}, nkt - 1);
+      }
     };
     if (!OPS && next_hook == NO_HOOK) k_loop(std::false_type{});
     else k_loop(std::true_type{});
