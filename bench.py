@@ -256,6 +256,19 @@ def main():
             torch.cuda.synchronize()
             others[name]["affected_only_trials_per_s"] = round(5 * ww.n_trials / (time.perf_counter() - t1), 1)
             pl.destroy()
+            if name == "detector_stress":
+                # Coverage of the three output-side detectors on the same fault list (Sec. VI-A's
+                # exponent-only bound check against the operand-derived magnitude bounds).
+                cov = {}
+                for label, mode in (("rowcol", fi.BOUND_ROWCOL), ("global", fi.BOUND_GLOBAL), ("exponent", fi.BOUND_EXPONENT)):
+                    pb = fi.Plan(fi.plan_desc(ww.M, ww.N, ww.K, ww.kb, ww.fmt, bound_mode=mode),
+                                 fi.words_to_device(ww.A), fi.words_to_device(ww.B))
+                    pb.fi_gemm_inject_batch_affected(ff, ww.n_trials, ww.policies[0], rr)
+                    pb.fi_classify(rr, ww.n_trials, d_cls[:1].new_empty(ww.n_trials), d_cnt)
+                    torch.cuda.synchronize()
+                    cov[label] = [int(x) for x in d_cnt.cpu().tolist()]
+                    pb.destroy()
+                others[name]["masked_sdc_detected_by_detector"] = cov
         out["other_campaigns"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

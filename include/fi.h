@@ -52,7 +52,7 @@ enum {
 enum { FI_FP16 = 0, FI_BF16 = 1 };
 enum { FI_SITE_NONE = 0, FI_SITE_ACC = 1, FI_SITE_A = 2, FI_SITE_B = 3, FI_SITE_PRODUCT = 4 };
 enum { FI_CORRECT_NONE = 0, FI_CORRECT_ZERO = 1, FI_CORRECT_RECOMPUTE = 2 };
-enum { FI_BOUND_ROWCOL = 0, FI_BOUND_GLOBAL = 1 };
+enum { FI_BOUND_ROWCOL = 0, FI_BOUND_GLOBAL = 1, FI_BOUND_EXPONENT = 2 };
 enum { FI_MASKED = 0, FI_SDC = 1, FI_DETECTED = 2 };
 /* Exponent-only checks of the erroneous product of a PRODUCT fault (Sec. VI-A). */
 enum { FI_PCHECK_NONE = 0, FI_PCHECK_BOUND = 1, FI_PCHECK_RANGE_MAX = 2, FI_PCHECK_RANGE_FLIP = 3 };
@@ -111,7 +111,10 @@ typedef struct {
   uint32_t dtype;        /* FI_FP16 / FI_BF16 */
   uint32_t b_layout;
   uint32_t bound_mode;   /* FI_BOUND_ROWCOL: T_ij = gamma*K*ra_i*cb_j, ra_i = max_k|a_ik|,
-                            cb_j = max_k|b_kj|; FI_BOUND_GLOBAL: gamma*K*max ra*max cb */
+                            cb_j = max_k|b_kj|; FI_BOUND_GLOBAL: gamma*K*max ra*max cb;
+                            FI_BOUND_EXPONENT: the bound check of Sec. VI-A read on the binary32
+                            output word, exponent 1eeexxxx with a 1 among eee, i.e. flag where
+                            |c| >= 2^17 (and Inf, NaN); uses no operand statistics or gamma */
   float    gamma;        /* >= 1; 0 selects the default 1 + 2^-11 */
   int64_t  lda, ldb;     /* in elements */
 } fi_plan_desc;

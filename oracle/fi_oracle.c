@@ -353,6 +353,8 @@ static float vec_max(const float* v, int n) {
 static float threshold_at(const orc_problem* p, const float* ra, const float* cb,
                           float ra_max, float cb_max, int i, int j) {
   if (p->bound_mode == ORC_BOUND_GLOBAL) return orc_threshold(p->K, ra_max, cb_max, p->gamma);
+  /* Exponent field >= 128 + 16 <=> |c| >= 2^17 <=> NOT (|c| <= the float just below 2^17). */
+  if (p->bound_mode == ORC_BOUND_EXPONENT) return 131071.9921875f;
   return orc_threshold(p->K, ra[i], cb[j], p->gamma);
 }
 

@@ -37,7 +37,10 @@ extern "C" {
 enum { ORC_FP16 = 0, ORC_BF16 = 1 };
 enum { ORC_SITE_NONE = 0, ORC_SITE_ACC = 1, ORC_SITE_A = 2, ORC_SITE_B = 3, ORC_SITE_PRODUCT = 4 };
 enum { ORC_CORRECT_NONE = 0, ORC_CORRECT_ZERO = 1, ORC_CORRECT_RECOMPUTE = 2 };
-enum { ORC_BOUND_ROWCOL = 0, ORC_BOUND_GLOBAL = 1 };
+enum { ORC_BOUND_ROWCOL = 0, ORC_BOUND_GLOBAL = 1,
+       /* Sec. VI-A bound check read on a binary32 output word: exponent 1eeexxxx with a 1 among
+        * eee, i.e. |value| >= 2^17 (or Inf / NaN); needs no operand statistics. */
+       ORC_BOUND_EXPONENT = 2 };
 enum { ORC_MASKED = 0, ORC_SDC = 1, ORC_DETECTED = 2 };
 enum { ORC_MODE_FULL = 0, ORC_MODE_AFFECTED = 1 };
 /* Exponent-only checks of an erroneous product (Sec. VI-A). */

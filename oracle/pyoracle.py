@@ -16,7 +16,7 @@ _LIB = os.path.join(_HERE, "libfi_oracle.so")
 FP16, BF16 = 0, 1
 SITE_NONE, SITE_ACC, SITE_A, SITE_B, SITE_PRODUCT = 0, 1, 2, 3, 4
 CORRECT_NONE, CORRECT_ZERO, CORRECT_RECOMPUTE = 0, 1, 2
-BOUND_ROWCOL, BOUND_GLOBAL = 0, 1
+BOUND_ROWCOL, BOUND_GLOBAL, BOUND_EXPONENT = 0, 1, 2
 MASKED, SDC, DETECTED = 0, 1, 2
 MODE_FULL, MODE_AFFECTED = 0, 1
 KIND_ALL_ACC, KIND_ALL_A, KIND_ALL_B, KIND_MIX_ACC_A, KIND_ALL_PRODUCT = 0, 1, 2, 3, 4

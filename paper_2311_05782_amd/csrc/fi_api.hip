@@ -148,7 +148,7 @@ GemmArgs base_args(const fi_plan* p, int cfg = -1) {
   a.tiles_m = (a.M + c.bm - 1) / c.bm;
   a.tiles_n = (a.N + c.bn - 1) / c.bn;
   a.kra = p->kra; a.cb = p->cb; a.gamma = p->d.gamma;
-  a.bound_global = p->d.bound_mode == FI_BOUND_GLOBAL;
+  a.bound_global = p->d.bound_mode != FI_BOUND_ROWCOL;
   a.t_global = p->t_global;
   a.c_star = p->c_star; a.s_abs = p->s_abs;
   return a;
@@ -190,7 +190,7 @@ fi_status check_desc(const fi_plan_desc* d, float* gamma_out) {
   if (d->dtype != FI_FP16 && d->dtype != FI_BF16)
     return fail(FI_UNSUPPORTED, "dtype %u: only FP16 (0) and BF16 (1) operands", d->dtype);
   if (d->b_layout > 1) return fail(FI_INVALID_ARG, "b_layout must be 0 or 1");
-  if (d->bound_mode > 1) return fail(FI_INVALID_ARG, "bound_mode must be 0 or 1");
+  if (d->bound_mode > FI_BOUND_EXPONENT) return fail(FI_INVALID_ARG, "bound_mode must be 0, 1 or 2");
   float g = d->gamma == 0.0f ? 1.0f + 1.0f / 2048.0f : d->gamma;
   if (!(g >= 1.0f) || !(g <= 3.0e38f)) return fail(FI_INVALID_ARG, "gamma must be finite and >= 1");
   if (d->K > 65536u) return fail(FI_UNSUPPORTED, "K > 65536");
@@ -292,6 +292,8 @@ fi_status build_plan(fi_plan* p, const void* d_A, const void* d_B, hipStream_t s
   volatile float t = host[0] * host[1];
   t = t * d.gamma;
   p->t_global = t;
+  // Exponent field >= 144 <=> NOT (|c| <= largest binary32 below 2^17)
+  if (d.bound_mode == FI_BOUND_EXPONENT) p->t_global = 131071.9921875f;
   return FI_OK;
 }
 
@@ -538,11 +540,11 @@ fi_status fi_detect_correct(fi_plan* plan, float* d_c, uint32_t batch, uint32_t 
   dim3 grid((unsigned)gx, batch);
   if (vec) {
     hipLaunchKernelGGL(fi::detect_correct_kernel<4>, grid, dim3(256), 0, s, d_c, (int)d.M, (int)d.N, plan->kra,
-                       plan->cb, d.gamma, (int)(d.bound_mode == FI_BOUND_GLOBAL), plan->t_global, (int)policy,
+                       plan->cb, d.gamma, (int)(d.bound_mode != FI_BOUND_ROWCOL), plan->t_global, (int)policy,
                        plan->c_star, d_flags, d_n_flagged);
   } else {
     hipLaunchKernelGGL(fi::detect_correct_kernel<1>, grid, dim3(256), 0, s, d_c, (int)d.M, (int)d.N, plan->kra,
-                       plan->cb, d.gamma, (int)(d.bound_mode == FI_BOUND_GLOBAL), plan->t_global, (int)policy,
+                       plan->cb, d.gamma, (int)(d.bound_mode != FI_BOUND_ROWCOL), plan->t_global, (int)policy,
                        plan->c_star, d_flags, d_n_flagged);
   }
   FI_HIP(hipGetLastError());

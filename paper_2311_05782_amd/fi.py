@@ -18,7 +18,7 @@ OK, INVALID_ARG, UNSUPPORTED, OOM, DEVICE, STATE = range(6)
 FP16, BF16 = 0, 1
 SITE_NONE, SITE_ACC, SITE_A, SITE_B, SITE_PRODUCT = 0, 1, 2, 3, 4
 CORRECT_NONE, CORRECT_ZERO, CORRECT_RECOMPUTE = 0, 1, 2
-BOUND_ROWCOL, BOUND_GLOBAL = 0, 1
+BOUND_ROWCOL, BOUND_GLOBAL, BOUND_EXPONENT = 0, 1, 2
 MASKED, SDC, DETECTED = 0, 1, 2
 PCHECK_NONE, PCHECK_BOUND, PCHECK_RANGE_MAX, PCHECK_RANGE_FLIP = 0, 1, 2, 3
 HIST_SITE, HIST_DEV_PRE, HIST_DEV_POST = 0, 1, 2

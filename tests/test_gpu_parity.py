@@ -302,6 +302,33 @@ def test_standalone_detector_equals_fused_epilogue_and_oracle(N):
     plan.destroy()
 
 
+@pytest.mark.parametrize("cfg", [0, 5])
+def test_exponent_bound_detector_campaign_and_standalone(cfg):
+    import torch
+    M, N, K, kb, fmt = 200, 136, 128, 64, orc.BF16
+    Aw, Bw = wl.gaussian(M, N, K, fmt, seed=21)
+    p = orc.problem(M, N, K, kb, fmt, bound_mode=orc.BOUND_EXPONENT)
+    plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg, bound_mode=fi.BOUND_EXPONENT)
+    faults = fi.fi_sample_faults(5, 0, 512, plan.desc, fi.KIND_MIX_ACC_A, 1)
+    faults["xor_mask"][::2] = 1 << np.random.default_rng(0).integers(23, 31, size=256).astype(np.uint32)
+    recs, raw = gu.gpu_campaign(plan, faults, wl.CORRECT_NONE, want_c=True)
+    s = gu.compare_records(recs, orc.campaign(p, Aw, Bw, gu.to_orc_faults(faults), wl.CORRECT_NONE), faults, site_tol=1.0)
+    assert not s["mismatches"], s["mismatches"][:5]
+    assert (recs["n_flagged"] > 0).sum() > 20
+    # the flag is a function of the output word alone: exponent 1eeexxxx with a 1 among eee
+    e = (raw.view(np.uint32) >> 23) & 0xFF
+    want = ((e & 0x80) != 0) & ((e & 0x70) != 0)
+    assert np.array_equal(recs["n_flagged"], want.reshape(len(faults), -1).sum(axis=1).astype(np.uint32))
+    d_c = torch.from_numpy(raw.copy()).cuda()
+    d_fl = torch.empty(raw.shape, dtype=torch.uint8, device="cuda")
+    d_n = torch.empty(len(faults), dtype=torch.int32, device="cuda")
+    plan.fi_detect_correct(d_c, len(faults), wl.CORRECT_ZERO, d_fl, d_n)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_fl.cpu().numpy().astype(bool), want)
+    assert np.array_equal(d_c.cpu().numpy().view(np.uint32), np.where(want, 0, raw.view(np.uint32)))
+    plan.destroy()
+
+
 def test_campaign_calls_replay_correctly_from_a_hip_graph():
     # The library clears records and counters with kernels, not memsets, so its calls can be
     # captured.  Replays are interleaved with eager work and synchronisations and every replay is
