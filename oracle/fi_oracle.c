@@ -627,6 +627,78 @@ int orc_campaign(const orc_problem* p, const uint16_t* A, const uint16_t* B,
   return 0;
 }
 
+/* ------------------------------------------- two layers: hand-over and propagation
+ * Sec. I asks for the gap between the resilience of one matrix multiplication and of what the
+ * application computes from it.  The smallest such application is a second layer: the (possibly
+ * faulty, possibly corrected) output of the first GEMM passes a ReLU, is rounded to the operand
+ * format and becomes the A operand of the next GEMM. */
+uint16_t orc_activation_round_one(float c, int fmt) {
+  float r;
+  if (isnan(c)) r = c;            /* a NaN stays a NaN */
+  else if (c > 0.0f) r = c;
+  else r = 0.0f;                  /* negatives and -0 become +0 */
+  return orc_round16(r, fmt);
+}
+
+void orc_activation_round(const float* c, size_t n, int fmt, uint16_t* h) {
+  for (size_t e = 0; e < n; ++e) h[e] = orc_activation_round_one(c[e], fmt);
+}
+
+/* Trial t multiplies ITS OWN A operand, A_stack + t * trial_stride (same leading dimension as
+ * A), by the plan's B; nothing is injected.  Every output element is compared with the
+ * fault-free C* = A x B, passed through the detector / corrector and counted (O4-O6), the
+ * statistics and tolerances being those of the GOLDEN operands.  Mode FULL recomputes every
+ * element; mode AFFECTED takes the rows whose operand words all equal the golden row's from
+ * C* (the same deterministic dot products would reproduce them bit for bit). */
+int orc_propagate(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                  const uint16_t* A_stack, size_t trial_stride, int n_trials, int policy,
+                  int mode, float* cc_out, orc_record* recs) {
+  if (check_problem(p) || !A || !B || !A_stack || !recs || n_trials < 0) return 1;
+  if (policy < 0 || policy > 2) return 1;
+  int M = p->M, N = p->N, K = p->K;
+  size_t mn = (size_t)M * N;
+  float *Af = NULL, *Bt = NULL;
+  int rc = decode_operands(p, A, B, &Af, &Bt);
+  if (rc) return rc;
+  float* Cstar = (float*)malloc(sizeof(float) * mn);
+  double* S = (double*)malloc(sizeof(double) * mn);
+  float* ra = (float*)malloc(sizeof(float) * (size_t)M);
+  float* cb = (float*)malloc(sizeof(float) * (size_t)N);
+  orc_rowcol_absmax(p, A, B, ra, cb);
+  float ra_max = vec_max(ra, M), cb_max = vec_max(cb, N);
+  gemm_decoded(M, N, K, p->kb, Af, Bt, -1, -1, NO_FAULT, Cstar, NULL, S, NULL, NULL);
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+  for (int t = 0; t < n_trials; ++t) {
+    const uint16_t* At = A_stack + (size_t)t * trial_stride;
+    float* a = (float*)malloc(sizeof(float) * (size_t)K);
+    orc_record* rec = &recs[t];
+    clear_record(rec);
+    for (int i = 0; i < M; ++i) {
+      int same = 1;
+      for (int k = 0; k < K; ++k) {
+        uint16_t w = a_word(p, At, i, k);
+        if (w != a_word(p, A, i, k)) same = 0;
+        a[k] = dec(w, p->fmt);
+      }
+      for (int j = 0; j < N; ++j) {
+        size_t e = (size_t)i * N + j;
+        float c_f = (mode == ORC_MODE_AFFECTED && same)
+                        ? Cstar[e]
+                        : dot_blocked(a, Bt + (size_t)j * K, K, p->kb, NO_FAULT, NULL, NULL);
+        float T = threshold_at(p, ra, cb, ra_max, cb_max, i, j);
+        account(rec, c_f, Cstar[e], S[e], T, policy);
+        if (cc_out) cc_out[(size_t)t * mn + e] = corrected(c_f, flagged(c_f, T), policy, Cstar[e]);
+      }
+    }
+    finish(rec);
+    free(a);
+  }
+  free(Af); free(Bt); free(Cstar); free(S); free(ra); free(cb);
+  return 0;
+}
+
 void orc_classify(const orc_record* recs, int n, uint8_t* cls, uint64_t counts[3]) {
   counts[0] = counts[1] = counts[2] = 0;
   for (int t = 0; t < n; ++t) {

@@ -150,6 +150,19 @@ int orc_campaign(const orc_problem* p, const uint16_t* A, const uint16_t* B,
                  const orc_fault* faults, int n_trials, int policy, int mode,
                  orc_record* recs);
 
+/* Hand-over between two layers: h = RNE_fmt(relu(c)), relu keeping NaN and mapping negatives
+ * and -0 to +0 (Sec. I: from the resilience of one GEMM to that of what is computed from it). */
+uint16_t orc_activation_round_one(float c, int fmt);
+void orc_activation_round(const float* c, size_t n, int fmt, uint16_t* h);
+
+/* The next layer's GEMM with a per-trial A operand (trial t reads A_stack + t*trial_stride,
+ * leading dimension p->lda) and no fault of its own; records compare every output element
+ * with C* = A x B.  cc_out (nullable) is [n_trials][M][N].  mode: ORC_MODE_FULL recomputes
+ * every element, ORC_MODE_AFFECTED only the rows whose operand words differ from A's. */
+int orc_propagate(const orc_problem* p, const uint16_t* A, const uint16_t* B,
+                  const uint16_t* A_stack, size_t trial_stride, int n_trials, int policy,
+                  int mode, float* cc_out, orc_record* recs);
+
 /* O6 classification totals: counts[0..2] = masked, sdc, detected. */
 void orc_classify(const orc_record* recs, int n, uint8_t* cls, uint64_t counts[3]);
 

@@ -87,6 +87,10 @@ def lib():
         L.orc_campaign.argtypes = [PP, u16p, u16p, vp, C.c_int, C.c_int, C.c_int, vp]
         L.orc_deviation_histogram.restype = None
         L.orc_deviation_histogram.argtypes = [vp, vp, C.c_int, C.c_int, vp]
+        L.orc_activation_round.restype = None
+        L.orc_activation_round.argtypes = [f32p, C.c_size_t, C.c_int, u16p]
+        L.orc_propagate.restype = C.c_int
+        L.orc_propagate.argtypes = [PP, u16p, u16p, u16p, C.c_size_t, C.c_int, C.c_int, C.c_int, f32p, vp]
         L.orc_classify.restype = None
         L.orc_classify.argtypes = [vp, C.c_int, vp, vp]
         L.orc_splitmix64_next.restype = C.c_uint64
@@ -219,6 +223,30 @@ def campaign(p, A, B, faults, policy, mode=MODE_AFFECTED):
     if rc:
         raise ValueError("orc_campaign failed: %d" % rc)
     return recs
+
+
+def activation_round(c, fmt):
+    """h = RNE_fmt(relu(c)) as 16-bit words, same shape as c."""
+    c = np.ascontiguousarray(c, np.float32)
+    h = np.empty(c.shape, np.uint16)
+    lib().orc_activation_round(_ptr(c), c.size, fmt, _ptr(h))
+    return h
+
+
+def propagate(p, A, B, A_stack, policy, mode=MODE_FULL, want_outputs=False):
+    """A_stack: [n_trials, M, lda] words, trial t's own A operand.  Returns records (and the
+    corrected outputs [n_trials, M, N])."""
+    A, B = _u16(A), _u16(B)
+    A_stack = _u16(A_stack)
+    assert A_stack.ndim == 3 and A_stack.shape[1] == p.M and A_stack.shape[2] == p.lda
+    n = A_stack.shape[0]
+    recs = np.zeros(n, RECORD_DTYPE)
+    cc = np.empty((n, p.M, p.N), np.float32) if want_outputs else None
+    rc = lib().orc_propagate(C.byref(p), _ptr(A), _ptr(B), _ptr(A_stack), p.M * p.lda, n, policy, mode,
+                             _ptr(cc), _ptr(recs))
+    if rc:
+        raise ValueError("orc_propagate failed: %d" % rc)
+    return (recs, cc) if want_outputs else recs
 
 
 HIST_SITE, HIST_DEV_PRE, HIST_DEV_POST = 0, 1, 2

@@ -42,8 +42,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 // CAMPAIGN: every tile of every trial.  GOLDEN: the plan's fault-free pass.  AFFECTED: only the
-// tiles a trial's fault can reach (one workgroup slot per trial and candidate tile).
-enum { MODE_CAMPAIGN = 0, MODE_GOLDEN = 1, MODE_AFFECTED = 2 };
+// tiles a trial's fault can reach (one workgroup slot per trial and candidate tile).  PROPAGATE:
+// no fault of its own; every trial multiplies its OWN A operand (the activations a faulty
+// previous layer handed on) and every output element is compared with the fault-free result.
+enum { MODE_CAMPAIGN = 0, MODE_GOLDEN = 1, MODE_AFFECTED = 2, MODE_PROPAGATE = 3 };
 
 struct GemmArgs {
   const uint16_t* A;        // [M][lda]
@@ -70,6 +72,7 @@ struct GemmArgs {
   const uint32_t* perm;
   const uint32_t* part_counts;
   const uint32_t* desc;
+  uint64_t a_trial_stride;  // PROPAGATE: trial t reads A + t * a_trial_stride (elements)
 };
 
 template <int DT>
@@ -300,7 +303,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
   int sel_t = 0, sel_v = 0, sel_lane = -1;
   bool affected = false;    // this tile can differ from the fault-free result
   int opfault_kt = -1;      // k-tile in which this workgroup stages a faulted operand word
-  if constexpr (MODE != MODE_GOLDEN) {
+  if constexpr (MODE == MODE_PROPAGATE) affected = true;
+  if constexpr (MODE == MODE_CAMPAIGN || MODE == MODE_AFFECTED) {
     const fi_fault f = p.faults[trial];
     fkind = f.kind; frow = f.row; fcol = f.col; fmask = f.xor_mask;
     bool valid = true;
@@ -374,6 +378,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
 
   typedef __attribute__((address_space(3))) void lds_void;
   typedef const __attribute__((address_space(1))) void glb_void;
+  const uint16_t* const Ap = MODE == MODE_PROPAGATE ? p.A + (size_t)trial * p.a_trial_stride : p.A;
 
   // Issue the loads of k-tile kt into `stage`.  Returns false if the tile is not wholly inside
   // [0, K): then fix_tile() must zero what lies outside once the loads have landed.
@@ -385,7 +390,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     if (inside) {
 #pragma unroll
       for (int c = 0; c < A_G; ++c)
-        __builtin_amdgcn_global_load_lds((glb_void*)(p.A + a_goff[c] + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(Ap + a_goff[c] + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
 #pragma unroll
       for (int c = 0; c < B_G; ++c)
         __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
@@ -395,7 +400,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
       for (int c = 0; c < A_G; ++c) {
         const int ch = (lslot ^ lds_swizzle((wave * A_G + c) * 8 + lrow)) * 8;
         const bool kin = (k0 + ch) >= 0 && (k0 + ch) < p.K;
-        __builtin_amdgcn_global_load_lds((glb_void*)(p.A + a_goff[c] + (kin ? k0 : 0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(Ap + a_goff[c] + (kin ? k0 : 0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
       }
 #pragma unroll
       for (int c = 0; c < B_G; ++c) {
@@ -426,7 +431,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
         if (!((k0 + ch) >= 0 && (k0 + ch) < p.K)) *reinterpret_cast<u32x4*>(sB + c * 1024) = zero4;
       }
     }
-    if constexpr (MODE != MODE_GOLDEN) {
+    if constexpr (MODE == MODE_CAMPAIGN || MODE == MODE_AFFECTED) {
       if (kt == opfault_kt) {
         const bool isA = fkind == FI_SITE_A;
         const int kk = (isA ? (int)fcol : (int)frow) - kt * BK;            // 0..63 (kshift is 0 here)
@@ -551,7 +556,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
     __syncthreads();
     mma_step(f1, [&]() { if (more) read_frags(f0, s_other, 0); });
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (MODE != MODE_GOLDEN) {
+    if constexpr (MODE == MODE_CAMPAIGN || MODE == MODE_AFFECTED) {
       if (kt == hook_kt) accumulator_fault();   // one wave of one workgroup per trial
     }
   }
@@ -624,7 +629,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
             const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
             // Only what the fault can reach differs from the fault-free result: the element
             // itself, or its output row (A fault) / column (B fault).
-            const bool reach = (fkind == FI_SITE_B || row == (int)frow) && (fkind == FI_SITE_A || col == (int)fcol);
+            const bool reach = MODE == MODE_PROPAGATE ||
+                               ((fkind == FI_SITE_B || row == (int)frow) && (fkind == FI_SITE_A || col == (int)fcol));
             if (row < p.M && col < p.N && reach) {
               const float c = t[v];
               const size_t idx = (size_t)row * p.N + col;
