@@ -191,6 +191,33 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
 fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
                                         uint32_t policy, fi_trial_result* d_results, void* stream);
 
+/* Hand-over between two layers (Sec. I: from the resilience of one matrix multiplication to
+ * that of what the application computes from it; Sec. V-B (i): zeros are common in
+ * activations): d_h[e] = RNE_fmt(relu(d_c[e])) for n elements, as 16-bit words of `dtype`.
+ * relu keeps a NaN (handed on as the format's quiet NaN) and maps negatives and -0 to +0;
+ * values beyond the format's range round to +Inf.  d_c (device, 16-byte aligned) is not
+ * modified; d_h (device, 8-byte aligned) is overwritten.  No plan is needed.
+ * Errors: UNSUPPORTED (dtype, alignment), INVALID_ARG (NULLs, n == 0). */
+fi_status fi_activation_round(uint32_t dtype, const float* d_c, uint64_t n, uint16_t* d_h, void* stream);
+
+/* The next layer of a two-layer workload: n_trials executions of the plan's GEMM in one launch,
+ * trial t with ITS OWN A operand d_a_stack + t * trial_stride (device, 16-bit words, [M][lda]
+ * like the plan's A; trial_stride in elements, a multiple of 8, at least (M-1)*lda + K, or 0
+ * to give every trial the same operand) and the plan's B; no fault is injected.  Every output
+ * element of every trial passes the plan's detector / corrector and is compared with the
+ * plan's fault-free result C* = A x B under the plan's tolerance: d_results[t] holds
+ * n_flagged, n_bitdiff, n_dev_pre, n_dev_post, the largest deviations and the guard-band
+ * counts over the whole output (site words 0).  Rows of a trial's operand that equal the
+ * plan's A word for word reproduce the rows of C* bit for bit.  A trial's operand may hold
+ * Inf or NaN (they propagate as IEEE and are flagged).  d_c_out as in fi_gemm_inject_batch.
+ * The caller owns d_a_stack and keeps it unmodified until the work has run.  All 2*M*N*K
+ * flops of every trial are executed (one trial per workgroup tile; tile configurations 0..2).
+ * Errors: INVALID_ARG (NULLs, n_trials == 0, bad policy, trial_stride too small),
+ * UNSUPPORTED (alignment; tiles x trials >= 2^31). */
+fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t trial_stride,
+                                  uint32_t n_trials, uint32_t policy, fi_trial_result* d_results,
+                                  float* d_c_out, void* stream);
+
 /* The detector / corrector alone on materialised outputs (Sec. VI-A/B):
  * d_c is [batch][M][N], corrected in place; d_flags is NULL or
  * [batch][M][N] bytes (1 = flagged); d_n_flagged is NULL or [batch] counters,

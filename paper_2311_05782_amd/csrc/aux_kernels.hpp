@@ -194,6 +194,34 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
   }
 }
 
+// Hand-over between two layers: h = RNE_fmt(relu(c)).  relu keeps a NaN and maps negatives
+// and -0 to +0; the rounding is the integer one of round16 (no dependence on the wave's float
+// modes).  HBM bound: 4 bytes read, 2 written per element; four elements per lane and step.
+template <int DT>
+__global__ void __launch_bounds__(256) activation_round_kernel(const float* __restrict__ c, size_t n,
+                                                              uint16_t* __restrict__ h) {
+  const size_t n4 = n / 4;
+  const size_t step = (size_t)gridDim.x * 256;
+  const size_t first = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (size_t i = first; i < n4; i += step) {
+    const f32x4_t v = reinterpret_cast<const f32x4_t*>(c)[i];
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float x = v[e];
+      w[e] = round16<DT>((x > 0.0f || x != x) ? x : 0.0f);
+    }
+    uint2 o;
+    o.x = w[0] | (w[1] << 16);
+    o.y = w[2] | (w[3] << 16);
+    reinterpret_cast<uint2*>(h)[i] = o;
+  }
+  for (size_t i = n4 * 4 + first; i < n; i += step) {
+    const float x = c[i];
+    h[i] = (uint16_t)round16<DT>((x > 0.0f || x != x) ? x : 0.0f);
+  }
+}
+
 // Splits a batch: trials the multi-trial GEMM kernel can take (no fault, an accumulator flip or
 // a product-term fault; out-of-range sites count as "no fault" and get status 1 in their zeroed
 // record) go to the front of perm in list order, all others (operand faults) behind them.

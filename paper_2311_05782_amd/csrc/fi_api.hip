@@ -517,6 +517,57 @@ fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults,
   return FI_OK;
 }
 
+fi_status fi_activation_round(uint32_t dtype, const float* d_c, uint64_t n, uint16_t* d_h, void* stream) {
+  if (dtype != FI_FP16 && dtype != FI_BF16)
+    return fail(FI_UNSUPPORTED, "dtype %u: only FP16 (0) and BF16 (1)", dtype);
+  if (!d_c || !d_h) return fail(FI_INVALID_ARG, "d_c and d_h must be non-NULL");
+  if (n == 0) return fail(FI_INVALID_ARG, "n is 0");
+  if ((reinterpret_cast<uintptr_t>(d_c) & 15u) || (reinterpret_cast<uintptr_t>(d_h) & 7u))
+    return fail(FI_UNSUPPORTED, "d_c must be 16-byte and d_h 8-byte aligned");
+  uint64_t blocks = (n / 4 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks == 0) blocks = 1;
+  if (dtype == FI_BF16)
+    hipLaunchKernelGGL(fi::activation_round_kernel<FI_BF16>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream),
+                       d_c, (size_t)n, d_h);
+  else
+    hipLaunchKernelGGL(fi::activation_round_kernel<FI_FP16>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream),
+                       d_c, (size_t)n, d_h);
+  FI_HIP(hipGetLastError());
+  return FI_OK;
+}
+
+fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t trial_stride, uint32_t n_trials,
+                                  uint32_t policy, fi_trial_result* d_results, float* d_c_out, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_a_stack || !d_results) return fail(FI_INVALID_ARG, "d_a_stack and d_results must be non-NULL");
+  if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
+  if (policy > FI_CORRECT_RECOMPUTE) return fail(FI_INVALID_ARG, "unknown correction policy %u", policy);
+  if ((reinterpret_cast<uintptr_t>(d_a_stack) & 15u) || (trial_stride & 7u))
+    return fail(FI_UNSUPPORTED, "d_a_stack must be 16-byte aligned with trial_stride a multiple of 8");
+  if (trial_stride != 0 && trial_stride < ((uint64_t)plan->d.M - 1) * (uint64_t)plan->d.lda + plan->d.K)
+    return fail(FI_INVALID_ARG, "trial_stride %llu is smaller than one operand ((M-1)*lda + K elements)",
+                (unsigned long long)trial_stride);
+  GemmArgs a = base_args(plan);
+  const uint64_t blocks = (uint64_t)a.tiles_m * a.tiles_n * n_trials;
+  if (blocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
+  hipStream_t s = as_stream(stream);
+  const size_t words = (size_t)n_trials * (sizeof(fi_trial_result) / 4);
+  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3((unsigned)((words + 255) / 256 > 1024 ? 1024 : (words + 255) / 256)),
+                     dim3(256), 0, s, reinterpret_cast<uint32_t*>(d_results), words, 0u);
+  FI_HIP(hipGetLastError());
+  a.A = static_cast<const uint16_t*>(d_a_stack);
+  a.a_trial_stride = trial_stride;
+  a.n_trials = (int)n_trials;
+  a.group = plan->group;
+  a.results = d_results;
+  a.c_out = d_c_out;
+  a.policy = (int)policy;
+  FI_HIP(launch_gemm<fi::MODE_PROPAGATE>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
+  return FI_OK;
+}
+
 fi_status fi_detect_correct(fi_plan* plan, float* d_c, uint32_t batch, uint32_t policy, uint8_t* d_flags,
                             uint32_t* d_n_flagged, void* stream) {
   fi_status st = check_plan(plan);

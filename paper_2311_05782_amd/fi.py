@@ -29,7 +29,7 @@ BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
            "fi_plan_set_product_check", "fi_deviation_histogram",
            "fi_gemm_inject_batch", "fi_gemm_inject_batch_affected", "fi_detect_correct", "fi_classify", "fi_sample_faults",
-           "fi_last_error"]
+           "fi_activation_round", "fi_gemm_propagate_batch", "fi_last_error"]
 
 FAULT_DTYPE = np.dtype([("kind", "<u4"), ("row", "<u4"), ("col", "<u4"), ("kblock", "<u4"),
                         ("xor_mask", "<u4")])
@@ -84,6 +84,8 @@ def lib():
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch_affected.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp]
     L.fi_detect_correct.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
+    L.fi_activation_round.argtypes = [C.c_uint32, vp, C.c_uint64, vp, vp]
+    L.fi_gemm_propagate_batch.argtypes = [vp, vp, C.c_uint64, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_classify.argtypes = [vp, vp, C.c_uint32, vp, vp, vp]
     L.fi_deviation_histogram.argtypes = [vp, vp, vp, C.c_uint32, C.c_uint32, vp, vp]
     L.fi_sample_faults.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.POINTER(PlanDesc), C.c_uint32,
@@ -132,6 +134,10 @@ def fi_sample_faults(seed, first_trial, n_trials, desc, kind_mode, nbits):
     _check(lib().fi_sample_faults(seed, first_trial, n_trials, C.byref(desc), kind_mode, nbits,
                                   out.ctypes.data_as(C.c_void_p)))
     return out
+
+
+def fi_activation_round(dtype, d_c, n, d_h, stream=None):
+    _check(lib().fi_activation_round(dtype, _dptr(d_c), n, _dptr(d_h), _stream(stream)))
 
 
 class Plan:
@@ -188,6 +194,10 @@ class Plan:
     def fi_gemm_inject_batch_affected(self, d_faults, n_trials, policy, d_results, stream=None):
         _check(lib().fi_gemm_inject_batch_affected(self._h, _dptr(d_faults), n_trials, policy, _dptr(d_results),
                                                    _stream(stream)))
+
+    def fi_gemm_propagate_batch(self, d_a_stack, trial_stride, n_trials, policy, d_results, d_c_out=None, stream=None):
+        _check(lib().fi_gemm_propagate_batch(self._h, _dptr(d_a_stack), trial_stride, n_trials, policy,
+                                             _dptr(d_results), _dptr(d_c_out), _stream(stream)))
 
     def fi_detect_correct(self, d_c, batch, policy, d_flags=None, d_n_flagged=None, stream=None):
         _check(lib().fi_detect_correct(self._h, _dptr(d_c), batch, policy, _dptr(d_flags),

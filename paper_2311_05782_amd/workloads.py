@@ -134,5 +134,17 @@ def gaussian(M, N, K, fmt, seed=0, scale_a=1.0, scale_b=1.0):
     return to_words(a, fmt), to_words(b, fmt)
 
 
+def two_layer_mlp(M=512, D=768, H=3072, fmt=BF16, seed=5):
+    """Inputs of a two-layer feed-forward block Y = relu(X W1) W2 with the shapes of a
+    transformer encoder's (D -> H -> D): X [M][D] ~ N(0,1), W1 [H][D] and W2 [D][H] ~ N(0, 0.02),
+    both weight matrices stored with the contraction index contiguous.  Returns the three word
+    arrays; seeded, synthetic (no trained weights)."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, D), dtype=np.float32)
+    w1 = rng.standard_normal((H, D), dtype=np.float32) * np.float32(0.02)
+    w2 = rng.standard_normal((D, H), dtype=np.float32) * np.float32(0.02)
+    return to_words(x, fmt), to_words(w1, fmt), to_words(w2, fmt)
+
+
 ALL = {"tiny128": tiny, "bert_linear": bert_linear, "resnet_conv": resnet_conv,
        "square4096": square4096, "detector_stress": detector_stress}

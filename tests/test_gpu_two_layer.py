@@ -1,0 +1,151 @@
+"""GPU parity for the two-layer workload: the hand-over kernel (ReLU + rounding to the operand
+format) and the next layer's GEMM on per-trial operands, through the C ABI, against the oracle."""
+import numpy as np
+import pytest
+
+from oracle import pyoracle as orc
+from paper_2311_05782_amd import fi, workloads as wl
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _activation_gpu(c, fmt):
+    import torch
+    d_c = torch.from_numpy(np.ascontiguousarray(c, np.float32)).cuda()
+    d_h = torch.empty(d_c.numel(), dtype=torch.int16, device="cuda")
+    fi.fi_activation_round(fmt, d_c, d_c.numel(), d_h)
+    torch.cuda.synchronize()
+    return d_h.cpu().numpy().view(np.uint16).reshape(c.shape)
+
+
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+def test_activation_round_bit_equal_including_specials_and_a_ragged_tail(fmt):
+    rng = np.random.default_rng(7)
+    special = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, -np.nan, 65504.0, 65519.9, 65520.0, 2.0 ** -24,
+                        2.0 ** -25, 1.5 * 2.0 ** -25, 2.0 ** -14, 3.3e38, 3.4e38, 1e-40, -1e-40], np.float32)
+    c = np.concatenate([special, rng.normal(0, 1, 300001), rng.normal(0, 1e4, 100000), rng.normal(0, 1e-6, 100000),
+                        rng.uniform(0, 2.0 ** -13, 50000)]).astype(np.float32)
+    assert c.size % 4 != 0
+    # every bit pattern of the upper half too: all exponents, both signs
+    hi = (np.arange(65536, dtype=np.uint32) << 16 | 0x8000).view(np.float32)
+    for x in (c, hi, c[:3]):
+        got, want = _activation_gpu(x, fmt), orc.activation_round(x, fmt)
+        nan = np.isnan(x)
+        assert np.array_equal(got[~nan], want[~nan])
+        assert np.array_equal(got[nan] & 0x7FFF, want[nan] & 0x7FFF)
+
+
+def _stack_gpu(plan, stack, policy, want_c=False):
+    import torch
+    n = stack.shape[0]
+    d = plan.desc
+    d_s = fi.words_to_device(stack)
+    d_r = fi.empty_results(n)
+    d_c = torch.empty((n, d.M, d.N), dtype=torch.float32, device="cuda") if want_c else None
+    plan.fi_gemm_propagate_batch(d_s, stack.shape[1] * stack.shape[2], n, policy, d_r, d_c)
+    recs = fi.results_to_host(d_r)
+    return (recs, d_c.cpu().numpy()) if want_c else recs
+
+
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+@pytest.mark.parametrize("shape", [(300, 200, 192, 32), (130, 65, 96, 48), (64, 64, 64, 16)])
+def test_next_layer_exact_regime_bit_equal(fmt, cfg, shape):
+    # small-integer operands in every trial: sums are exact, so outputs and every counter agree
+    M, N, K, kb = shape
+    Aw, Bw = wl.small_integers(M, N, K, fmt, seed=M + K, lim=4, step=2)
+    rng = np.random.default_rng(cfg + N)
+    n = 7
+    stack = np.stack([Aw.copy() for _ in range(n)])
+    for t in range(1, n):                                        # trial 0 keeps the golden operand
+        rows = rng.choice(M, size=int(rng.integers(1, 6)), replace=False)
+        other = wl.small_integers(M, N, K, fmt, seed=100 + t, lim=4, step=2)[0]
+        stack[t, rows] = other[rows]
+    stack[n - 1] = wl.small_integers(M, N, K, fmt, seed=999, lim=4, step=2)[0]   # every row differs
+    plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg, group=3)
+    p = orc.problem(M, N, K, kb, fmt)
+    for policy in (orc.CORRECT_NONE, orc.CORRECT_ZERO, orc.CORRECT_RECOMPUTE):
+        recs, cout = _stack_gpu(plan, stack, policy, want_c=True)
+        orecs, occ = orc.propagate(p, Aw, Bw, stack, policy, want_outputs=True)
+        assert np.array_equal(cout.view(np.uint32), occ.view(np.uint32))
+        for k in ("n_flagged", "n_bitdiff", "n_dev_pre", "n_dev_post"):
+            assert np.array_equal(recs[k], orecs[k]), (k, recs[k], orecs[k])
+        assert np.array_equal(recs["max_dev_pre"], orecs["max_dev_pre"].astype(np.float32))
+        assert np.array_equal(recs["max_dev_post"], orecs["max_dev_post"].astype(np.float32))
+        assert recs["n_bitdiff"][0] == 0 and recs["n_bitdiff"][n - 1] > M * N // 2
+        assert not recs["status"].any() and not recs["site_word_after"].any()
+    plan.destroy()
+
+
+@pytest.mark.parametrize("fmt,cfg", [(orc.FP16, 0), (orc.BF16, 1), (orc.BF16, 2)])
+def test_next_layer_on_perturbed_gaussian_operands_guard_band_rule(fmt, cfg):
+    M, N, K, kb = 260, 136, 256, 32
+    Aw, Bw = wl.gaussian(M, N, K, fmt, seed=31)
+    rng = np.random.default_rng(32)
+    n = 48
+    stack = np.stack([Aw.copy() for _ in range(n)])
+    for t in range(n):
+        for i in rng.choice(M, size=int(rng.integers(0, 4)), replace=False):
+            bit = int(rng.integers(0, 15))                       # any mantissa or exponent bit
+            stack[t, i, rng.integers(K)] ^= np.uint16(1 << bit)
+    stack[5, 7, 3] = 0x7C00 if fmt == orc.FP16 else 0x7F80       # an Inf and a NaN handed on
+    stack[6, 9, 200] = 0x7E00 if fmt == orc.FP16 else 0x7FC0
+    plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg)
+    p = orc.problem(M, N, K, kb, fmt)
+    none = np.zeros(n, fi.FAULT_DTYPE)
+    for policy in (orc.CORRECT_ZERO, orc.CORRECT_RECOMPUTE):
+        recs = _stack_gpu(plan, stack, policy)
+        orecs = orc.propagate(p, Aw, Bw, stack, policy, mode=orc.MODE_AFFECTED)
+        s = gu.compare_records(recs, orecs, none, site_tol=1.0)
+        assert not s["mismatches"], s["mismatches"][:5]
+        assert s["gpu_counts"][1] > 0 and s["gpu_counts"][2] > 0 and n - s["borderline"] >= 12
+        assert recs["n_flagged"][5] >= N and recs["n_flagged"][6] >= N     # a whole non-finite row each
+    # stride 0: every trial reads the same operand
+    import torch
+    d_r = fi.empty_results(3)
+    plan.fi_gemm_propagate_batch(fi.words_to_device(stack[5]), 0, 3, orc.CORRECT_ZERO, d_r)
+    r = fi.results_to_host(d_r)
+    assert r[0].tobytes() == r[1].tobytes() == r[2].tobytes() and r[0]["n_flagged"] >= N
+    with pytest.raises(fi.FiError):
+        plan.fi_gemm_propagate_batch(fi.words_to_device(stack), 8, 3, orc.CORRECT_ZERO, d_r)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+def test_two_layers_end_to_end_against_the_oracle_chain(fmt):
+    # layer 1: campaign with materialised corrected outputs -> ReLU + rounding -> layer 2 on the
+    # stack.  Small-integer inputs make layer 1 exact, so both sides hand on the same words.
+    import torch
+    M, D, H, P, kb = 70, 64, 144, 40, 32
+    lim = 2 if fmt == orc.FP16 else 1
+    Xw, W1w = wl.small_integers(M, H, D, fmt, seed=41, lim=lim)
+    W2w = wl.small_integers(P, P, H, fmt, seed=42, lim=lim)[0][:, :H]          # [P][H]
+    p1 = orc.problem(M, H, D, kb, fmt)
+    plan1 = gu.make_plan(Xw, W1w, kb, fmt)
+    n = 96
+    faults = fi.fi_sample_faults(9, 0, n, plan1.desc, fi.KIND_ALL_ACC, 1)
+    faults["xor_mask"][::4] = 1 << 31                            # sign flips: ReLU decides
+    recs1, c1 = gu.gpu_campaign(plan1, faults, orc.CORRECT_ZERO, want_c=True)
+    h_gpu = _activation_gpu(c1, fmt)
+    hstar_gpu = _activation_gpu(plan1.buffer_to_host(fi.BUF_C_STAR), fmt)
+    # the oracle's chain
+    of = gu.to_orc_faults(faults)
+    occ = np.stack([orc.trial(p1, Xw, W1w, of[t:t + 1], orc.CORRECT_ZERO, want_outputs=True)[2] for t in range(n)])
+    h_orc = orc.activation_round(occ, fmt)
+    hstar_orc = orc.activation_round(orc.gemm(p1, Xw, W1w), fmt)
+    assert np.array_equal(h_gpu, h_orc) and np.array_equal(hstar_gpu, hstar_orc)
+    assert (hstar_orc == 0).mean() > 0.3
+    p2 = orc.problem(M, P, H, 48, fmt)
+    plan2 = gu.make_plan(hstar_gpu, W2w, 48, fmt)
+    recs2 = _stack_gpu(plan2, h_gpu, orc.CORRECT_NONE)
+    orecs2 = orc.propagate(p2, hstar_orc, W2w, h_orc, orc.CORRECT_NONE, mode=orc.MODE_AFFECTED)
+    s = gu.compare_records(recs2, orecs2, np.zeros(n, fi.FAULT_DTYPE), site_tol=1.0)
+    assert not s["mismatches"], s["mismatches"][:5]
+    # layer-to-output masking: trials that layer 1 does not call masked but whose final output is
+    sdc1 = gu.cls_of(recs1) != 0
+    masked2 = gu.cls_of(recs2) == 0
+    assert np.array_equal(masked2, orecs2["cls"] == 0) or s["borderline"] > 0
+    assert (sdc1 & masked2).sum() > 5 and (sdc1 & ~masked2).sum() > 5
+    assert not (~sdc1 & ~masked2 & (recs1["n_bitdiff"] == 0)).any()
+    plan1.destroy(); plan2.destroy()
