@@ -77,6 +77,53 @@ def cpu_baseline(w, budget_s=15.0):
                       % (rows - 1, w.M, w.N, w.K, reps, t, rows)}
 
 
+def two_layer(torch, n_trials=256, policy=1):
+    import numpy as np
+    from paper_2311_05782_amd import fi, workloads as wl
+    M, D, H, fmt = 512, 768, 3072, wl.BF16
+    Xw, W1w, W2w = wl.two_layer_mlp(M, D, H, fmt)
+    plan1 = fi.Plan(fi.plan_desc(M, H, D, 32, fmt), fi.words_to_device(Xw), fi.words_to_device(W1w))
+    d_h = torch.empty((n_trials, M, H), dtype=torch.int16, device="cuda")
+    d_hstar = torch.empty((M, H), dtype=torch.int16, device="cuda")
+    fi.fi_activation_round(fmt, plan1.buffer_ptr(fi.BUF_C_STAR), M * H, d_hstar)
+    torch.cuda.synchronize()
+    plan2 = fi.Plan(fi.plan_desc(M, D, H, 32, fmt), d_hstar, fi.words_to_device(W2w))
+    d_c1 = torch.empty((n_trials, M, H), dtype=torch.float32, device="cuda")
+    r1, r2 = fi.empty_results(n_trials), fi.empty_results(n_trials)
+    res = {"shape": "%dx%d -> %d -> %d bf16, k-block 32" % (M, D, H, D), "trials": n_trials,
+           "policy": {0: "none", 1: "zero", 2: "recompute"}[policy]}
+    for label, mode, nbits in (("acc_1bit", fi.KIND_ALL_ACC, 1), ("product_4bit", fi.KIND_ALL_PRODUCT, 4)):
+        ff = fi.to_device(fi.fi_sample_faults(11, 0, n_trials, plan1.desc, mode, nbits))
+
+        def chain():
+            plan1.fi_gemm_inject_batch(ff, n_trials, policy, r1, d_c1)
+            fi.fi_activation_round(fmt, d_c1, n_trials * M * H, d_h)
+            plan2.fi_gemm_propagate_batch(d_h, M * H, n_trials, wl.CORRECT_NONE, r2)
+        chain()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        ev[0].record(); plan1.fi_gemm_inject_batch(ff, n_trials, policy, r1, d_c1)
+        ev[1].record(); fi.fi_activation_round(fmt, d_c1, n_trials * M * H, d_h)
+        ev[2].record(); plan2.fi_gemm_propagate_batch(d_h, M * H, n_trials, wl.CORRECT_NONE, r2)
+        ev[3].record(); torch.cuda.synchronize()
+        ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(3)]
+        a, b = fi.results_to_host(r1), fi.results_to_host(r2)
+        c1 = np.where(a["n_flagged"] > 0, 2, np.where(a["n_dev_pre"] > 0, 1, 0))
+        out_masked = b["n_dev_pre"] == 0
+        res[label] = {
+            "layer1_masked_sdc_detected": [int((c1 == k).sum()) for k in range(3)],
+            "output_masked": int(out_masked.sum()),
+            "layer1_sdc_masked_at_output": int(((c1 == 1) & out_masked).sum()),
+            "layer1_detected_masked_at_output_after_correction": int(((c1 == 2) & out_masked).sum()),
+            "ms_layer1_activation_layer2": [round(x, 3) for x in ms],
+            "chain_trials_per_s": round(n_trials / (sum(ms) * 1e-3), 1),
+            "layer2_tflops": round(2.0 * M * D * H * n_trials / (ms[2] * 1e-3) / 1e12, 1),
+            "activation_GBps": round(n_trials * M * H * 6 / (ms[1] * 1e-3) / 1e9, 1),
+        }
+    plan1.destroy(); plan2.destroy()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -270,6 +317,11 @@ def main():
                     pb.destroy()
                 others[name]["masked_sdc_detected_by_detector"] = cov
         out["other_campaigns"] = others
+    # Two layers, Y = relu(X W1) W2 with a transformer feed-forward block's shapes: a fault in the
+    # first GEMM, detector + corrector, ReLU and rounding to the operand format, then the second GEMM
+    # of every trial in full; how many of the faults layer 1 does not mask still show at the output.
+    if extras or args.campaigns:
+        out["two_layer"] = two_layer(torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
         out["cpu_baseline"]["value"] = float("%.4g" % out["cpu_baseline"]["value"])
