@@ -196,7 +196,7 @@ fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults,
  * activations): d_h[e] = RNE_fmt(relu(d_c[e])) for n elements, as 16-bit words of `dtype`.
  * relu keeps a NaN (handed on as the format's quiet NaN) and maps negatives and -0 to +0;
  * values beyond the format's range round to +Inf.  d_c (device, 16-byte aligned) is not
- * modified; d_h (device, 8-byte aligned) is overwritten.  No plan is needed.
+ * modified; d_h (device, 16-byte aligned) is overwritten.  No plan is needed.
  * Errors: UNSUPPORTED (dtype, alignment), INVALID_ARG (NULLs, n == 0). */
 fi_status fi_activation_round(uint32_t dtype, const float* d_c, uint64_t n, uint16_t* d_h, void* stream);
 

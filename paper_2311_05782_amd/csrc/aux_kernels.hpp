@@ -196,27 +196,32 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
 
 // Hand-over between two layers: h = RNE_fmt(relu(c)).  relu keeps a NaN and maps negatives
 // and -0 to +0; the rounding is the integer one of round16 (no dependence on the wave's float
-// modes).  HBM bound: 4 bytes read, 2 written per element; four elements per lane and step.
+// modes).  HBM bound: 4 bytes read, 2 written per element; eight elements per lane and step
+// (two 16-byte loads in flight, one 16-byte store).
 template <int DT>
 __global__ void __launch_bounds__(256) activation_round_kernel(const float* __restrict__ c, size_t n,
                                                               uint16_t* __restrict__ h) {
-  const size_t n4 = n / 4;
+  const size_t n8 = n / 8;
   const size_t step = (size_t)gridDim.x * 256;
   const size_t first = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (size_t i = first; i < n4; i += step) {
-    const f32x4_t v = reinterpret_cast<const f32x4_t*>(c)[i];
-    uint32_t w[4];
+  for (size_t i = first; i < n8; i += step) {
+    const f32x4_t v0 = reinterpret_cast<const f32x4_t*>(c)[2 * i];
+    const f32x4_t v1 = reinterpret_cast<const f32x4_t*>(c)[2 * i + 1];
+    uint32_t w[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float x = v[e];
+      const float x = v0[e], y = v1[e];
       w[e] = round16<DT>((x > 0.0f || x != x) ? x : 0.0f);
+      w[4 + e] = round16<DT>((y > 0.0f || y != y) ? y : 0.0f);
     }
-    uint2 o;
-    o.x = w[0] | (w[1] << 16);
-    o.y = w[2] | (w[3] << 16);
-    reinterpret_cast<uint2*>(h)[i] = o;
+    u32x4_t o;
+    o[0] = w[0] | (w[1] << 16);
+    o[1] = w[2] | (w[3] << 16);
+    o[2] = w[4] | (w[5] << 16);
+    o[3] = w[6] | (w[7] << 16);
+    reinterpret_cast<u32x4_t*>(h)[i] = o;
   }
-  for (size_t i = n4 * 4 + first; i < n; i += step) {
+  for (size_t i = n8 * 8 + first; i < n; i += step) {
     const float x = c[i];
     h[i] = (uint16_t)round16<DT>((x > 0.0f || x != x) ? x : 0.0f);
   }

@@ -522,9 +522,9 @@ fi_status fi_activation_round(uint32_t dtype, const float* d_c, uint64_t n, uint
     return fail(FI_UNSUPPORTED, "dtype %u: only FP16 (0) and BF16 (1)", dtype);
   if (!d_c || !d_h) return fail(FI_INVALID_ARG, "d_c and d_h must be non-NULL");
   if (n == 0) return fail(FI_INVALID_ARG, "n is 0");
-  if ((reinterpret_cast<uintptr_t>(d_c) & 15u) || (reinterpret_cast<uintptr_t>(d_h) & 7u))
-    return fail(FI_UNSUPPORTED, "d_c must be 16-byte and d_h 8-byte aligned");
-  uint64_t blocks = (n / 4 + 255) / 256;
+  if ((reinterpret_cast<uintptr_t>(d_c) & 15u) || (reinterpret_cast<uintptr_t>(d_h) & 15u))
+    return fail(FI_UNSUPPORTED, "d_c and d_h must be 16-byte aligned");
+  uint64_t blocks = (n / 8 + 255) / 256;
   if (blocks > 16384) blocks = 16384;
   if (blocks == 0) blocks = 1;
   if (dtype == FI_BF16)
@@ -560,7 +560,9 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
   a.A = static_cast<const uint16_t*>(d_a_stack);
   a.a_trial_stride = trial_stride;
   a.n_trials = (int)n_trials;
-  a.group = plan->group;
+  // Trials share B but not A: keep a trial's tiles close together in the dispatch order (its A
+  // panels are then re-read from the XCD's L2, not from HBM) and only a few trials per B tile.
+  a.group = plan->group < 3 ? plan->group : 3;
   a.results = d_results;
   a.c_out = d_c_out;
   a.policy = (int)policy;
