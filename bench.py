@@ -27,8 +27,8 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "ae8af2113bb05e25fd7ade087c8c0f6ca5fc3a56b4e1dbbd0fe3cafe498f2e98",
-    "fetch_bytes": 2.18088e6 * 2.0 * 1024,
+    "sources_sha256": "49bb018189f4187d8ea29ea262988837c00b031e8de796d3e57946cba39e096d",
+    "fetch_bytes": 2.18094e6 * 2.0 * 1024,
     "write_bytes": 151.312 * 1.0 * 1024,
 }
 
