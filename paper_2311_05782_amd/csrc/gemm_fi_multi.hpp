@@ -395,11 +395,14 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       constexpr int r = rr;
       if (r < n_act && n_flag[r] != 0 && lane == 0) atomicAdd(&p.results[trial[r]].n_flagged, n_flag[r]);
     });
-    // Deviation counters of the trials whose fault lies in this tile (rare).
-    if (affected == 0) return;
+    // Deviation counters of the trials whose fault can reach an element this wave holds (rare):
+    // the wave owning the element, or the waves holding its output row (A) / column (B).
+    uint32_t owned = 0;
+    static_for<R>([&](auto rr) { owned |= hook_step[rr] >= 0 ? 1u << rr : 0u; });
+    if (owned == 0) return;
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
-      if ((affected >> r) & 1u) {
+      if ((owned >> r) & 1u) {
         fi_trial_result* res = p.results + trial[r];
         const int site_row = (int)desc_field(r, 1), site_col = (int)desc_field(r, 2);
         // what the fault can reach: the element, or (OPS) its output row (A) / column (B)
@@ -408,39 +411,61 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         const bool need_col = !op || desc_field(r, 5) == FI_SITE_B;
         uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
         float mx_pre = 0.0f, mx_post = 0.0f;
-        static_for<TM * TN>([&](auto tt) {
-          constexpr int i = tt / TN, j = tt % TN;
-          const f32x16 T = thresholds(tt);
-          const f32x16 t = acc[r][i][j];
-          const int col = col_base + 32 * j;
+        auto account = [&](float c, float Tv, int row, int col) __attribute__((always_inline)) {
+          const size_t idx = (size_t)row * p.N + col;
+          const float cs = p.c_star[idx];
+          const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
+          const bool flag = !(fabsf(c) <= Tv);
+          float cc = c;
+          if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+          if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
+          const float dpre = finite_or_inf(fabsf(c - cs));
+          const float dpost = finite_or_inf(fabsf(cc - cs));
+          const bool changed = __float_as_uint(c) != __float_as_uint(cs);
+          n_bit += changed ? 1u : 0u;
+          n_pre += !(dpre <= tau) ? 1u : 0u;
+          n_post += !(dpost <= tau) ? 1u : 0u;
+          mx_pre = fmaxf(mx_pre, dpre);
+          mx_post = fmaxf(mx_post, dpost);
+          const float band = fmaxf(2.0f * tau, Tv * 0.015625f);
+          const float mag = fabsf(c);
+          n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - Tv) <= band) ? 1u : 0u;
+          n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
+        };
+        if (need_row) {
+          // One row: it lives in one 32-row tile, one register index and one lane half
+          // (accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4).
+          const int wr = site_row - m0 - wm * WTM;            // 0 .. WTM-1: this wave holds the row
+          const int ri = wr & 31;
+          const int sel_v = 4 * (ri >> 3) + (ri & 3), sel_hi = (ri >> 2) & 1;
+          static_for<TM * TN>([&](auto tt) {
+            constexpr int i = tt / TN, j = tt % TN;
+            if (i == (wr >> 5)) {
+              const f32x16 T = thresholds(tt);
+              const f32x16 t = acc[r][i][j];
+              float c = t[0], Tv = T[0];
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-            if ((!need_row || row == site_row) && (!need_col || col == site_col) && row < p.M && col < p.N) {
-              const float c = t[v];
-              const size_t idx = (size_t)row * p.N + col;
-              const float cs = p.c_star[idx];
-              const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
-              const float Tv = T[v];
-              const bool flag = !(fabsf(c) <= Tv);
-              float cc = c;
-              if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
-              if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
-              const float dpre = finite_or_inf(fabsf(c - cs));
-              const float dpost = finite_or_inf(fabsf(cc - cs));
-              const bool changed = __float_as_uint(c) != __float_as_uint(cs);
-              n_bit += changed ? 1u : 0u;
-              n_pre += !(dpre <= tau) ? 1u : 0u;
-              n_post += !(dpost <= tau) ? 1u : 0u;
-              mx_pre = fmaxf(mx_pre, dpre);
-              mx_post = fmaxf(mx_post, dpost);
-              const float band = fmaxf(2.0f * tau, Tv * 0.015625f);
-              const float mag = fabsf(c);
-              n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - Tv) <= band) ? 1u : 0u;
-              n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
+              for (int v = 1; v < 16; ++v) {
+                c = (v == sel_v) ? t[v] : c;
+                Tv = (v == sel_v) ? T[v] : Tv;
+              }
+              const int col = col_base + 32 * j;
+              if (lhi == sel_hi && (!need_col || col == site_col) && col < p.N) account(c, Tv, site_row, col);
             }
-          }
-        });
+          });
+        } else {
+          static_for<TM * TN>([&](auto tt) {
+            constexpr int i = tt / TN, j = tt % TN;
+            const f32x16 T = thresholds(tt);
+            const f32x16 t = acc[r][i][j];
+            const int col = col_base + 32 * j;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+              if (col == site_col && row < p.M) account(t[v], T[v], row, col);
+            }
+          });
+        }
         uint32_t sum;
         sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&res->n_bitdiff, sum);
         sum = wave_sum(n_pre);  if (lane == 0 && sum) atomicAdd(&res->n_dev_pre, sum);
