@@ -156,7 +156,6 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   uint32_t desc_cur, desc_nxt = 0;                       // lane-distributed descriptor words
   int n_act = 0;                                         // trials in this group
   int trial[R], hook_step[R];                            // hook_step: -1 unless this wave owns the site
-  uint32_t affected = 0;                                 // bit r: this tile can differ from C*
   int next_hook = NO_HOOK;                               // earliest pending accumulator event of this wave
   uint32_t is_operand = 0;                               // bit r: trial r's event is an operand patch (OPS)
   int next_pre = NO_HOOK;                                // earliest pending operand patch of this wave (OPS)
@@ -166,7 +165,6 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   };
   auto decode = [&]() {
     n_act = min(R, n_fast - cur.grp * R);
-    affected = 0;
     next_hook = NO_HOOK;
     is_operand = 0;
     next_pre = NO_HOOK;
@@ -183,7 +181,6 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
           const bool isA = desc_field(r, 5) == FI_SITE_A;
           const int l = isA ? li : lj;
           if (l >= 0 && l < (isA ? BM : BN)) {
-            affected |= 1u << r;
             const int wl = isA ? l - wm * WTM : l - wn * WTN;
             if (wl >= 0 && wl < (isA ? WTM : WTN)) {
               hook_step[r] = hs;
@@ -192,7 +189,6 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
             }
           }
         } else if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
-          affected |= 1u << r;
           const int wi = li - wm * WTM, wj = lj - wn * WTN;
           if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
             hook_step[r] = hs;

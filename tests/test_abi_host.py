@@ -84,6 +84,13 @@ def test_argument_errors_need_no_device():
     assert _status(lambda: fi._check(L.fi_gemm_inject_batch(None, A, 1, 0, B, None, None)))[0] == fi.INVALID_ARG
     assert _status(lambda: fi._check(L.fi_detect_correct(None, A, 1, 0, None, None, None)))[0] == fi.INVALID_ARG
     assert _status(lambda: fi._check(L.fi_classify(None, A, 1, None, B, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_gemm_propagate_batch(None, A, 0, 1, 0, B, None, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_gemm_inject_batch_affected(None, A, 1, 0, B, None)))[0] == fi.INVALID_ARG
+    # the hand-over kernel's arguments
+    assert _status(lambda: fi._check(L.fi_activation_round(2, A, 16, B, None)))[0] == fi.UNSUPPORTED
+    assert _status(lambda: fi._check(L.fi_activation_round(fi.BF16, None, 16, B, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_activation_round(fi.BF16, A, 0, B, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_activation_round(fi.BF16, A, 16, C.c_void_p(0x2008), None)))[0] == fi.UNSUPPORTED
     # sampler argument checks
     assert _status(lambda: fi.fi_sample_faults(0, 0, 4, good, 9, 1))[0] == fi.INVALID_ARG
     assert _status(lambda: fi.fi_sample_faults(0, 0, 4, good, 0, 0))[0] == fi.INVALID_ARG

@@ -149,3 +149,51 @@ def test_two_layers_end_to_end_against_the_oracle_chain(fmt):
     assert (sdc1 & masked2).sum() > 5 and (sdc1 & ~masked2).sum() > 5
     assert not (~sdc1 & ~masked2 & (recs1["n_bitdiff"] == 0)).any()
     plan1.destroy(); plan2.destroy()
+
+
+def test_the_chain_replays_correctly_from_a_hip_graph():
+    # The three calls clear their records with kernels and allocate nothing, so the whole chain
+    # can be captured; replays alternate with eager work and are compared with the eager result.
+    import torch
+    fmt, kb = orc.BF16, 32
+    Xw, W1w, W2w = wl.two_layer_mlp(M=128, D=64, H=192, fmt=fmt, seed=3)
+    M, D, H = 128, 64, 192
+    plan1 = gu.make_plan(Xw, W1w, kb, fmt)
+    d_hstar = torch.empty((M, H), dtype=torch.int16, device="cuda")
+    fi.fi_activation_round(fmt, plan1.buffer_ptr(fi.BUF_C_STAR), M * H, d_hstar)
+    torch.cuda.synchronize()
+    plan2 = fi.Plan(fi.plan_desc(M, D, H, kb, fmt), d_hstar, fi.words_to_device(W2w))
+    n = 40
+    lists = [fi.fi_sample_faults(s, 0, n, plan1.desc, fi.KIND_MIX_ACC_A, 2) for s in (1, 2, 3)]
+    d_f = fi.to_device(lists[0])
+    d_c1 = torch.empty((n, M, H), dtype=torch.float32, device="cuda")
+    d_h = torch.empty((n, M, H), dtype=torch.int16, device="cuda")
+    r1, r2 = fi.empty_results(n), fi.empty_results(n)
+
+    def chain(stream=None):
+        plan1.fi_gemm_inject_batch(d_f, n, orc.CORRECT_ZERO, r1, d_c1, stream=stream)
+        fi.fi_activation_round(fmt, d_c1, n * M * H, d_h, stream=stream)
+        plan2.fi_gemm_propagate_batch(d_h, M * H, n, orc.CORRECT_NONE, r2, stream=stream)
+
+    eager = []
+    for f in lists:
+        d_f.copy_(fi.to_device(f))
+        chain()
+        eager.append((fi.results_to_host(r1).tobytes(), fi.results_to_host(r2).tobytes()))
+    assert eager[0] != eager[1]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    d_f.copy_(fi.to_device(lists[0]))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            chain(stream=torch.cuda.current_stream().cuda_stream)
+    for rep in range(2):
+        for k, f in enumerate(lists):
+            d_f.copy_(fi.to_device(f))
+            r1.zero_(); r2.fill_(0xFF)                              # eager work between replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert (fi.results_to_host(r1).tobytes(), fi.results_to_host(r2).tobytes()) == eager[k], (rep, k)
+    plan1.destroy(); plan2.destroy()
