@@ -522,20 +522,38 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       constexpr int SC = decltype(stage_c)::value;
       if constexpr (SC >= 0) stage = SC;
       const bool more = !LAST || has_next;                // a tile follows in the other stage
+      // The pending events are looked up once per k-tile, before the tile prefetch is issued
+      // (a look-up that has to wait for memory then waits for nothing else), and again only
+      // after an event has fired.
+      int np = NO_HOOK, nh = NO_HOOK;
+      if constexpr (EV) {
+        np = OPS ? next_pre : NO_HOOK;
+        nh = next_hook;
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // nothing else is in flight at this point
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if constexpr (!LAST) issue_tile(cur, kt + 1, stage ^ 1);
       else if (has_next) issue_tile(nxt, 0, stage ^ 1);
       const uint8_t* s = smem + stage * STAGE;
       const uint8_t* s_other = smem + (stage ^ 1) * STAGE;
       auto step = [&](const Frags& f, int g, auto&& mid) __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
-        if (OPS && g == next_pre) {
+        if (OPS && g == np) {
           mid();
           mma_patched(f, g);
+          np = next_pre;
+          __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) here, on the rare path, not at the join
         } else {
           mma_step_mid(f, mid);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (EV) hooks(g);
+        if constexpr (EV) {
+          if (g == nh) {
+            hooks(g);
+            nh = next_hook;
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+          }
+        }
       };
       step(f0, 4 * kt, [&]() { read_frags(f1, s, 1); });
       step(f1, 4 * kt + 1, [&]() { read_frags(f0, s, 2); });
