@@ -244,12 +244,25 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
                                                                const uint16_t* __restrict__ A,
                                                                const uint16_t* __restrict__ B, uint32_t lda,
                                                                uint32_t ldb, int product_check_mode,
+                                                               uint32_t bm, uint32_t bn,
                                                                uint32_t* __restrict__ perm,
                                                                uint32_t* __restrict__ counts,
                                                                uint32_t* __restrict__ desc,
                                                                fi_trial_result* __restrict__ results) {
   __shared__ uint32_t offs[1024];
   __shared__ uint32_t total_fast;
+  // Operand faults are ordered by the tile row (A) or tile column (B) their fault reaches, so
+  // that the R trials of a group mostly share it: the other tiles' work items then carry no
+  // event at all.  1024 buckets; more tile rows + columns than that are merged pairwise.
+  __shared__ uint32_t bucket[1024];
+  const uint32_t tiles_m = (M + bm - 1) / bm, n_keys = tiles_m + (N + bn - 1) / bn;
+  uint32_t key_shift = 0;
+  while ((n_keys >> key_shift) > 1024u) ++key_shift;
+  auto key_of = [&](const fi_fault& x) -> uint32_t {
+    return (x.kind == FI_SITE_A ? x.row / bm : tiles_m + x.col / bn) >> key_shift;
+  };
+  bucket[threadIdx.x] = 0;
+  __syncthreads();
   const uint32_t chunk = (n + 1023) / 1024;
   const uint32_t lo = min(threadIdx.x * chunk, n), hi = min(lo + chunk, n);
   // 0: operand fault (other kernel); 1: runs fault-free; 2: accumulator flip; 3: bad site;
@@ -262,9 +275,28 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
     return x.kind == FI_SITE_NONE ? 1 : 3;
   };
   uint32_t c = 0;
-  for (uint32_t t = lo; t < hi; ++t) c += kind_of(f[t]) != 0 ? 1u : 0u;
+  for (uint32_t t = lo; t < hi; ++t) {
+    const fi_fault x = f[t];
+    if (kind_of(x) != 0) c += 1u;
+    else atomicAdd(&bucket[key_of(x)], 1u);
+  }
   offs[threadIdx.x] = c;
   __syncthreads();
+  // exclusive prefix sum of the buckets (Hillis-Steele, one bucket per thread)
+  {
+    const uint32_t own = bucket[threadIdx.x];
+    uint32_t incl = own;
+    for (int d = 1; d < 1024; d <<= 1) {
+      __syncthreads();
+      const uint32_t other = threadIdx.x >= (uint32_t)d ? bucket[threadIdx.x - d] : 0u;
+      __syncthreads();
+      incl += other;
+      bucket[threadIdx.x] = incl;
+    }
+    __syncthreads();
+    bucket[threadIdx.x] = incl - own;
+    __syncthreads();
+  }
   if (threadIdx.x == 0) {            // 1024 additions: negligible next to the batch itself
     uint32_t run = 0;
     for (int i = 0; i < 1024; ++i) { uint32_t v = offs[i]; offs[i] = run; run += v; }
@@ -275,7 +307,6 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
   __syncthreads();
   uint32_t pf = offs[threadIdx.x];                       // fast trials before my chunk
   const uint32_t n_fast = total_fast;
-  uint32_t ps = n_fast + (lo - pf);                      // slow trials before my chunk, after the front
   for (uint32_t t = lo; t < hi; ++t) {
     const fi_fault x = f[t];
     const int k = kind_of(x);
@@ -283,12 +314,13 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
       // operand fault: second part of the batch; its descriptors start at the next multiple of 8
       const bool isA = x.kind == FI_SITE_A;
       const uint32_t kk = isA ? x.col : x.row, m16 = x.xor_mask & 0xFFFFu;
-      uint32_t* d = desc + ((size_t)((n_fast + 7u) & ~7u) + (ps - n_fast)) * 6;
+      const uint32_t pos = atomicAdd(&bucket[key_of(x)], 1u);      // order inside a bucket is arbitrary
+      uint32_t* d = desc + ((size_t)((n_fast + 7u) & ~7u) + pos) * 6;
       d[0] = t; d[1] = x.row; d[2] = x.col; d[3] = (kk / 16) | 0x20000000u; d[4] = m16; d[5] = x.kind;
       const uint32_t w = isA ? A[(size_t)x.row * lda + x.col] : B[(size_t)x.col * ldb + x.row];
       results[t].site_word_before = w;
       results[t].site_word_after = w ^ m16;
-      perm[ps++] = t;
+      perm[n_fast + pos] = t;
       continue;
     }
     uint32_t* d = desc + (size_t)pf * 6;

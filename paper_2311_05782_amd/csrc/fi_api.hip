@@ -462,12 +462,12 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
     if (plan->d.dtype == FI_BF16)
       hipLaunchKernelGGL(fi::partition_trials_kernel<FI_BF16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
                          plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
-                         plan->perm,
+                         (uint32_t)kMulti[plan->mcfg].bm, (uint32_t)kMulti[plan->mcfg].bn, plan->perm,
                          counts, plan->desc, d_results);
     else
       hipLaunchKernelGGL(fi::partition_trials_kernel<FI_FP16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
                          plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
-                         plan->perm,
+                         (uint32_t)kMulti[plan->mcfg].bm, (uint32_t)kMulti[plan->mcfg].bn, plan->perm,
                          counts, plan->desc, d_results);
     FI_HIP(hipGetLastError());
     a.perm = plan->perm;

@@ -538,7 +538,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       const uint8_t* s_other = smem + (stage ^ 1) * STAGE;
       auto step = [&](const Frags& f, int g, auto&& mid) __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
-        if (OPS && g == np) {
+        if (OPS && EV && g == np) {
           mid();
           mma_patched(f, g);
           np = next_pre;
@@ -585,7 +585,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         k_tile(with_events, std::true_type{}, dyn{}, nkt - 1);
       }
     };
-    if (!OPS && next_hook == NO_HOOK) k_loop(std::false_type{});
+    if (next_hook == NO_HOOK && (!OPS || next_pre == NO_HOOK)) k_loop(std::false_type{});
     else k_loop(std::true_type{});
 
     if constexpr (!EARLY_T) fetch_threshold_inputs();
