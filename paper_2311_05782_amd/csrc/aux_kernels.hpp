@@ -229,7 +229,8 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
 
 // Splits a batch: trials the multi-trial GEMM kernel can take (no fault, an accumulator flip or
 // a product-term fault; out-of-range sites count as "no fault" and get status 1 in their zeroed
-// record) go to the front of perm in list order, all others (operand faults) behind them.
+// record) go to the front of perm in list order, all others (operand faults) behind them,
+// ordered by the tile row (A) or tile column (B) of a bm x bn tiling that their fault reaches.
 // counts = {front, back}.  For front position q, desc[6q .. 6q+5] = {trial, row, col, event,
 // w0, w1}: event = -1 for no fault, else the 16-wide MFMA step after which the accumulator
 // changes - (s+1)*kb/16 - 1 for a flip with w0 = the XOR mask; k/16, with bit 30 set, for a

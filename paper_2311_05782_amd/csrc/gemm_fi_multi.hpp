@@ -506,9 +506,6 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
           f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     });
 
-    // The k-loop exists twice: waves with no accumulator event in this item (nearly all) run a
-    // copy free of event checks; the others run the copy with the hooks.  Both execute the same
-    // barriers, so waves of one workgroup may take different copies.
     // One k-tile.  Every fragment read is issued inside the MFMA burst of the step before the
     // one that uses it (after the first few MFMAs), so a wave never waits for a read it has just
     // issued; the barrier sits before the last step, whose fragments the wave already holds, and
@@ -565,9 +562,10 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
       step(f1, 4 * kt + 3, [&]() { if (more) read_frags(f0, s_other, 0); });
       stage ^= 1;
     };
-    // The k-loop exists twice: waves with no accumulator event in this item (nearly all) run a
-    // copy free of event checks; the others run the copy with the hooks.  Both execute the same
-    // barriers, so waves of one workgroup may take different copies.
+    // The k-loop exists twice: waves with no event in this item - no accumulator fault and no
+    // operand patch of their own (nearly all) - run a copy free of event checks; the others run
+    // the copy with the hooks.  Both execute the same barriers, so waves of one workgroup may
+    // take different copies.
     auto k_loop = [&](auto with_events) __attribute__((always_inline)) {
       using dyn = std::integral_constant<int, -1>;
       using st0 = std::integral_constant<int, 0>;
