@@ -19,10 +19,18 @@
  *     HIP device; h_ is host memory.  The library never allocates memory it
  *     hands to the caller and never frees caller memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
- *     device work is enqueued on it.  fi_plan_create synchronises that stream
- *     once (it has to read back an operand-validity word); the other calls do
- *     not synchronise, so device-side failures surface at the caller's next
+ *     device work is enqueued on it.  Three calls allocate device memory and
+ *     synchronise, and so must stay outside stream capture: fi_plan_create (it
+ *     reads back an operand-validity word), fi_plan_reserve, and
+ *     fi_gemm_inject_batch on the FIRST batch a plan sees on a given stream or
+ *     on a batch larger than any before on that stream (it sizes that
+ *     stream's trial-order scratch; fi_plan_reserve does this ahead of time).
+ *     fi_plan_destroy waits for the device.  No other call allocates or
+ *     synchronises, so device-side failures surface at the caller's next
  *     synchronising call.
+ *   - A plan may have batches in flight on several streams at once (each
+ *     stream has its own scratch; at most 64 streams per plan).  Calls on one
+ *     plan are not thread-safe: serialise them on the host.
  *   - Every function returns an fi_status; on failure output parameters are
  *     untouched and fi_last_error() describes the problem.  Nothing throws or
  *     aborts across this boundary.
@@ -106,6 +114,10 @@ typedef struct {
  * transposed once into plan-owned memory at plan creation.
  * Requirements: k_block a multiple of 16, K a multiple of k_block, K <= 65536;
  * dA/dB 16-byte aligned and lda/ldb multiples of 8 elements. */
+/* gamma: slack factor on the detector's bound, >= 1.  0 selects the default,
+ * 1 + 2^-11 * ceil(K / 4096): a K-term FP32 accumulation can exceed the exact sum of
+ * magnitudes by (1 + 2^-24)^(K-1), and the three roundings of the bound itself lose three more
+ * ulps; the default is about twice that, so a fault-free element is never flagged. */
 typedef struct {
   uint32_t M, N, K, k_block;
   uint32_t dtype;        /* FI_FP16 / FI_BF16 */
@@ -151,6 +163,12 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
  * either (every shape accumulates each element in the same order); `stream` is unused. */
 fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, void* stream);
 
+/* Sizes the trial-order scratch `stream` uses for this plan's batches to max_trials, so that
+ * fi_gemm_inject_batch with n_trials <= max_trials on that stream neither allocates nor
+ * synchronises (a caller about to capture the calls into a HIP graph wants this).
+ * Errors: INVALID_ARG (max_trials == 0), OOM, STATE (more than 64 streams). */
+fi_status fi_plan_reserve(fi_plan* plan, uint32_t max_trials, void* stream);
+
 /* Exponent-only detection / correction applied to the erroneous product re_err of every
  * PRODUCT fault before the write-back (Sec. VI-A; correction only where detection fires,
  * Sec. VI-B).  It reads the exponent field of the 16-bit product word:
@@ -183,11 +201,14 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
 /* The same campaign restricted to what a fault can reach: for each trial only the output
  * tiles holding the faulted element (ACC, PRODUCT), its output row (A) or its output column
  * (B) are computed; every other element of a trial equals the fault-free result bit for bit
- * and, for gamma at or above the default, cannot be flagged.  d_results[t] then equals the
- * record fi_gemm_inject_batch writes.  This is a different product - trials per second, not
+ * and must not be flagged: the plan counts, when it is created, the elements of the fault-free
+ * result its own detector flags (none under FI_BOUND_ROWCOL / FI_BOUND_GLOBAL with gamma at or
+ * above the default; possible under FI_BOUND_EXPONENT, where any |C*_ij| >= 2^17 is flagged, or
+ * with a smaller gamma), and this call returns FI_UNSUPPORTED if there are any.  d_results[t] then
+ * equals the record fi_gemm_inject_batch writes.  This is a different product - trials per second, not
  * matrix-core throughput: a trial costs 2*K (element) to 2*N*K or 2*M*K (row, column) useful
  * flops instead of 2*M*N*K - and its rate is never reported against the MFMA roof.
- * Errors as fi_gemm_inject_batch. */
+ * Errors as fi_gemm_inject_batch, and UNSUPPORTED as described above. */
 fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
                                         uint32_t policy, fi_trial_result* d_results, void* stream);
 
@@ -232,7 +253,7 @@ fi_status fi_detect_correct(fi_plan* plan, float* d_c, uint32_t batch, uint32_t 
 fi_status fi_classify(fi_plan* plan, const fi_trial_result* d_results, uint32_t n_trials,
                       uint8_t* d_class, uint64_t* d_counts, void* stream);
 
-/* Log2-binned histogram of a per-trial deviation (Sec. V-B "numeric deviation analysis", Fig. 7;
+/* Log2-binned histogram of a per-trial deviation (Sec. V-B, the analysis of how far results move; Fig. 7;
  * Fig. 9), from which the empirical CDF follows by a running sum.
  *   FI_HIST_SITE     |re'_sum - re_sum|: the change of the destination register, in binary32 from
  *                    the two site words (accumulator and product-term faults only);
@@ -257,6 +278,11 @@ fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trial
 
 /* Thread-local description of the last failure on this thread. */
 const char* fi_last_error(void);
+
+/* Hex SHA-256 of the kernel and ABI sources this binary was compiled from ("unknown" for a
+ * build that did not record it), so that a loader can refuse a binary older than the sources
+ * beside it.  A static string; never NULL.  Needs no device. */
+const char* fi_build_info(void);
 
 #ifdef __cplusplus
 }

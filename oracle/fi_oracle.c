@@ -337,6 +337,18 @@ int orc_rowcol_absmax(const orc_problem* p, const uint16_t* A, const uint16_t* B
   return bad ? 2 : 0;
 }
 
+/* Default slack factor.  With exact products (two 16-bit operands multiply exactly in
+ * binary32) the K - 1 rounded additions of any summation order inflate a sum of magnitudes by
+ * at most (1 + 2^-24)^(K-1), about 1 + K * 2^-24, and the three roundings of the threshold
+ * itself lose at most three ulps.  gamma = 1 + 2^-11 * ceil(K / 4096) is at least 1 + 2 K 2^-24:
+ * twice what is needed, so a fault-free element is never flagged (for K <= 4096 this is the
+ * constant 1 + 2^-11). */
+float orc_default_gamma(int K) {
+  int units = (K + 4095) / 4096;
+  if (units < 1) units = 1;
+  return 1.0f + (float)units / 2048.0f;
+}
+
 float orc_threshold(int K, float ra, float cb, float gamma) {
   float t = (float)K * ra;   /* one rounding each */
   t = t * cb;

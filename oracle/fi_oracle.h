@@ -128,6 +128,8 @@ int orc_gemm(const orc_problem* p, const uint16_t* A, const uint16_t* B,
 int orc_rowcol_absmax(const orc_problem* p, const uint16_t* A, const uint16_t* B,
                       float* ra, float* cb);
 
+/* O4 default slack factor: 1 + 2^-11 * ceil(K / 4096). */
+float orc_default_gamma(int K);
 /* O4 threshold: fl32(fl32(fl32(K*ra)*cb)*gamma). */
 float orc_threshold(int K, float ra, float cb, float gamma);
 

@@ -77,6 +77,8 @@ def lib():
         L.orc_gemm.argtypes = [PP, u16p, u16p, f32p, f64p, f64p]
         L.orc_rowcol_absmax.restype = C.c_int
         L.orc_rowcol_absmax.argtypes = [PP, u16p, u16p, f32p, f32p]
+        L.orc_default_gamma.restype = C.c_float
+        L.orc_default_gamma.argtypes = [C.c_int]
         L.orc_threshold.restype = C.c_float
         L.orc_threshold.argtypes = [C.c_int, C.c_float, C.c_float, C.c_float]
         L.orc_detect_correct.restype = C.c_int
@@ -113,8 +115,14 @@ def _u16(a):
     return a
 
 
-def problem(M, N, K, kb, fmt, b_layout=0, bound_mode=BOUND_ROWCOL, gamma=DEFAULT_GAMMA,
+def default_gamma(K):
+    return float(lib().orc_default_gamma(int(K)))
+
+
+def problem(M, N, K, kb, fmt, b_layout=0, bound_mode=BOUND_ROWCOL, gamma=None,
             lda=None, ldb=None, product_check=0):
+    if gamma is None:
+        gamma = default_gamma(K)
     if lda is None:
         lda = K
     if ldb is None:

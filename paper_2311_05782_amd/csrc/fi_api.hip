@@ -6,12 +6,16 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <unordered_set>
+#include <vector>
 
 #include "aux_kernels.hpp"
 #include "fi.h"
 #include "gemm_fi.hpp"
 #include "gemm_fi_multi.hpp"
+#include "tile_cfg.hpp"
 
 namespace {
 
@@ -33,96 +37,69 @@ fi_status fail(fi_status code, const char* fmt, ...) {
                   hipGetErrorString(e_));                                                   \
   } while (0)
 
-constexpr uint32_t PLAN_MAGIC = 0x46495031u;   // "FIP1"
 constexpr int PAD = 512;                       // row/column vectors are zero padded to this multiple
 
-// Tile configurations: workgroup tile BM x BN computed by WM x WN waves.
-struct TileCfg { int bm, bn, wm, wn; };
-constexpr TileCfg kCfg[] = {
-    {256, 256, 4, 2},   // 8 waves, each 64 x 128: large square-ish problems
-    {128, 128, 2, 2},   // 4 waves, each 64 x 64
-    {256, 64, 4, 1},    // 4 waves, each 64 x 64: narrow outputs (N <= 64)
-};
-constexpr int kNumCfg = sizeof(kCfg) / sizeof(kCfg[0]);
-
-// Multi-trial configurations: R trials share one staged BM x BN tile (see gemm_fi_multi.hpp).
-struct MultiCfg { int r, bm, bn, wm, wn; };
-constexpr MultiCfg kMulti[] = {
-    {4, 128, 128, 4, 2},   // each wave 32 x 64 for 4 trials
-    {2, 128, 128, 4, 2},   // each wave 32 x 64 for 2 trials
-    {8, 128, 64, 4, 2},    // each wave 32 x 32 for 8 trials: narrow outputs
-};
-constexpr int kNumMulti = sizeof(kMulti) / sizeof(kMulti[0]);
+using fi::kCfg;
+using fi::kMulti;
+using fi::kNumCfg;
+using fi::kNumMulti;
+using fi::TileCfg;
+using fi::MultiCfg;
 
 }  // namespace
 
+// Trial order and descriptors of one batch of the multi-trial kernel.  One set per stream a
+// plan's batches have been enqueued on: batches on the same stream follow each other, batches
+// on different streams may be in flight together and must not share this state.
+struct BatchScratch {
+  hipStream_t stream = nullptr;
+  uint32_t* perm = nullptr;   // [cap] trial order + 2 counters behind it
+  uint32_t* desc = nullptr;   // [(cap + 16) * kMultiDescWords]
+  uint32_t cap = 0;
+};
+
 struct fi_plan {
-  uint32_t magic;
-  fi_plan_desc d;
-  const uint16_t* A;
-  const uint16_t* B;       // effective [N][ldb] K-contiguous matrix
-  uint32_t ldb;
-  uint16_t* Bt;            // plan-owned transposed copy (b_layout 1) or NULL
-  float* c_star;           // [M][N]
-  float* s_abs;            // [M][N]
-  float* kra;              // [pad(M)]
-  float* cb;               // [pad(N)]
-  float* scratch;          // 4 floats + 1 word
-  float t_global;
-  int cfg;                 // index into kCfg
-  int cfg_affected;        // index into kCfg for the affected-tiles-only campaign
-  int mcfg;                // index into kMulti, or -1: every trial through the single-trial kernel
-  int group;               // trials sharing a tile back to back
-  int device;
-  uint32_t* perm;          // [perm_cap] trial order of the current batch + 2 counters behind it
-  uint32_t* desc;          // [(perm_cap + 8) * 5] descriptors of the multi-trial kernel's trials
-  uint32_t perm_cap;
-  int n_cus;               // compute units of the device: grid of the persistent kernel
-  int product_check;       // FI_PCHECK_*
+  fi_plan_desc d = {};
+  const uint16_t* A = nullptr;
+  const uint16_t* B = nullptr;       // effective [N][ldb] K-contiguous matrix
+  uint32_t ldb = 0;
+  uint16_t* Bt = nullptr;            // plan-owned transposed copy (b_layout 1) or NULL
+  float* c_star = nullptr;           // [M][N]
+  float* s_abs = nullptr;            // [M][N]
+  float* kra = nullptr;              // [pad(M)]
+  float* cb = nullptr;               // [pad(N)]
+  float* scratch = nullptr;          // 4 floats + 4 words: maxima, "operand not finite", clean flags
+  float t_global = 0.0f;
+  uint32_t n_clean_flagged = 0;      // elements of C* the plan's own detector flags
+  int cfg = 0;                       // index into kCfg
+  int cfg_affected = 0;              // index into kCfg for the affected-tiles-only campaign
+  int mcfg = -1;                     // index into kMulti, or -1: every trial through the single-trial kernel
+  int group = 32;                    // trials sharing a tile back to back
+  int device = 0;
+  std::vector<BatchScratch> batch;   // per stream, see BatchScratch
+  int n_cus = 8;                     // compute units of the device: grid of the persistent kernel
+  int product_check = FI_PCHECK_NONE;
 };
 
 namespace {
 
 using fi::GemmArgs;
 
-template <int DT, int CFG, int MODE>
-hipError_t launch_cfg(const GemmArgs& a, int n_blocks, hipStream_t s) {
-  constexpr TileCfg c = kCfg[CFG];
-  hipLaunchKernelGGL((fi::gemm_fi_kernel<DT, c.bm, c.bn, c.wm, c.wn, MODE>), dim3(n_blocks),
-                     dim3(c.wm * c.wn * 64), 0, s, a);
-  return hipGetLastError();
-}
-
-template <int MODE>
-hipError_t launch_gemm(int dtype, int cfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
+// Each (format, configuration) pair has its launcher in a translation unit of its own.
+hipError_t launch_gemm(int mode, int dtype, int cfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
 #define FI_CASE(DT, CFG) \
-  if (dtype == DT && cfg == CFG) return launch_cfg<DT, CFG, MODE>(a, n_blocks, s)
-  FI_CASE(FI_FP16, 0); FI_CASE(FI_FP16, 1); FI_CASE(FI_FP16, 2);
-  FI_CASE(FI_BF16, 0); FI_CASE(FI_BF16, 1); FI_CASE(FI_BF16, 2);
+  if (dtype == DT && cfg == CFG) return fi::launch_single_d##DT##_c##CFG(mode, a, n_blocks, s)
+  FI_CASE(0, 0); FI_CASE(0, 1); FI_CASE(0, 2);
+  FI_CASE(1, 0); FI_CASE(1, 1); FI_CASE(1, 2);
 #undef FI_CASE
   return hipErrorInvalidValue;
 }
 
-// Two launches: the plain instantiation on the first part of the batch (no fault, accumulator
-// flips, product-term faults), the operand-patching one on the second part (operand faults).
-// Each finds its trial count on the device and exits at once if it is zero.
-template <int DT, int MC>
-hipError_t launch_multi_cfg(const GemmArgs& a, int n_blocks, hipStream_t s) {
-  constexpr MultiCfg c = kMulti[MC];
-  hipLaunchKernelGGL((fi::gemm_fi_multi_kernel<DT, c.r, c.bm, c.bn, c.wm, c.wn, false>), dim3(n_blocks),
-                     dim3(c.wm * c.wn * 64), 0, s, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((fi::gemm_fi_multi_kernel<DT, c.r, c.bm, c.bn, c.wm, c.wn, true>), dim3(n_blocks),
-                     dim3(c.wm * c.wn * 64), 0, s, a);
-  return hipGetLastError();
-}
-
 hipError_t launch_multi(int dtype, int mcfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
 #define FI_CASE(DT, MC) \
-  if (dtype == DT && mcfg == MC) return launch_multi_cfg<DT, MC>(a, n_blocks, s)
-  FI_CASE(FI_FP16, 0); FI_CASE(FI_FP16, 1); FI_CASE(FI_FP16, 2);
-  FI_CASE(FI_BF16, 0); FI_CASE(FI_BF16, 1); FI_CASE(FI_BF16, 2);
+  if (dtype == DT && mcfg == MC) return fi::launch_multi_d##DT##_c##MC(a, n_blocks, s)
+  FI_CASE(0, 0); FI_CASE(0, 1); FI_CASE(0, 2);
+  FI_CASE(1, 0); FI_CASE(1, 1); FI_CASE(1, 2);
 #undef FI_CASE
   return hipErrorInvalidValue;
 }
@@ -160,11 +137,11 @@ fi_status compute_golden(fi_plan* p, hipStream_t s, const uint16_t* absA, const 
   GemmArgs a = base_args(p);
   a.n_trials = 1; a.group = 1;
   a.c_out = p->c_star;
-  FI_HIP(launch_gemm<fi::MODE_GOLDEN>((int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
+  FI_HIP(launch_gemm(fi::MODE_GOLDEN, (int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
   a.A = absA; a.B = absB;
   a.lda = a.ldb = (uint32_t)p->d.K;     // the copies are packed
   a.c_out = p->s_abs;
-  FI_HIP(launch_gemm<fi::MODE_GOLDEN>((int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
+  FI_HIP(launch_gemm(fi::MODE_GOLDEN, (int)p->d.dtype, p->cfg, a, a.tiles_m * a.tiles_n, s));
   return FI_OK;
 }
 
@@ -191,7 +168,9 @@ fi_status check_desc(const fi_plan_desc* d, float* gamma_out) {
     return fail(FI_UNSUPPORTED, "dtype %u: only FP16 (0) and BF16 (1) operands", d->dtype);
   if (d->b_layout > 1) return fail(FI_INVALID_ARG, "b_layout must be 0 or 1");
   if (d->bound_mode > FI_BOUND_EXPONENT) return fail(FI_INVALID_ARG, "bound_mode must be 0, 1 or 2");
-  float g = d->gamma == 0.0f ? 1.0f + 1.0f / 2048.0f : d->gamma;
+  // Default slack: 1 + 2^-11 for K <= 4096, growing in proportion beyond (a K-term FP32
+  // accumulation inflates a sum by at most (1 + 2^-24)^(K-1); twice that, in units of 4096 terms).
+  float g = d->gamma == 0.0f ? 1.0f + (float)((d->K + 4095u) / 4096u) / 2048.0f : d->gamma;
   if (!(g >= 1.0f) || !(g <= 3.0e38f)) return fail(FI_INVALID_ARG, "gamma must be finite and >= 1");
   if (d->K > 65536u) return fail(FI_UNSUPPORTED, "K > 65536");
   if (d->M > (1u << 24) || d->N > (1u << 24)) return fail(FI_UNSUPPORTED, "M or N > 2^24");
@@ -201,9 +180,15 @@ fi_status check_desc(const fi_plan_desc* d, float* gamma_out) {
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// Live plans.  A handle is looked up here before it is dereferenced, so a destroyed (or
+// never created) plan is an error and not a read of freed memory.
+std::mutex g_live_mu;
+std::unordered_set<const fi_plan*> g_live;
+
 fi_status check_plan(const fi_plan* p) {
   if (!p) return fail(FI_INVALID_ARG, "plan is NULL");
-  if (p->magic != PLAN_MAGIC) return fail(FI_STATE, "plan is not live (destroyed or corrupt)");
+  std::lock_guard<std::mutex> lock(g_live_mu);
+  if (g_live.find(p) == g_live.end()) return fail(FI_STATE, "plan is not live (destroyed or never created)");
   return FI_OK;
 }
 
@@ -214,8 +199,36 @@ void free_plan_buffers(fi_plan* p) {
   if (p->kra) (void)hipFree(p->kra);
   if (p->cb) (void)hipFree(p->cb);
   if (p->scratch) (void)hipFree(p->scratch);
-  if (p->perm) (void)hipFree(p->perm);
-  if (p->desc) (void)hipFree(p->desc);
+  for (BatchScratch& b : p->batch) {
+    if (b.perm) (void)hipFree(b.perm);
+    if (b.desc) (void)hipFree(b.desc);
+  }
+  p->batch.clear();
+}
+
+// The batch scratch of `stream`, holding at least n trials.  Allocates on the first batch of a
+// stream and when a batch is larger than any before on it (the replaced buffers are freed,
+// which waits for device work that may still read them).
+fi_status batch_scratch(fi_plan* p, hipStream_t stream, uint32_t n, BatchScratch** out) {
+  BatchScratch* b = nullptr;
+  for (BatchScratch& x : p->batch)
+    if (x.stream == stream) b = &x;
+  if (!b) {
+    if (p->batch.size() >= 64) return fail(FI_STATE, "a plan serves at most 64 distinct streams");
+    p->batch.emplace_back();
+    b = &p->batch.back();
+    b->stream = stream;
+  }
+  if (b->cap < n) {
+    if (b->perm) (void)hipFree(b->perm);
+    if (b->desc) (void)hipFree(b->desc);
+    b->perm = nullptr; b->desc = nullptr; b->cap = 0;
+    FI_HIP(hipMalloc(&b->perm, ((size_t)n + 2) * sizeof(uint32_t)));
+    FI_HIP(hipMalloc(&b->desc, ((size_t)n + 16) * fi::kMultiDescWords * sizeof(uint32_t)));
+    b->cap = n;
+  }
+  *out = b;
+  return FI_OK;
 }
 
 size_t padded(uint32_t n) { return ((size_t)n + PAD - 1) / PAD * PAD; }
@@ -294,6 +307,101 @@ fi_status build_plan(fi_plan* p, const void* d_A, const void* d_B, hipStream_t s
   p->t_global = t;
   // Exponent field >= 144 <=> NOT (|c| <= largest binary32 below 2^17)
   if (d.bound_mode == FI_BOUND_EXPONENT) p->t_global = 131071.9921875f;
+  // How many elements of the fault-free result the plan's own detector flags (none under the
+  // operand-derived bounds with gamma at or above the default; possible under the exponent-only
+  // bound or a caller's smaller gamma).  The affected-tiles-only campaign relies on it being 0.
+  {
+    uint32_t* n_clean = reinterpret_cast<uint32_t*>(p->scratch + 5);
+    const bool vec = d.N % 4 == 0;
+    size_t gx = vec ? (size_t)d.M : (mn + 255) / 256;
+    if (gx > 2048) gx = 2048;
+    if (vec)
+      hipLaunchKernelGGL(fi::detect_correct_kernel<4>, dim3((unsigned)gx, 1), dim3(256), 0, s, p->c_star, (int)d.M,
+                         (int)d.N, p->kra, p->cb, d.gamma, (int)(d.bound_mode != FI_BOUND_ROWCOL), p->t_global,
+                         (int)FI_CORRECT_NONE, (const float*)nullptr, (uint8_t*)nullptr, n_clean);
+    else
+      hipLaunchKernelGGL(fi::detect_correct_kernel<1>, dim3((unsigned)gx, 1), dim3(256), 0, s, p->c_star, (int)d.M,
+                         (int)d.N, p->kra, p->cb, d.gamma, (int)(d.bound_mode != FI_BOUND_ROWCOL), p->t_global,
+                         (int)FI_CORRECT_NONE, (const float*)nullptr, (uint8_t*)nullptr, n_clean);
+    FI_HIP(hipGetLastError());
+    FI_HIP(hipMemcpyAsync(&p->n_clean_flagged, n_clean, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    FI_HIP(hipStreamSynchronize(s));
+  }
+  return FI_OK;
+}
+
+// Where one batch of the multi-trial kernel keeps its trial order, the two part counts and the
+// per-trial descriptors; all of it is rewritten by the partition kernel of every batch.
+struct TrialScratch {
+  uint32_t* perm = nullptr;     // [n_trials]
+  uint32_t* counts = nullptr;   // [2]
+  uint32_t* desc = nullptr;     // [(n_trials + 16) * kMultiDescWords]
+};
+
+fi_status check_batch_args(const fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
+                           const fi_trial_result* d_results) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (!d_faults || !d_results) return fail(FI_INVALID_ARG, "d_faults and d_results must be non-NULL");
+  if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
+  if (policy > FI_CORRECT_RECOMPUTE) return fail(FI_INVALID_ARG, "unknown correction policy %u", policy);
+  return FI_OK;
+}
+
+// One campaign batch: record fill, then either the partition kernel and the two launches of
+// the multi-trial kernel (scratch in `ts`), or one launch of the one-trial kernel.
+fi_status inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
+                       fi_trial_result* d_results, float* d_c_out, hipStream_t s, const TrialScratch& ts) {
+  GemmArgs a = base_args(plan);
+  const uint64_t blocks = (uint64_t)a.tiles_m * a.tiles_n * n_trials;
+  if (blocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
+  const MultiCfg mc = kMulti[plan->mcfg >= 0 ? plan->mcfg : 0];
+  GemmArgs m = a;
+  uint64_t mblocks = 0;
+  if (plan->mcfg >= 0) {
+    m.tiles_m = (a.M + mc.bm - 1) / mc.bm;
+    m.tiles_n = (a.N + mc.bn - 1) / mc.bn;
+    // Persistent workgroups, one per CU (the register budget admits no more), each walking the
+    // work list with the grid as stride; a multiple of 8 keeps a workgroup's items on one XCD.
+    const uint64_t groups = ((uint64_t)n_trials + mc.r - 1) / mc.r;
+    const uint64_t items = (uint64_t)m.tiles_m * m.tiles_n * groups;
+    if (items >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 work items; split the batch");
+    const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8);
+    mblocks = items < cus ? items : cus;
+  }
+  const size_t words = (size_t)n_trials * (sizeof(fi_trial_result) / 4);
+  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3((unsigned)((words + 255) / 256 > 1024 ? 1024 : (words + 255) / 256)),
+                     dim3(256), 0, s, reinterpret_cast<uint32_t*>(d_results), words, 0u);
+  FI_HIP(hipGetLastError());
+  for (GemmArgs* g : {&a, &m}) {
+    g->n_trials = (int)n_trials;
+    g->group = plan->group;
+    g->faults = d_faults;
+    g->results = d_results;
+    g->c_out = d_c_out;
+    g->policy = (int)policy;
+    g->product_check = plan->product_check;
+  }
+  if (plan->mcfg < 0) {
+    FI_HIP(launch_gemm(fi::MODE_CAMPAIGN, (int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
+    return FI_OK;
+  }
+  // R trials at a time share staged operands.  The batch is split on the device into the trials
+  // whose fault leaves the operands alone and the operand-fault trials; each part has its own
+  // instantiation of the kernel.
+  if (plan->d.dtype == FI_BF16)
+    hipLaunchKernelGGL(fi::partition_trials_kernel<FI_BF16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
+                       plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
+                       (uint32_t)mc.bm, (uint32_t)mc.bn, ts.perm, ts.counts, ts.desc, d_results);
+  else
+    hipLaunchKernelGGL(fi::partition_trials_kernel<FI_FP16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
+                       plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
+                       (uint32_t)mc.bm, (uint32_t)mc.bn, ts.perm, ts.counts, ts.desc, d_results);
+  FI_HIP(hipGetLastError());
+  m.perm = ts.perm;
+  m.part_counts = ts.counts;
+  m.desc = ts.desc;
+  FI_HIP(launch_multi((int)plan->d.dtype, plan->mcfg, m, (int)mblocks, s));
   return FI_OK;
 }
 
@@ -312,6 +420,11 @@ inline uint32_t scale_to(uint32_t n, uint64_t u) { return (uint32_t)(((u >> 32) 
 extern "C" {
 
 const char* fi_last_error(void) { return g_err; }
+
+#ifndef FI_SOURCES_SHA256
+#define FI_SOURCES_SHA256 "unknown"
+#endif
+const char* fi_build_info(void) { return FI_SOURCES_SHA256; }
 
 fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* d_B, void* stream,
                          fi_plan** out) {
@@ -334,9 +447,8 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   st = check_device();
   if (st != FI_OK) return st;
 
-  fi_plan* p = new (std::nothrow) fi_plan;
+  fi_plan* p = new (std::nothrow) fi_plan();
   if (!p) return fail(FI_OOM, "host allocation failed");
-  memset(p, 0, sizeof(*p));
   p->d = d;
   p->d.gamma = gamma;
   p->cfg = pick_cfg(d);
@@ -354,7 +466,10 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
     delete p;
     return st;
   }
-  p->magic = PLAN_MAGIC;
+  {
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    g_live.insert(p);
+  }
   *out = p;
   return FI_OK;
 }
@@ -362,9 +477,12 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
 fi_status fi_plan_destroy(fi_plan* plan) {
   fi_status st = check_plan(plan);
   if (st != FI_OK) return st;
+  {
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    g_live.erase(plan);
+  }
   (void)hipDeviceSynchronize();   // work that still reads the plan's buffers
   free_plan_buffers(plan);
-  plan->magic = 0;
   delete plan;
   return FI_OK;
 }
@@ -400,6 +518,14 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
   return FI_OK;
 }
 
+fi_status fi_plan_reserve(fi_plan* plan, uint32_t max_trials, void* stream) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (max_trials == 0) return fail(FI_INVALID_ARG, "max_trials is 0");
+  BatchScratch* bs = nullptr;
+  return batch_scratch(plan, as_stream(stream), max_trials, &bs);
+}
+
 fi_status fi_plan_set_product_check(fi_plan* plan, uint32_t mode) {
   fi_status st = check_plan(plan);
   if (st != FI_OK) return st;
@@ -426,69 +552,16 @@ fi_status fi_plan_describe(const fi_plan* plan, char* h_buf, uint64_t n) {
 
 fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
                                fi_trial_result* d_results, float* d_c_out, void* stream) {
-  fi_status st = check_plan(plan);
+  fi_status st = check_batch_args(plan, d_faults, n_trials, policy, d_results);
   if (st != FI_OK) return st;
-  if (!d_faults || !d_results) return fail(FI_INVALID_ARG, "d_faults and d_results must be non-NULL");
-  if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
-  if (policy > FI_CORRECT_RECOMPUTE) return fail(FI_INVALID_ARG, "unknown correction policy %u", policy);
-  GemmArgs a = base_args(plan);
-  const uint64_t blocks = (uint64_t)a.tiles_m * a.tiles_n * n_trials;
-  if (blocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
-  hipStream_t s = as_stream(stream);
-  const size_t words = (size_t)n_trials * (sizeof(fi_trial_result) / 4);
-  hipLaunchKernelGGL(fi::fill_u32_kernel, dim3((unsigned)((words + 255) / 256 > 1024 ? 1024 : (words + 255) / 256)),
-                     dim3(256), 0, s, reinterpret_cast<uint32_t*>(d_results), words, 0u);
-  FI_HIP(hipGetLastError());
-  a.n_trials = (int)n_trials;
-  a.group = plan->group;
-  a.faults = d_faults;
-  a.results = d_results;
-  a.c_out = d_c_out;
-  a.policy = (int)policy;
-  a.product_check = plan->product_check;
+  TrialScratch ts;
   if (plan->mcfg >= 0) {
-    // R trials at a time share staged operands.  The batch is split on the device into the trials
-    // whose fault leaves the operands alone and the operand-fault trials; each part has its own
-    // instantiation of the kernel.
-    if (plan->perm_cap < n_trials) {
-      if (plan->perm) (void)hipFree(plan->perm);     // waits for work that may still read it
-      if (plan->desc) (void)hipFree(plan->desc);
-      plan->perm = nullptr; plan->desc = nullptr; plan->perm_cap = 0;
-      FI_HIP(hipMalloc(&plan->perm, ((size_t)n_trials + 2) * sizeof(uint32_t)));
-      FI_HIP(hipMalloc(&plan->desc, ((size_t)n_trials + 16) * fi::kMultiDescWords * sizeof(uint32_t)));
-      plan->perm_cap = n_trials;
-    }
-    uint32_t* counts = plan->perm + plan->perm_cap;
-    if (plan->d.dtype == FI_BF16)
-      hipLaunchKernelGGL(fi::partition_trials_kernel<FI_BF16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
-                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
-                         (uint32_t)kMulti[plan->mcfg].bm, (uint32_t)kMulti[plan->mcfg].bn, plan->perm,
-                         counts, plan->desc, d_results);
-    else
-      hipLaunchKernelGGL(fi::partition_trials_kernel<FI_FP16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
-                         plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
-                         (uint32_t)kMulti[plan->mcfg].bm, (uint32_t)kMulti[plan->mcfg].bn, plan->perm,
-                         counts, plan->desc, d_results);
-    FI_HIP(hipGetLastError());
-    a.perm = plan->perm;
-    a.part_counts = counts;
-    a.desc = plan->desc;
-    const MultiCfg mc = kMulti[plan->mcfg];
-    GemmArgs m = a;
-    m.tiles_m = (a.M + mc.bm - 1) / mc.bm;
-    m.tiles_n = (a.N + mc.bn - 1) / mc.bn;
-    // Persistent workgroups, one per CU (the register budget admits no more), each walking the
-    // work list with the grid as stride; a multiple of 8 keeps a workgroup's items on one XCD.
-    const uint64_t groups = ((uint64_t)n_trials + mc.r - 1) / mc.r;
-    const uint64_t items = (uint64_t)m.tiles_m * m.tiles_n * groups;
-    if (items >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 work items; split the batch");
-    const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8);
-    const uint64_t mblocks = items < cus ? items : cus;
-    FI_HIP(launch_multi((int)plan->d.dtype, plan->mcfg, m, (int)mblocks, s));
-    return FI_OK;
+    BatchScratch* bs = nullptr;
+    st = batch_scratch(plan, as_stream(stream), n_trials, &bs);
+    if (st != FI_OK) return st;
+    ts.perm = bs->perm; ts.counts = bs->perm + bs->cap; ts.desc = bs->desc;
   }
-  FI_HIP(launch_gemm<fi::MODE_CAMPAIGN>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
-  return FI_OK;
+  return inject_batch(plan, d_faults, n_trials, policy, d_results, d_c_out, as_stream(stream), ts);
 }
 
 fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
@@ -498,6 +571,9 @@ fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults,
   if (!d_faults || !d_results) return fail(FI_INVALID_ARG, "d_faults and d_results must be non-NULL");
   if (n_trials == 0) return fail(FI_INVALID_ARG, "n_trials is 0");
   if (policy > FI_CORRECT_RECOMPUTE) return fail(FI_INVALID_ARG, "unknown correction policy %u", policy);
+  if (plan->n_clean_flagged != 0)
+    return fail(FI_UNSUPPORTED, "the plan's detector flags %u element(s) of the fault-free result itself, which the "
+                "affected-tiles-only campaign would not count; use fi_gemm_inject_batch", plan->n_clean_flagged);
   GemmArgs a = base_args(plan, plan->cfg_affected);
   const uint64_t slots = (uint64_t)(a.tiles_m > a.tiles_n ? a.tiles_m : a.tiles_n);
   const uint64_t blocks = slots * n_trials;
@@ -513,7 +589,7 @@ fi_status fi_gemm_inject_batch_affected(fi_plan* plan, const fi_fault* d_faults,
   a.results = d_results;
   a.policy = (int)policy;
   a.product_check = plan->product_check;
-  FI_HIP(launch_gemm<fi::MODE_AFFECTED>((int)plan->d.dtype, plan->cfg_affected, a, (int)blocks, s));
+  FI_HIP(launch_gemm(fi::MODE_AFFECTED, (int)plan->d.dtype, plan->cfg_affected, a, (int)blocks, s));
   return FI_OK;
 }
 
@@ -566,7 +642,7 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
   a.results = d_results;
   a.c_out = d_c_out;
   a.policy = (int)policy;
-  FI_HIP(launch_gemm<fi::MODE_PROPAGATE>((int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
+  FI_HIP(launch_gemm(fi::MODE_PROPAGATE, (int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
   return FI_OK;
 }
 

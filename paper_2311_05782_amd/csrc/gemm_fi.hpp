@@ -98,8 +98,8 @@ __device__ __forceinline__ float decode16(uint32_t w) {
 }
 
 // binary32 -> FP16 / BF16 word, round to nearest even, in integer arithmetic (no dependence on
-// the wave's denormal or rounding modes).  This is the format a product is held in by the
-// paper's fault model (Sec. IV-C: the result of a multiplication operation).
+// the wave's denormal or rounding modes).  The paper's fault model holds a product in the
+// operand format (Sec. IV-C).
 template <int DT>
 __device__ __forceinline__ uint32_t round16(float x) {
   const uint32_t b = __float_as_uint(x);
@@ -395,18 +395,19 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_kernel(const GemmArgs p) 
       for (int c = 0; c < B_G; ++c)
         __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
     } else {
-      // chunks outside [0, K) are fetched from k = chunk offset (always valid) and zeroed later
+      // chunks outside [0, K) are fetched from the start of their row (always inside the operand,
+      // also when K < 64) and zeroed later
 #pragma unroll
       for (int c = 0; c < A_G; ++c) {
         const int ch = (lslot ^ lds_swizzle((wave * A_G + c) * 8 + lrow)) * 8;
         const bool kin = (k0 + ch) >= 0 && (k0 + ch) < p.K;
-        __builtin_amdgcn_global_load_lds((glb_void*)(Ap + a_goff[c] + (kin ? k0 : 0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(Ap + a_goff[c] + (kin ? k0 : -ch)), (lds_void*)(sA + c * 1024), 16, 0, 0);
       }
 #pragma unroll
       for (int c = 0; c < B_G; ++c) {
         const int ch = (lslot ^ lds_swizzle((wave * B_G + c) * 8 + lrow)) * 8;
         const bool kin = (k0 + ch) >= 0 && (k0 + ch) < p.K;
-        __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + (kin ? k0 : 0)), (lds_void*)(sB + c * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(p.B + b_goff[c] + (kin ? k0 : -ch)), (lds_void*)(sB + c * 1024), 16, 0, 0);
       }
     }
   };

@@ -27,9 +27,9 @@ BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 
 # Symbols include/fi.h declares; the loader checks every one.
 EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
-           "fi_plan_set_product_check", "fi_deviation_histogram",
+           "fi_plan_set_product_check", "fi_plan_reserve", "fi_deviation_histogram",
            "fi_gemm_inject_batch", "fi_gemm_inject_batch_affected", "fi_detect_correct", "fi_classify", "fi_sample_faults",
-           "fi_activation_round", "fi_gemm_propagate_batch", "fi_last_error"]
+           "fi_activation_round", "fi_gemm_propagate_batch", "fi_last_error", "fi_build_info"]
 
 FAULT_DTYPE = np.dtype([("kind", "<u4"), ("row", "<u4"), ("col", "<u4"), ("kblock", "<u4"),
                         ("xor_mask", "<u4")])
@@ -75,12 +75,22 @@ def lib():
     vp = C.c_void_p
     L.fi_last_error.restype = C.c_char_p
     L.fi_last_error.argtypes = []
+    L.fi_build_info.restype = C.c_char_p
+    L.fi_build_info.argtypes = []
+    # A binary older than the sources beside it is refused, not silently used.
+    if not os.environ.get("FI_LIBRARY"):
+        from . import build as _build
+        built, now = L.fi_build_info().decode(), _build.sources_digest()
+        if built != now:
+            raise ImportError("%s was built from other sources (%s..., now %s...): run "
+                              "python paper_2311_05782_amd/build.py" % (LIB_PATH, built[:12], now[:12]))
     L.fi_plan_create.argtypes = [C.POINTER(PlanDesc), vp, vp, vp, C.POINTER(vp)]
     L.fi_plan_destroy.argtypes = [vp]
     L.fi_plan_buffer.argtypes = [vp, C.c_uint32, C.POINTER(vp)]
     L.fi_plan_tune.argtypes = [vp, C.c_int32, C.c_int32, vp]
     L.fi_plan_describe.argtypes = [vp, C.c_char_p, C.c_uint64]
     L.fi_plan_set_product_check.argtypes = [vp, C.c_uint32]
+    L.fi_plan_reserve.argtypes = [vp, C.c_uint32, vp]
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch_affected.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp]
     L.fi_detect_correct.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
@@ -91,7 +101,7 @@ def lib():
     L.fi_sample_faults.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.POINTER(PlanDesc), C.c_uint32,
                                    C.c_uint32, vp]
     for name in EXPORTS:
-        if name != "fi_last_error":
+        if name not in ("fi_last_error", "fi_build_info"):
             getattr(L, name).restype = C.c_int32
     _lib = L
     return L
@@ -174,6 +184,9 @@ class Plan:
 
     def tune(self, tile_config=-1, trial_group=-1, stream=None):
         _check(lib().fi_plan_tune(self._h, tile_config, trial_group, _stream(stream)))
+
+    def reserve(self, max_trials, stream=None):
+        _check(lib().fi_plan_reserve(self._h, max_trials, _stream(stream)))
 
     def set_product_check(self, mode):
         _check(lib().fi_plan_set_product_check(self._h, mode))

@@ -86,6 +86,13 @@ def test_argument_errors_need_no_device():
     assert _status(lambda: fi._check(L.fi_classify(None, A, 1, None, B, None)))[0] == fi.INVALID_ARG
     assert _status(lambda: fi._check(L.fi_gemm_propagate_batch(None, A, 0, 1, 0, B, None, None)))[0] == fi.INVALID_ARG
     assert _status(lambda: fi._check(L.fi_gemm_inject_batch_affected(None, A, 1, 0, B, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_plan_reserve(None, 16, None)))[0] == fi.INVALID_ARG
+    # a handle that is not a live plan (never created, or destroyed) is looked up, not dereferenced
+    bogus = C.c_void_p(0x1000)
+    assert _status(lambda: fi._check(L.fi_plan_destroy(bogus)))[0] == fi.STATE
+    assert _status(lambda: fi._check(L.fi_plan_reserve(bogus, 16, None)))[0] == fi.STATE
+    assert _status(lambda: fi._check(L.fi_gemm_inject_batch(bogus, A, 1, 0, B, None, None)))[0] == fi.STATE
+    assert _status(lambda: fi._check(L.fi_classify(bogus, A, 1, None, B, None)))[0] == fi.STATE
     # the hand-over kernel's arguments
     assert _status(lambda: fi._check(L.fi_activation_round(2, A, 16, B, None)))[0] == fi.UNSUPPORTED
     assert _status(lambda: fi._check(L.fi_activation_round(fi.BF16, None, 16, B, None)))[0] == fi.INVALID_ARG
@@ -107,3 +114,9 @@ def test_no_device_is_reported_not_hidden():
     st, msg = _status(lambda: fi._check(fi.lib().fi_plan_create(C.byref(good), C.c_void_p(0x1000),
                                                               C.c_void_p(0x2000), None, C.byref(out))))
     assert st == fi.STATE and out.value is None
+
+
+def test_library_reports_the_sources_it_was_built_from():
+    from paper_2311_05782_amd import build
+    L = fi.lib()
+    assert L.fi_build_info().decode() == build.sources_digest()

@@ -102,6 +102,33 @@ def test_clean_outputs_never_exceed_threshold():
                 assert abs(Cm[i, j]) > 0.99 * orc.threshold(K, ra[i], cb[j], 1.0)
 
 
+def test_default_slack_grows_with_K_and_covers_a_long_accumulation():
+    # 1 + 2^-11 up to K = 4096, one more 2^-11 per further 4096 terms.
+    assert orc.default_gamma(16) == 1 + 2.0 ** -11 and orc.default_gamma(4096) == 1 + 2.0 ** -11
+    assert orc.default_gamma(4097) == 1 + 2.0 ** -10 and orc.default_gamma(8192) == 1 + 2.0 ** -10
+    assert orc.default_gamma(65536) == 1 + 2.0 ** -7
+    # Why: 65536 equal products (143/128)^2, added one by one in binary32, round upwards step
+    # after step and end 8.9e-4 above the exact sum - more than the 4.9e-4 the short-K slack allows.
+    K, kb, fmt = 65536, 64, orc.BF16
+    a = np.full((1, K), 143.0 / 128.0, np.float32)
+    Aw, Bw = wl.to_words(a, fmt), wl.to_words(a, fmt)
+    p = orc.problem(1, 1, K, kb, fmt)
+    assert p.gamma == np.float32(1 + 2.0 ** -7)
+    c = float(orc.gemm(p, Aw, Bw)[0, 0])
+    exact = K * (143.0 / 128.0) ** 2
+    assert c == float(np.cumsum(np.full(K, np.float32((143.0 / 128.0) ** 2), np.float32), dtype=np.float32)[-1])
+    assert c / exact > 1 + 2.0 ** -11 and c / exact < 1 + 2.0 ** -8
+    ra, cb, _ = orc.rowcol_absmax(p, Aw, Bw)
+    assert c > orc.threshold(K, ra[0], cb[0], 1 + 2.0 ** -11)        # the short-K slack would flag it
+    assert c <= orc.threshold(K, ra[0], cb[0], orc.default_gamma(K))  # the default does not
+    # and every mantissa of a same-sign, all-maximal row stays below the default bound
+    for K in (8192, 65536):
+        for m in range(128, 256, 5):
+            v = np.float32((m / 128.0) ** 2)
+            tot = float(np.cumsum(np.full(K, v, np.float32), dtype=np.float32)[-1])
+            assert tot <= orc.threshold(K, m / 128.0, m / 128.0, orc.default_gamma(K)), (K, m)
+
+
 def test_rowcol_absmax_and_threshold_rounding():
     M, N, K = 3, 2, 32
     a = np.zeros((M, K), np.float32); b = np.zeros((N, K), np.float32)
