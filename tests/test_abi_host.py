@@ -120,3 +120,36 @@ def test_library_reports_the_sources_it_was_built_from():
     from paper_2311_05782_amd import build
     L = fi.lib()
     assert L.fi_build_info().decode() == build.sources_digest()
+
+
+def _one_trial_kernel_fetch_offsets(M, K, lda, BM, n_waves, kshift, m0):
+    """Element offsets of every 16-byte chunk the one-trial kernel's staging fetches for one
+    operand and one workgroup (the address arithmetic of its issue_tile, restated): row groups
+    of 8 rows per wave instruction, lane = 8 * row-in-group + slot, fetched chunk = slot ^ g(row),
+    rows past the end clamped to the last, chunks outside [0, K) fetched from the row's start."""
+    out = []
+    nkt = (K + kshift + 63) // 64
+    groups = BM // 8 // n_waves
+    for kt in range(nkt):
+        k0 = kt * 64 - kshift
+        inside = k0 >= 0 and k0 + 64 <= K
+        for wave in range(n_waves):
+            for c in range(groups):
+                for lane in range(64):
+                    row = (wave * groups + c) * 8 + (lane >> 3)
+                    ch = ((lane & 7) ^ ((row & 7) ^ ((row >> 3) & 1))) * 8
+                    goff = min(m0 + row, M - 1) * lda + ch
+                    kin = 0 <= k0 + ch < K
+                    out.append(goff + (k0 if (inside or kin) else -ch))
+    return out
+
+
+def test_one_trial_kernel_never_fetches_outside_its_operands():
+    # Every chunk is 8 elements; it must lie inside [0, (M-1)*lda + K) for packed and padded rows,
+    # K shorter than a k-tile, ragged tiles and every k-shift an accumulator fault can ask for.
+    for (M, K, lda) in [(5, 16, 16), (128, 16, 16), (33, 48, 48), (300, 96, 96), (257, 128, 136), (64, 64, 64)]:
+        for (BM, nw) in [(256, 8), (128, 4), (256, 4)]:
+            for kshift in (0, 16, 32, 48):
+                for m0 in range(0, M, BM):
+                    offs = _one_trial_kernel_fetch_offsets(M, K, lda, BM, nw, kshift, m0)
+                    assert min(offs) >= 0 and max(offs) + 8 <= (M - 1) * lda + K, (M, K, lda, BM, kshift, m0)

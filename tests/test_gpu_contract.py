@@ -130,7 +130,7 @@ def test_affected_only_campaign_refuses_a_plan_whose_clean_result_is_flagged():
                               (orc.SITE_ACC, 7, 9, 1, 1 << 31)])
     recs = gu.gpu_campaign(plan, faults, wl.CORRECT_ZERO)
     for t in range(len(faults)):
-        o = orc.trial(p, Aw, Bw, faults[t:t + 1], wl.CORRECT_ZERO, orc.MODE_FULL)[0]
+        o = orc.trial(p, Aw, Bw, faults[t:t + 1], wl.CORRECT_ZERO, orc.MODE_FULL)
         assert int(recs["n_flagged"][t]) == int(o["n_flagged"]) >= 1, t
     d_r = fi.empty_results(len(faults))
     with pytest.raises(fi.FiError) as e:

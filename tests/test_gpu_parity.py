@@ -342,12 +342,13 @@ def test_campaign_calls_replay_correctly_from_a_hip_graph():
     d_r = fi.empty_results(n)
     d_cls = torch.empty(n, dtype=torch.uint8, device="cuda")
     d_cnt = torch.empty(3, dtype=torch.int64, device="cuda")
-    plan.fi_gemm_inject_batch(d_f, n, fi.CORRECT_ZERO, d_r)           # eager: also sizes the plan's scratch
+    plan.fi_gemm_inject_batch(d_f, n, fi.CORRECT_ZERO, d_r)
     plan.fi_classify(d_r, n, d_cls, d_cnt)
     torch.cuda.synchronize()
     want_r = fi.results_to_host(d_r).copy()
     want_cnt = d_cnt.cpu().numpy().copy()
     side = torch.cuda.Stream()
+    plan.reserve(n, side)               # each stream has its own batch scratch: size it outside the capture
     g = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(g, stream=side):

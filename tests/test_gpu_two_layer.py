@@ -152,8 +152,8 @@ def test_two_layers_end_to_end_against_the_oracle_chain(fmt):
 
 
 def test_the_chain_replays_correctly_from_a_hip_graph():
-    # The three calls clear their records with kernels and allocate nothing, so the whole chain
-    # can be captured; replays alternate with eager work and are compared with the eager result.
+    # The three calls clear their records with kernels and, once the stream's batch scratch is
+    # reserved, allocate nothing, so the whole chain can be captured; replays alternate with eager work and are compared with the eager result.
     import torch
     fmt, kb = orc.BF16, 32
     Xw, W1w, W2w = wl.two_layer_mlp(M=128, D=64, H=192, fmt=fmt, seed=3)
@@ -185,6 +185,7 @@ def test_the_chain_replays_correctly_from_a_hip_graph():
     g = torch.cuda.CUDAGraph()
     d_f.copy_(fi.to_device(lists[0]))
     torch.cuda.synchronize()
+    plan1.reserve(n, side)              # the capturing stream's batch scratch, sized outside the capture
     with torch.cuda.stream(side):
         with torch.cuda.graph(g, stream=side):
             chain(stream=torch.cuda.current_stream().cuda_stream)
