@@ -198,6 +198,20 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
                                uint32_t policy, fi_trial_result* d_results, float* d_c_out,
                                void* stream);
 
+/* fi_gemm_inject_batch for callers that cannot allocate device memory or synchronise: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same records and outputs; the trial order, the part counts and the
+ * per-trial descriptors of the batch live in a static device array of the library (about
+ * 460 KB per GPU, held until the process ends) instead of plan-owned buffers, so the call
+ * allocates nothing and never synchronises.  Limits: n_trials <= 16384 (FI_UNSUPPORTED beyond);
+ * every call on a GPU - whatever the plan or stream - uses that GPU's one array, which is
+ * rewritten by each call's partition kernel before it is read, so calls that overlap on one
+ * GPU race: order them (one stream, or events).  The array's address is looked up when a plan
+ * is created on that GPU.  Errors otherwise as fi_gemm_inject_batch. */
+fi_status fi_gemm_inject_batch_noalloc(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
+                                       uint32_t policy, fi_trial_result* d_results, float* d_c_out,
+                                       void* stream);
+
 /* The same campaign restricted to what a fault can reach: for each trial only the output
  * tiles holding the faulted element (ACC, PRODUCT), its output row (A) or its output column
  * (B) are computed; every other element of a trial equals the fault-free result bit for bit

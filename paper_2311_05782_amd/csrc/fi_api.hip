@@ -405,6 +405,31 @@ fi_status inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trial
   return FI_OK;
 }
 
+// ---- scratch of fi_gemm_inject_batch_noalloc: one array per GPU, held until the process ends.
+constexpr uint32_t kNoAllocMaxTrials = 16384;
+constexpr size_t kNoAllocPermWords = (((size_t)kNoAllocMaxTrials + 2 + 63) / 64) * 64;   // desc starts 256-byte aligned
+constexpr size_t kNoAllocWords = kNoAllocPermWords + ((size_t)kNoAllocMaxTrials + 16) * fi::kMultiDescWords;
+static __device__ __align__(256) uint32_t scratch[kNoAllocWords];
+
+// The array's address on each device (the name above is only a host-side handle for the
+// symbol: every use from host code goes through the looked-up pointer).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+uint32_t* g_scratch_ptr[kMaxDevices] = {};
+
+// Looks the address up once per device, with that device current.  Called from
+// fi_plan_create (set-up), so that the entry point itself only reads the table.
+fi_status resolve_static_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return fail(FI_UNSUPPORTED, "device index %d beyond %d", device, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[device]) return FI_OK;
+  uint32_t* ptr = nullptr;
+  FI_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+  if (!ptr) return fail(FI_DEVICE, "hipGetSymbolAddress returned a NULL address for the static scratch");
+  g_scratch_ptr[device] = ptr;
+  return FI_OK;
+}
+
 uint64_t splitmix64(uint64_t* state) {
   uint64_t z = (*state += 0x9E3779B97F4A7C15ull);
   z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
@@ -462,6 +487,12 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   st = build_plan(p, d_A, d_B, as_stream(stream));
   if (st != FI_OK) {
     (void)hipStreamSynchronize(as_stream(stream));
+    free_plan_buffers(p);
+    delete p;
+    return st;
+  }
+  st = resolve_static_scratch(p->device);
+  if (st != FI_OK) {
     free_plan_buffers(p);
     delete p;
     return st;
@@ -561,6 +592,26 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
     if (st != FI_OK) return st;
     ts.perm = bs->perm; ts.counts = bs->perm + bs->cap; ts.desc = bs->desc;
   }
+  return inject_batch(plan, d_faults, n_trials, policy, d_results, d_c_out, as_stream(stream), ts);
+}
+
+fi_status fi_gemm_inject_batch_noalloc(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
+                                       fi_trial_result* d_results, float* d_c_out, void* stream) {
+  fi_status st = check_batch_args(plan, d_faults, n_trials, policy, d_results);
+  if (st != FI_OK) return st;
+  if (n_trials > kNoAllocMaxTrials)
+    return fail(FI_UNSUPPORTED, "n_trials %u exceeds the %u trials the static scratch holds; split the batch or use "
+                "fi_gemm_inject_batch", n_trials, kNoAllocMaxTrials);
+  uint32_t* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    base = g_scratch_ptr[plan->device];
+  }
+  if (!base) return fail(FI_STATE, "the static scratch of device %d was not resolved at plan creation", plan->device);
+  TrialScratch ts;
+  ts.perm = base;
+  ts.counts = base + kNoAllocMaxTrials;          // the two words behind the trial order
+  ts.desc = base + kNoAllocPermWords;
   return inject_batch(plan, d_faults, n_trials, policy, d_results, d_c_out, as_stream(stream), ts);
 }
 
