@@ -152,11 +152,12 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
 /* Optional tuning.  tile_config: -1 keep, else an index into the kernel table:
  *   0..2  one trial per workgroup on a 256x256, 128x128 or 256x64 output tile
  *         (every fault kind, any K);
- *   3..5  R trials per workgroup sharing one staged operand tile: R=4 on 128x128,
- *         R=2 on 128x128, R=8 on 128x64 (the default when K % 64 == 0).  The batch is
- *         split on the device into the trials whose fault leaves the operands alone
- *         and the operand-fault trials; the latter run in a second instantiation that
- *         feeds the faulted trial a patched copy of the fragment registers.
+ *   3..6  R trials per workgroup sharing one staged operand tile: R=4 on 128x128, R=2 on
+ *         128x128, R=8 on 128x64 (the default when K % 64 == 0), and, with two workgroups of
+ *         four waves per compute unit instead of one of eight, R=8 on 64x64.
+ *         The batch is split on the device into the trials whose fault leaves the operands
+ *         alone and the operand-fault trials; the latter run in a second instantiation that
+ *         XORs the faulted word in the fragment registers around the faulted trial's MFMAs.
  *         FI_UNSUPPORTED if K % 64 != 0.
  * trial_group: -1 keep, else how many trials (groups of R trials) of the same
  * output tile are scheduled next to each other, 1..4096.  Results do not depend on

@@ -98,8 +98,8 @@ hipError_t launch_gemm(int mode, int dtype, int cfg, const GemmArgs& a, int n_bl
 hipError_t launch_multi(int dtype, int mcfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
 #define FI_CASE(DT, MC) \
   if (dtype == DT && mcfg == MC) return fi::launch_multi_d##DT##_c##MC(a, n_blocks, s)
-  FI_CASE(0, 0); FI_CASE(0, 1); FI_CASE(0, 2);
-  FI_CASE(1, 0); FI_CASE(1, 1); FI_CASE(1, 2);
+  FI_CASE(0, 0); FI_CASE(0, 1); FI_CASE(0, 2); FI_CASE(0, 3);
+  FI_CASE(1, 0); FI_CASE(1, 1); FI_CASE(1, 2); FI_CASE(1, 3);
 #undef FI_CASE
   return hipErrorInvalidValue;
 }
@@ -361,12 +361,13 @@ fi_status inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trial
   if (plan->mcfg >= 0) {
     m.tiles_m = (a.M + mc.bm - 1) / mc.bm;
     m.tiles_n = (a.N + mc.bn - 1) / mc.bn;
-    // Persistent workgroups, one per CU (the register budget admits no more), each walking the
-    // work list with the grid as stride; a multiple of 8 keeps a workgroup's items on one XCD.
+    // Persistent workgroups, as many per CU as the configuration's register budget admits, each
+    // walking the work list with the grid as stride; a multiple of 8 keeps a workgroup's items
+    // on one XCD.
     const uint64_t groups = ((uint64_t)n_trials + mc.r - 1) / mc.r;
     const uint64_t items = (uint64_t)m.tiles_m * m.tiles_n * groups;
     if (items >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 work items; split the batch");
-    const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8);
+    const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8) * (uint64_t)mc.wgs;
     mblocks = items < cus ? items : cus;
   }
   const size_t words = (size_t)n_trials * (sizeof(fi_trial_result) / 4);
@@ -573,8 +574,8 @@ fi_status fi_plan_describe(const fi_plan* plan, char* h_buf, uint64_t n) {
   const char* dt = plan->d.dtype == FI_BF16 ? "bf16" : "fp16";
   if (plan->mcfg >= 0) {
     const MultiCfg m = kMulti[plan->mcfg];
-    snprintf(h_buf, n, "gemm_fi_multi_kernel<%s, R=%d, %dx%d, %d threads, persistent> (a second, operand-patching "
-             "instantiation for operand faults)", dt, m.r, m.bm, m.bn, m.wm * m.wn * 64);
+    snprintf(h_buf, n, "gemm_fi_multi_kernel<%s, R=%d, %dx%d, %d threads, persistent x%d per CU> (a second, "
+             "operand-patching instantiation for operand faults)", dt, m.r, m.bm, m.bn, m.wm * m.wn * 64, m.wgs);
   } else {
     snprintf(h_buf, n, "gemm_fi_kernel<%s, %dx%d, %d threads>", dt, c.bm, c.bn, c.wm * c.wn * 64);
   }

@@ -41,7 +41,7 @@ namespace fi {
 constexpr int kMultiDescWords = 6;   // trial, row, col, event, w0, w1
 
 template <int DT, int R, int BM, int BN, int WM, int WN, bool OPS>
-__global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmArgs p) {
+__global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const GemmArgs p) {
   constexpr int BK = 64;
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -83,6 +83,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     int m0, n0, grp;
     uint32_t a_goff[A_G], b_goff[B_G];
   };
+  Item cur, nxt;                                         // the current item and the one after it
   auto locate = [&](uint32_t w, Item& it) {
     int tile;
     work_of_index(w, n_work, p.tiles_m * p.tiles_n, n_groups, p.group, tile, it.grp);
@@ -110,6 +111,24 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     for (int c = 0; c < B_G; ++c)
       __builtin_amdgcn_global_load_lds((glb_void*)(p.B + it.b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
   };
+  // The same with the choice made at run time: the next k-tile of the current item, or (last)
+  // the first k-tile of the next item.  Offsets are selected value by value, never through a
+  // pointer to one of the two items (which would move them to scratch memory).
+  auto issue_tile_of = [&](bool last, int kt, int stage) {
+    const int k0 = last ? 0 : (kt + 1) * BK;
+    uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
+    uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
+#pragma unroll
+    for (int c = 0; c < A_G; ++c) {
+      const uint32_t off = last ? nxt.a_goff[c] : cur.a_goff[c];
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + off + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int c = 0; c < B_G; ++c) {
+      const uint32_t off = last ? nxt.b_goff[c] : cur.b_goff[c];
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + off + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
+    }
+  };
   // A group's R descriptors, one word per lane; fields are picked out with v_readlane.
   auto load_desc = [&](int grp) -> uint32_t {
     return lane < R * kMultiDescWords ? desc[(size_t)grp * (R * kMultiDescWords) + lane] : 0u;
@@ -130,44 +149,72 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
 #pragma unroll
     for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(s + b_rd + j * 4096 + slot);
   };
-  // one fragment set, R accumulator sets
-  auto mma_step = [&](const Frags& f) {
-    static_for<R * TM * TN>([&](auto t) {
-      constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
-      acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
-    });
-  };
-  // The same with `mid` (a fragment read for the next step) issued after the first few MFMAs:
-  // the read lands under the rest of the burst instead of being waited for in front of it.
-  auto mma_step_mid = [&](const Frags& f, auto&& mid) __attribute__((always_inline)) {
-    static_for<R * TM * TN>([&](auto t) {
-      constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
-      if constexpr (t == (R * TM * TN >= 8 ? 2 : 1)) {
-        __builtin_amdgcn_sched_barrier(0);
-        mid();
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
-    });
+  // One fragment set, R accumulator sets.  FIRST: the first MFMA step of an item, whose
+  // accumulators start from zero - the matrix instruction takes the constant 0 as its addend, so
+  // an item never spends vector instructions on clearing 128 accumulator registers.  `mid` (a
+  // fragment read for the next step) is issued after the first few MFMAs: the read lands under
+  // the rest of the burst instead of being waited for in front of it.
+  auto mma_step_mid = [&](const Frags& f, auto first, auto&& mid) __attribute__((always_inline)) {
+    constexpr bool FIRST = decltype(first)::value;
+    if constexpr (FIRST) {
+      // The R trials start from the same zero with the same fragments, so their first MFMAs are
+      // equal expressions and a compiler may compute one and copy it R - 1 times.  Every trial
+      // executes its own MFMAs: between trials one fragment register passes through an empty asm
+      // statement (no instruction, no extra register), after which the compiler can no longer
+      // take the next trial's inputs to be the previous trial's.
+      Frags q = f;
+      static_for<R * TM * TN>([&](auto t) {
+        constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+        if constexpr (t == (R * TM * TN >= 8 ? 2 : 1)) {
+          __builtin_amdgcn_sched_barrier(0);
+          mid();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (r > 0 && i == 0 && j == 0) asm volatile("" : "+v"(q.a[0]));
+        acc[r][i][j] = mfma_32x32x16<DT>(q.a[i], q.b[j],
+            f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f});
+      });
+    } else {
+      static_for<R * TM * TN>([&](auto t) {
+        constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+        if constexpr (t == (R * TM * TN >= 8 ? 2 : 1)) {
+          __builtin_amdgcn_sched_barrier(0);
+          mid();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
+      });
+    }
   };
 
   // ---- state of the current item
-  Item cur, nxt;
   uint32_t desc_cur, desc_nxt = 0;                       // lane-distributed descriptor words
   int n_act = 0;                                         // trials in this group
-  int trial[R], hook_step[R];                            // hook_step: -1 unless this wave owns the site
-  int next_hook = NO_HOOK;                               // earliest pending accumulator event of this wave
-  uint32_t is_operand = 0;                               // bit r: trial r's event is an operand patch (OPS)
-  int next_pre = NO_HOOK;                                // earliest pending operand patch of this wave (OPS)
-
+  // hook_step[r]: the MFMA step of trial r's event if this wave takes part in it (it owns the
+  // accumulator element, or its fragments hold the faulted operand word), else -1.
+  int trial[R], hook_step[R];
+  bool has_events = false;                               // some hook_step[r] >= 0
   auto desc_field = [&](int r, int field) -> uint32_t {
     return (uint32_t)__builtin_amdgcn_readlane((int)desc_cur, r * kMultiDescWords + field);
   };
+  // Fault-free value and magnitude sum of the element(s) of the faulted output ROW this lane
+  // holds, per trial with an event here: fetched when the item starts (they come from HBM, and
+  // an epilogue that fetched them trial after trial would expose one memory round trip each).
+  float cs_pre[R][TN], sa_pre[R][TN];
+  auto prefetch_row_golden = [&](auto rr) __attribute__((always_inline)) {
+    constexpr int r = rr;
+    const size_t row_off = (size_t)desc_field(r, 1) * (size_t)p.N;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const size_t idx = row_off + (size_t)min(cur.n0 + wn * WTN + l32 + 32 * j, p.N - 1);
+      cs_pre[r][j] = p.c_star[idx];
+      sa_pre[r][j] = p.s_abs[idx];
+    }
+  };
+
   auto decode = [&]() {
     n_act = min(R, n_fast - cur.grp * R);
-    next_hook = NO_HOOK;
-    is_operand = 0;
-    next_pre = NO_HOOK;
+    has_events = false;
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
       trial[r] = (int)desc_field(r, 0);
@@ -184,15 +231,16 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
             const int wl = isA ? l - wm * WTM : l - wn * WTN;
             if (wl >= 0 && wl < (isA ? WTM : WTN)) {
               hook_step[r] = hs;
-              is_operand |= 1u << r;
-              next_pre = min(next_pre, hs);
+              has_events = true;
+              if (isA) prefetch_row_golden(rr);
             }
           }
         } else if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
           const int wi = li - wm * WTM, wj = lj - wn * WTN;
           if (wi >= 0 && wi < WTM && wj >= 0 && wj < WTN) {
             hook_step[r] = hs;
-            next_hook = min(next_hook, hs);
+            has_events = true;
+            prefetch_row_golden(rr);
           }
         }
       }
@@ -235,65 +283,68 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
     // memory traffic pending here would make every iteration of the main loop wait for it.
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   };
-  // Accumulator faults due after MFMA step g of the item (at most one wave per trial owns one).
-  auto hooks = [&](int g) __attribute__((always_inline)) {
-    if (g == next_hook) {
-      int later = NO_HOOK;
-      static_for<R>([&](auto rr) {
-        constexpr int r = rr;
-        if (!((is_operand >> r) & 1u)) {
-          if (hook_step[r] == g) accumulator_fault(rr);
-          else if (hook_step[r] > g) later = min(later, hook_step[r]);
-        }
-      });
-      next_hook = later;
-    }
+  // Bit r: trial r's event falls on MFMA step g (and this wave takes part in it).
+  auto hit_mask = [&](int g) __attribute__((always_inline)) -> uint32_t {
+    uint32_t m = 0;
+    static_for<R>([&](auto rr) { m |= hook_step[rr] == g ? 1u << rr : 0u; });
+    return m;
   };
-  // MFMA step g of the item with operand patches (OPS): a trial whose faulted word is consumed
-  // here gets a copy of the fragment with that 16-bit word XORed (lane l holds row/column
-  // l % 32, k = 8*(l/32) .. +7 of the step, two k per register, even k in the low half).
-  auto mma_patched = [&](const Frags& f, int g) __attribute__((always_inline)) {
-    int later = NO_HOOK;
+  // Accumulator faults due after an MFMA step (at most one wave per trial owns one).
+  auto hooks = [&](uint32_t m) __attribute__((always_inline)) {
+    static_for<R>([&](auto rr) {
+      if ((m >> rr) & 1u) accumulator_fault(rr);
+    });
+  };
+  // Operand fault of trial r (OPS): XOR the faulted 16-bit word in the fragment registers the R
+  // trials share (lane l holds row / column l % 32, k = 8*(l/32) .. +7 of the step, two k per
+  // register, even k in the low half).  Called right before trial r's MFMAs of the step that
+  // consumes the word and again right after them, which restores the clean fragment: trial r
+  // gets exactly the MFMA inputs a run of its own would have staged, the other trials the clean
+  // ones, and the MFMAs themselves sit outside every branch.
+  auto toggle_operand = [&](Frags& f, auto rr) __attribute__((always_inline)) {
+    constexpr int r = rr;
+    const bool isA = desc_field(r, 5) == FI_SITE_A;
+    const int k = (int)(isA ? desc_field(r, 2) : desc_field(r, 1));
+    const int wl = isA ? (int)desc_field(r, 1) - cur.m0 - wm * WTM : (int)desc_field(r, 2) - cur.n0 - wn * WTN;
+    const int sel_lane = (wl & 31) + 32 * ((k >> 3) & 1);
+    const int sel_w = (k & 7) >> 1;
+    const uint32_t x = (lane == sel_lane) ? (desc_field(r, 4) & 0xFFFFu) << (16 * (k & 1)) : 0u;
+    // Every register is named statically (a register picked through a run-time index or a
+    // pointer to "the A or the B fragment" would move the fragments to scratch memory).
+    const uint32_t xa = isA ? x : 0u, xb = isA ? 0u : x;
+    static_for<TM * 4>([&](auto t) {
+      constexpr int ii = t / 4, w = t % 4;
+      f.a[ii][w] ^= (ii == (wl >> 5) && w == sel_w) ? xa : 0u;
+    });
+    static_for<TN * 4>([&](auto t) {
+      constexpr int jj = t / 4, w = t % 4;
+      f.b[jj][w] ^= (jj == (wl >> 5) && w == sel_w) ? xb : 0u;
+    });
+  };
+  // One MFMA step in a k-tile that holds an operand fault of this wave (OPS): bit r of m says
+  // that the step consumes trial r's faulted word.  The MFMAs stay in straight-line code; the
+  // toggles sit in cold blocks behind one scalar bit test each.
+  auto mma_step_ops = [&](Frags& f, uint32_t m, auto&& mid) __attribute__((always_inline)) {
+    constexpr int R_MID = TM * TN >= 2 ? 0 : 1;          // `mid` goes behind the first two MFMAs
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
-      Frags q = f;
-      if ((is_operand >> r) & 1u) {
-        if (hook_step[r] == g) {
-          const bool isA = desc_field(r, 5) == FI_SITE_A;
-          const int k = (int)(isA ? desc_field(r, 2) : desc_field(r, 1));
-          const int wl = isA ? (int)desc_field(r, 1) - cur.m0 - wm * WTM : (int)desc_field(r, 2) - cur.n0 - wn * WTN;
-          const int sel_lane = (wl & 31) + 32 * ((k >> 3) & 1);
-          const int sel_w = (k & 7) >> 1;
-          const uint32_t x = (lane == sel_lane) ? (desc_field(r, 4) & 0xFFFFu) << (16 * (k & 1)) : 0u;
-          if (isA) {
-            static_for<TM>([&](auto ii) {
-#pragma unroll
-              for (int w = 0; w < 4; ++w) q.a[ii][w] ^= (ii == (wl >> 5) && w == sel_w) ? x : 0u;
-            });
-          } else {
-            static_for<TN>([&](auto jj) {
-#pragma unroll
-              for (int w = 0; w < 4; ++w) q.b[jj][w] ^= (jj == (wl >> 5) && w == sel_w) ? x : 0u;
-            });
-          }
-        } else if (hook_step[r] > g) {
-          later = min(later, hook_step[r]);
-        }
-      }
+      if (__builtin_expect((m >> r) & 1u, 0)) toggle_operand(f, rr);
+      // A convergent no-op next to the MFMAs: the block holding them is then never duplicated
+      // into the two arms of the (repeated) test, which would put MFMAs behind a branch.
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_sched_barrier(0);
       static_for<TM * TN>([&](auto t) {
         constexpr int i = t / TN, j = t % TN;
-        acc[r][i][j] = mfma_32x32x16<DT>(q.a[i], q.b[j], acc[r][i][j]);
+        acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
       });
+      __builtin_amdgcn_sched_barrier(0);
+      if (__builtin_expect((m >> r) & 1u, 0)) toggle_operand(f, rr);
+      if constexpr (r == (R_MID < R ? R_MID : R - 1)) {
+        __builtin_amdgcn_sched_barrier(0);
+        mid();
+        __builtin_amdgcn_sched_barrier(0);
+      }
     });
-    next_pre = later;
-  };
-  auto mma_at = [&](const Frags& f, int g) __attribute__((always_inline)) {
-    if constexpr (OPS) {
-      if (g == next_pre) mma_patched(f, g);
-      else mma_step(f);
-    } else {
-      mma_step(f);
-    }
   };
 
   // ---- epilogue of the current item, trial by trial: detector, corrector, optional store;
@@ -407,10 +458,8 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
         const bool need_col = !op || desc_field(r, 5) == FI_SITE_B;
         uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
         float mx_pre = 0.0f, mx_post = 0.0f;
-        auto account = [&](float c, float Tv, int row, int col) __attribute__((always_inline)) {
-          const size_t idx = (size_t)row * p.N + col;
-          const float cs = p.c_star[idx];
-          const float tau = p.s_abs[idx] * 0.000244140625f;   // 2^-12, exact scaling
+        auto account = [&](float c, float Tv, float cs, float sabs) __attribute__((always_inline)) {
+          const float tau = sabs * 0.000244140625f;           // 2^-12, exact scaling
           const bool flag = !(fabsf(c) <= Tv);
           float cc = c;
           if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
@@ -446,7 +495,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
                 Tv = (v == sel_v) ? T[v] : Tv;
               }
               const int col = col_base + 32 * j;
-              if (lhi == sel_hi && (!need_col || col == site_col) && col < p.N) account(c, Tv, site_row, col);
+              if (lhi == sel_hi && (!need_col || col == site_col) && col < p.N) account(c, Tv, cs_pre[r][j], sa_pre[r][j]);
             }
           });
         } else {
@@ -458,7 +507,10 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-              if (col == site_col && row < p.M) account(t[v], T[v], row, col);
+              if (col == site_col && row < p.M) {
+                const size_t idx = (size_t)row * p.N + col;
+                account(t[v], T[v], p.c_star[idx], p.s_abs[idx]);
+              }
             }
           });
         }
@@ -501,90 +553,119 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_fi_multi_kernel(const GemmAr
   for (;;) {
     decode();
     if constexpr (EARLY_T) fetch_threshold_inputs();
-    static_for<R * TM * TN>([&](auto t) {
-      acc[t / (TM * TN)][(t / TN) % TM][t % TN] =
-          f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    });
 
     // One k-tile.  Every fragment read is issued inside the MFMA burst of the step before the
     // one that uses it (after the first few MFMAs), so a wave never waits for a read it has just
     // issued; the barrier sits before the last step, whose fragments the wave already holds, and
-    // the first fragments of the next tile are read inside that last burst.  LAST: the k-tile that
-    // ends an item - the tile loading into the other stage then belongs to the next item.
-    auto k_tile = [&](auto with_events, auto is_last, auto stage_c, int kt) __attribute__((always_inline)) {
+    // the first fragments of the next tile are read inside that last burst.  FIRST: the k-tile
+    // that opens an item (its first step starts the accumulators from zero).  LAST: the k-tile
+    // that ends an item - the tile loading into the other stage then belongs to the next item.
+    // EV: the k-tile holds an event of this wave - an accumulator fault after one of its steps,
+    // or (OPS) an operand word one of its steps consumes.
+    auto k_tile = [&](auto with_events, auto is_first, auto last_mode, auto stage_c, int kt) __attribute__((always_inline)) {
       constexpr bool EV = decltype(with_events)::value;
-      constexpr bool LAST = decltype(is_last)::value;
+      constexpr bool FIRST = decltype(is_first)::value;
+      // last_mode: 0 not the last k-tile, 1 the last, 2 decided at run time (items with events)
+      constexpr int LM = decltype(last_mode)::value;
+      static_assert(!(EV && FIRST), "items with events clear their accumulators up front");
       // stage_c: 0 or 1 when the LDS stage is known at compile time (the addresses of the
       // fragment reads then fold into immediates), -1 to use the running variable.
       constexpr int SC = decltype(stage_c)::value;
       if constexpr (SC >= 0) stage = SC;
-      const bool more = !LAST || has_next;                // a tile follows in the other stage
-      // The pending events are looked up once per k-tile, before the tile prefetch is issued
-      // (a look-up that has to wait for memory then waits for nothing else), and again only
-      // after an event has fired.
-      int np = NO_HOOK, nh = NO_HOOK;
+      const bool last = LM == 2 ? kt == nkt - 1 : LM == 1;
+      const bool more = !last || has_next;                // a tile follows in the other stage
       if constexpr (EV) {
-        np = OPS ? next_pre : NO_HOOK;
-        nh = next_hook;
-        __builtin_amdgcn_s_waitcnt(0x0F70);     // nothing else is in flight at this point
+        // Nothing of the rare paths stays in flight across the tile prefetch: the compiler
+        // places its waits statically, and a pending access would make the hot code wait for it.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if constexpr (!LAST) issue_tile(cur, kt + 1, stage ^ 1);
-      else if (has_next) issue_tile(nxt, 0, stage ^ 1);
+      if constexpr (LM == 0) issue_tile(cur, kt + 1, stage ^ 1);
+      else if constexpr (LM == 1) { if (has_next) issue_tile(nxt, 0, stage ^ 1); }
+      else if (more) issue_tile_of(last, kt, stage ^ 1);
       const uint8_t* s = smem + stage * STAGE;
       const uint8_t* s_other = smem + (stage ^ 1) * STAGE;
-      auto step = [&](const Frags& f, int g, auto&& mid) __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);
-        if (OPS && EV && g == np) {
-          mid();
-          mma_patched(f, g);
-          np = next_pre;
-          __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) here, on the rare path, not at the join
-        } else {
-          mma_step_mid(f, mid);
-        }
+      auto step = [&](Frags& f, int g, auto first, auto&& mid) __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (EV) {
-          if (g == nh) {
-            hooks(g);
-            nh = next_hook;
-            __builtin_amdgcn_s_waitcnt(0x0F70);
+          const uint32_t m = hit_mask(g);
+          if constexpr (OPS) {
+            mma_step_ops(f, m, mid);
+          } else {
+            mma_step_mid(f, first, mid);
+            __builtin_amdgcn_sched_barrier(0);
+            if (__builtin_expect(m != 0, 0)) hooks(m);
           }
+        } else {
+          mma_step_mid(f, first, mid);
         }
+        __builtin_amdgcn_sched_barrier(0);
       };
-      step(f0, 4 * kt, [&]() { read_frags(f1, s, 1); });
-      step(f1, 4 * kt + 1, [&]() { read_frags(f0, s, 2); });
-      step(f0, 4 * kt + 2, [&]() { read_frags(f1, s, 3); });
+      step(f0, 4 * kt, std::integral_constant<bool, FIRST>{}, [&]() { read_frags(f1, s, 1); });
+      step(f1, 4 * kt + 1, std::false_type{}, [&]() { read_frags(f0, s, 2); });
+      step(f0, 4 * kt + 2, std::false_type{}, [&]() { read_frags(f1, s, 3); });
       // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
       // once all waves are here the next tile has landed and this stage may be overwritten.
       if (more) __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads have landed
       __syncthreads();
-      step(f1, 4 * kt + 3, [&]() { if (more) read_frags(f0, s_other, 0); });
+      step(f1, 4 * kt + 3, std::false_type{}, [&]() { if (more) read_frags(f0, s_other, 0); });
       stage ^= 1;
     };
-    // The k-loop exists twice: waves with no event in this item - no accumulator fault and no
-    // operand patch of their own (nearly all) - run a copy free of event checks; the others run
-    // the copy with the hooks.  Both execute the same barriers, so waves of one workgroup may
-    // take different copies.
-    auto k_loop = [&](auto with_events) __attribute__((always_inline)) {
-      using dyn = std::integral_constant<int, -1>;
-      using st0 = std::integral_constant<int, 0>;
-      using st1 = std::integral_constant<int, 1>;
-      if ((nkt & 1) == 0 && stage == 0) {
+    using dyn = std::integral_constant<int, -1>;
+    using st0 = std::integral_constant<int, 0>;
+    using st1 = std::integral_constant<int, 1>;
+    using yes = std::true_type;
+    using no = std::false_type;
+    using mid_tile = std::integral_constant<int, 0>;
+    using last_tile = std::integral_constant<int, 1>;
+    using any_tile = std::integral_constant<int, 2>;
+    if (!has_events) {
+      // Nearly every wave of nearly every item: no event check anywhere.
+      if (nkt == 1) {
+        k_tile(no{}, yes{}, last_tile{}, dyn{}, 0);
+      } else if ((nkt & 1) == 0 && stage == 0) {
         // an even number of k-tiles: every item starts in stage 0 and the stages alternate statically
-        for (int kt = 0; kt + 2 < nkt; kt += 2) {
-          k_tile(with_events, std::false_type{}, st0{}, kt);
-          k_tile(with_events, std::false_type{}, st1{}, kt + 1);
+        k_tile(no{}, yes{}, mid_tile{}, st0{}, 0);
+        if (nkt > 2) {
+          k_tile(no{}, no{}, mid_tile{}, st1{}, 1);
+          for (int kt = 2; kt + 2 < nkt; kt += 2) {
+            k_tile(no{}, no{}, mid_tile{}, st0{}, kt);
+            k_tile(no{}, no{}, mid_tile{}, st1{}, kt + 1);
+          }
+          k_tile(no{}, no{}, mid_tile{}, st0{}, nkt - 2);
         }
-        k_tile(with_events, std::false_type{}, st0{}, nkt - 2);
-        k_tile(with_events, std::true_type{}, st1{}, nkt - 1);
+        k_tile(no{}, no{}, last_tile{}, st1{}, nkt - 1);
       } else {
-        for (int kt = 0; kt + 1 < nkt; ++kt) k_tile(with_events, std::false_type{}, dyn{}, kt);
-        k_tile(with_events, std::true_type{}, dyn{}, nkt - 1);
+        k_tile(no{}, yes{}, mid_tile{}, dyn{}, 0);
+        for (int kt = 1; kt + 1 < nkt; ++kt) k_tile(no{}, no{}, mid_tile{}, dyn{}, kt);
+        k_tile(no{}, no{}, last_tile{}, dyn{}, nkt - 1);
       }
-    };
-    if (next_hook == NO_HOOK && (!OPS || next_pre == NO_HOOK)) k_loop(std::false_type{});
-    else k_loop(std::true_type{});
+    } else {
+      // A wave with events in this item alternates runs of check-free k-tiles with single
+      // k-tiles of the checking copy, one per k-tile that holds an event.  (A choice between the
+      // two copies inside one loop body - MFMAs over all accumulators in both arms of a branch -
+      // makes the register allocator spill; a loop followed by a conditional tile does not.)
+      // Both copies execute the same barriers, so the waves of a workgroup may take different
+      // ones.  These copies keep to the running LDS stage, find out at run time whether a k-tile
+      // is the item's last, and the accumulators are cleared up front: rare path, and every copy
+      // of a k-tile costs code.
+      static_for<R * TM * TN>([&](auto t) {
+        acc[t / (TM * TN)][(t / TN) % TM][t % TN] =
+            f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      });
+      for (int kt = 0; kt < nkt;) {
+        int ev_tile = nkt;                                // first k-tile at or after kt with an event
+        static_for<R>([&](auto rr) {
+          const int t = hook_step[rr] >> 2;               // -1 >> 2 == -1: no event
+          ev_tile = (t >= kt && t < ev_tile) ? t : ev_tile;
+        });
+        for (; kt < ev_tile; ++kt) k_tile(no{}, no{}, any_tile{}, dyn{}, kt);
+        if (kt < nkt) {
+          k_tile(yes{}, no{}, any_tile{}, dyn{}, kt);
+          ++kt;
+        }
+      }
+    }
 
     if constexpr (!EARLY_T) fetch_threshold_inputs();
     epilogue();

@@ -20,12 +20,15 @@ constexpr TileCfg kCfg[] = {
 };
 constexpr int kNumCfg = sizeof(kCfg) / sizeof(kCfg[0]);
 
-// R trials share one staged BM x BN tile (see gemm_fi_multi.hpp).
-struct MultiCfg { int r, bm, bn, wm, wn; };
+// R trials share one staged BM x BN tile (see gemm_fi_multi.hpp); `wgs` persistent workgroups
+// per compute unit (two workgroups of four waves put one wave of each on every SIMD, so the
+// barriers and the epilogue of one run under the MFMAs of the other).
+struct MultiCfg { int r, bm, bn, wm, wn, wgs; };
 constexpr MultiCfg kMulti[] = {
-    {4, 128, 128, 4, 2},   // each wave 32 x 64 for 4 trials
-    {2, 128, 128, 4, 2},   // each wave 32 x 64 for 2 trials
-    {8, 128, 64, 4, 2},    // each wave 32 x 32 for 8 trials: narrow outputs
+    {4, 128, 128, 4, 2, 1},   // each wave 32 x 64 for 4 trials
+    {2, 128, 128, 4, 2, 1},   // each wave 32 x 64 for 2 trials
+    {8, 128, 64, 4, 2, 1},    // each wave 32 x 32 for 8 trials
+    {8, 64, 64, 2, 2, 2},     // each wave 32 x 32 for 8 trials, two workgroups per compute unit
 };
 constexpr int kNumMulti = sizeof(kMulti) / sizeof(kMulti[0]);
 
@@ -37,8 +40,8 @@ constexpr int kNumMulti = sizeof(kMulti) / sizeof(kMulti[0]);
   hipError_t launch_multi_d##DT##_c##MC(const GemmArgs& a, int n_blocks, hipStream_t s);
 FI_DECLARE_SINGLE(0, 0) FI_DECLARE_SINGLE(0, 1) FI_DECLARE_SINGLE(0, 2)
 FI_DECLARE_SINGLE(1, 0) FI_DECLARE_SINGLE(1, 1) FI_DECLARE_SINGLE(1, 2)
-FI_DECLARE_MULTI(0, 0) FI_DECLARE_MULTI(0, 1) FI_DECLARE_MULTI(0, 2)
-FI_DECLARE_MULTI(1, 0) FI_DECLARE_MULTI(1, 1) FI_DECLARE_MULTI(1, 2)
+FI_DECLARE_MULTI(0, 0) FI_DECLARE_MULTI(0, 1) FI_DECLARE_MULTI(0, 2) FI_DECLARE_MULTI(0, 3)
+FI_DECLARE_MULTI(1, 0) FI_DECLARE_MULTI(1, 1) FI_DECLARE_MULTI(1, 2) FI_DECLARE_MULTI(1, 3)
 #undef FI_DECLARE_SINGLE
 #undef FI_DECLARE_MULTI
 

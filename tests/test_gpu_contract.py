@@ -72,7 +72,7 @@ def test_reserve_then_capture_without_an_eager_call_first():
     plan.destroy()
 
 
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
 def test_rows_of_all_maximal_same_sign_products_are_never_flagged(cfg, fmt):
     # The worst case for "a clean element is not flagged": every product of a row equals

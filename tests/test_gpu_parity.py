@@ -60,7 +60,7 @@ def _mixed_faults(Aw, Bw, fmt, kb, n, seed):
 
 
 @pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("shape", [(300, 200, 192, 32), (257, 65, 128, 64), (96, 40, 96, 48), (64, 64, 64, 16)])
 def test_exact_regime_everything_bit_equal(fmt, cfg, shape):
     # Small-integer operands: every partial sum is exact, so summation order cannot matter and
@@ -150,7 +150,7 @@ def test_tiny_campaign():
     assert sum(s["gpu_counts"]) == 64 and min(s["gpu_counts"]) > 0
 
 
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6])
 def test_tiny_campaign_every_tile_shape_many_trials(cfg):
     w = wl.tiny()
     _campaign_parity(w, n_trials=1500, cfg=cfg, policies=(wl.CORRECT_ZERO, wl.CORRECT_RECOMPUTE, wl.CORRECT_NONE))
@@ -190,7 +190,7 @@ def test_zero_fault_trials_are_masked_on_every_workload():
         assert not recs["max_dev_pre"].any() and (gu.cls_of(recs) == fi.MASKED).all()
         # the fault-free result does not depend on the workgroup tile: a clean trial run with any
         # other tile shape is still bit-identical to the plan's C*
-        for cfg in (0, 1, 2, 3, 4, 5):
+        for cfg in (0, 1, 2, 3, 4, 5, 6):
             plan.tune(cfg, 3)
             recs = gu.gpu_campaign(plan, faults, wl.CORRECT_ZERO)
             assert not recs["n_bitdiff"].any() and not recs["n_flagged"].any(), (w.name, cfg)

@@ -42,7 +42,7 @@ def _safe_product_faults(Aw, Bw, fmt, n, seed):
 
 
 @pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
-@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("shape", [(300, 200, 192, 32), (257, 65, 128, 64), (96, 40, 96, 48), (64, 64, 64, 16)])
 def test_exact_regime_product_faults_bit_equal(fmt, cfg, shape):
     M, N, K, kb = shape
