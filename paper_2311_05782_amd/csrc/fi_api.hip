@@ -104,10 +104,15 @@ hipError_t launch_multi(int dtype, int mcfg, const GemmArgs& a, int n_blocks, hi
   return hipErrorInvalidValue;
 }
 
-// The multi-trial kernel needs whole 64-wide k-tiles.
+// The multi-trial kernel needs whole 64-wide k-tiles.  Eight trials per tile carry the least
+// operand traffic per flop.  On the largest problems one eight-wave workgroup per CU on a
+// 128 x 64 tile measured fastest (less traffic into LDS per flop); below that two four-wave
+// workgroups on 64 x 64 tiles win, because the barriers and the per-item epilogue of one run
+// under the MFMAs of the other (+2 .. 16 % on 1024^3, 512 x 3072 x 768 and 3136 x 64 x 576).
 int pick_multi(const fi_plan_desc& d) {
   if (d.K % 64 != 0) return -1;
-  return 2;   // 8 trials per 128 x 64 tile: the least operand traffic per flop, measured fastest
+  const double work = (double)d.M * (double)d.N * (double)d.K;
+  return work >= 34359738368.0 /* 2^35 */ ? 2 : 3;
 }
 
 int pick_cfg(const fi_plan_desc& d) {

@@ -444,9 +444,13 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     });
     // Deviation counters of the trials whose fault can reach an element this wave holds (rare):
     // the wave owning the element, or the waves holding its output row (A) / column (B).
+    // Counts are sums of lane masks (ballot + popcount: no cross-lane traffic); the two maxima
+    // of all trials are reduced together at the end, so the shuffles' latencies overlap.
     uint32_t owned = 0;
     static_for<R>([&](auto rr) { owned |= hook_step[rr] >= 0 ? 1u << rr : 0u; });
     if (owned == 0) return;
+    float mxp[R], mxq[R];                                   // per lane: largest deviation before / after correction
+    static_for<R>([&](auto rr) { mxp[rr] = 0.0f; mxq[rr] = 0.0f; });
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
       if ((owned >> r) & 1u) {
@@ -456,9 +460,10 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
         const bool op = OPS && ((desc_field(r, 3) >> 29) & 1u);
         const bool need_row = !op || desc_field(r, 5) == FI_SITE_A;
         const bool need_col = !op || desc_field(r, 5) == FI_SITE_B;
-        uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
+        uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;   // wave-uniform
         float mx_pre = 0.0f, mx_post = 0.0f;
-        auto account = [&](float c, float Tv, float cs, float sabs) __attribute__((always_inline)) {
+        // `act`: this lane's element is one the fault can reach.  Called by all lanes together.
+        auto account = [&](bool act, float c, float Tv, float cs, float sabs) __attribute__((always_inline)) {
           const float tau = sabs * 0.000244140625f;           // 2^-12, exact scaling
           const bool flag = !(fabsf(c) <= Tv);
           float cc = c;
@@ -466,16 +471,16 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
           if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cs;
           const float dpre = finite_or_inf(fabsf(c - cs));
           const float dpost = finite_or_inf(fabsf(cc - cs));
-          const bool changed = __float_as_uint(c) != __float_as_uint(cs);
-          n_bit += changed ? 1u : 0u;
-          n_pre += !(dpre <= tau) ? 1u : 0u;
-          n_post += !(dpost <= tau) ? 1u : 0u;
-          mx_pre = fmaxf(mx_pre, dpre);
-          mx_post = fmaxf(mx_post, dpost);
+          const bool changed = act && __float_as_uint(c) != __float_as_uint(cs);
+          n_bit += (uint32_t)__builtin_popcountll(__ballot(changed));
+          n_pre += (uint32_t)__builtin_popcountll(__ballot(act && !(dpre <= tau)));
+          n_post += (uint32_t)__builtin_popcountll(__ballot(act && !(dpost <= tau)));
+          mx_pre = fmaxf(mx_pre, act ? dpre : 0.0f);
+          mx_post = fmaxf(mx_post, act ? dpost : 0.0f);
           const float band = fmaxf(2.0f * tau, Tv * 0.015625f);
           const float mag = fabsf(c);
-          n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - Tv) <= band) ? 1u : 0u;
-          n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
+          n_bT += (uint32_t)__builtin_popcountll(__ballot(changed && mag <= 3.4028234e38f && fabsf(mag - Tv) <= band));
+          n_btau += (uint32_t)__builtin_popcountll(__ballot(changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau));
         };
         if (need_row) {
           // One row: it lives in one 32-row tile, one register index and one lane half
@@ -495,35 +500,57 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                 Tv = (v == sel_v) ? T[v] : Tv;
               }
               const int col = col_base + 32 * j;
-              if (lhi == sel_hi && (!need_col || col == site_col) && col < p.N) account(c, Tv, cs_pre[r][j], sa_pre[r][j]);
+              account(lhi == sel_hi && (!need_col || col == site_col) && col < p.N, c, Tv, cs_pre[r][j], sa_pre[r][j]);
             }
           });
         } else {
+          // One column: the lanes holding it read their rows' golden values; the other lanes read
+          // their own columns of the same rows (same cache lines) and count nothing.
           static_for<TM * TN>([&](auto tt) {
             constexpr int i = tt / TN, j = tt % TN;
             const f32x16 T = thresholds(tt);
             const f32x16 t = acc[r][i][j];
             const int col = col_base + 32 * j;
+            float cs[16], sa[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
-              if (col == site_col && row < p.M) {
-                const size_t idx = (size_t)row * p.N + col;
-                account(t[v], T[v], p.c_star[idx], p.s_abs[idx]);
-              }
+              const size_t idx = (size_t)min(row, p.M - 1) * p.N + min(col, p.N - 1);
+              cs[v] = p.c_star[idx];
+              sa[v] = p.s_abs[idx];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+              account(col == site_col && row < p.M, t[v], T[v], cs[v], sa[v]);
             }
           });
         }
-        uint32_t sum;
-        sum = wave_sum(n_bit);  if (lane == 0 && sum) atomicAdd(&res->n_bitdiff, sum);
-        sum = wave_sum(n_pre);  if (lane == 0 && sum) atomicAdd(&res->n_dev_pre, sum);
-        sum = wave_sum(n_post); if (lane == 0 && sum) atomicAdd(&res->n_dev_post, sum);
-        sum = wave_sum(n_bT);   if (lane == 0 && sum) atomicAdd(&res->n_border_T, sum);
-        sum = wave_sum(n_btau); if (lane == 0 && sum) atomicAdd(&res->n_border_tau, sum);
-        sum = wave_max(__float_as_uint(mx_pre));
-        if (lane == 0 && sum) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_pre), sum);
-        sum = wave_max(__float_as_uint(mx_post));
-        if (lane == 0 && sum) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_post), sum);
+        if (lane == 0) {
+          if (n_bit) atomicAdd(&res->n_bitdiff, n_bit);
+          if (n_pre) atomicAdd(&res->n_dev_pre, n_pre);
+          if (n_post) atomicAdd(&res->n_dev_post, n_post);
+          if (n_bT) atomicAdd(&res->n_border_T, n_bT);
+          if (n_btau) atomicAdd(&res->n_border_tau, n_btau);
+        }
+        mxp[r] = mx_pre;
+        mxq[r] = mx_post;
+      }
+    });
+    // non-negative floats (and +Inf) order like their words
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      static_for<R>([&](auto rr) {
+        mxp[rr] = fmaxf(mxp[rr], __shfl_xor(mxp[rr], o, 64));
+        mxq[rr] = fmaxf(mxq[rr], __shfl_xor(mxq[rr], o, 64));
+      });
+    }
+    static_for<R>([&](auto rr) {
+      constexpr int r = rr;
+      if (((owned >> r) & 1u) && lane == 0) {
+        fi_trial_result* res = p.results + trial[r];
+        if (mxp[r] > 0.0f) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_pre), __float_as_uint(mxp[r]));
+        if (mxq[r] > 0.0f) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_post), __float_as_uint(mxq[r]));
       }
     });
   };

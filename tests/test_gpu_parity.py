@@ -253,6 +253,8 @@ def test_nonfinite_operands_are_a_plan_error():
 def test_plan_describe_names_the_kernels_in_use():
     Aw, Bw = wl.gaussian(128, 128, 128, orc.BF16, seed=2)
     plan = gu.make_plan(Aw, Bw, 64, orc.BF16)
+    assert "gemm_fi_multi_kernel<bf16, R=8, 64x64" in plan.describe()      # a small problem
+    plan.tune(5)
     assert "gemm_fi_multi_kernel<bf16, R=8, 128x64" in plan.describe()
     plan.tune(1)
     assert plan.describe() == "gemm_fi_kernel<bf16, 128x128, 256 threads>"
