@@ -150,11 +150,13 @@ fi_status fi_plan_destroy(fi_plan* plan);
 fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr);
 
 /* Optional tuning.  tile_config: -1 keep, else an index into the kernel table:
- *   0..2  one trial per workgroup on a 256x256, 128x128 or 256x64 output tile
- *         (every fault kind, any K);
- *   3..6  R trials per workgroup sharing one staged operand tile: R=4 on 128x128, R=2 on
+ *   0..2  one trial per work item on a 256x256, 128x128 or 256x64 output tile (every fault
+ *         kind, any K).  When K % 64 == 0 the first two run as persistent workgroups - the
+ *         item loop of the multi-trial kernel below with one trial per item (also reachable
+ *         as 7 and 8) - and fi_gemm_propagate_batch uses the same persistent kernel.
+ *   3..8  R trials per workgroup sharing one staged operand tile: R=4 on 128x128, R=2 on
  *         128x128, R=8 on 128x64 (the default when K % 64 == 0), and, with two workgroups of
- *         four waves per compute unit instead of one of eight, R=8 on 64x64.
+ *         four waves per compute unit instead of one of eight, R=8 on 64x64; 7 and 8: R=1 (see above).
  *         The batch is split on the device into the trials whose fault leaves the operands
  *         alone and the operand-fault trials; the latter run in a second instantiation that
  *         XORs the faulted word in the fragment registers around the faulted trial's MFMAs.
@@ -247,7 +249,8 @@ fi_status fi_activation_round(uint32_t dtype, const float* d_c, uint64_t n, uint
  * plan's A word for word reproduce the rows of C* bit for bit.  A trial's operand may hold
  * Inf or NaN (they propagate as IEEE and are flagged).  d_c_out as in fi_gemm_inject_batch.
  * The caller owns d_a_stack and keeps it unmodified until the work has run.  All 2*M*N*K
- * flops of every trial are executed (one trial per workgroup tile; tile configurations 0..2).
+ * flops of every trial are executed (one trial per work item; tile configurations 0..2, of
+ * which 0 - the default - and 1 run as persistent workgroups when K % 64 == 0).
  * Errors: INVALID_ARG (NULLs, n_trials == 0, bad policy, trial_stride too small),
  * UNSUPPORTED (alignment; tiles x trials >= 2^31). */
 fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t trial_stride,

@@ -20,7 +20,7 @@ LIB = os.path.join(HERE, "libfi_gfx950.so")
 HEADERS = ["gemm_fi.hpp", "gemm_fi_multi.hpp", "aux_kernels.hpp", "tile_cfg.hpp"]
 SOURCES = ["fi_api.hip", "gemm_inst.hip"]
 # (family, dtype, cfg): family 0 = one trial per work item, 1 = R trials per work item
-INSTANCES = ([(1, dt, cfg) for dt in (0, 1) for cfg in (0, 1, 2, 3)] +
+INSTANCES = ([(1, dt, cfg) for dt in (0, 1) for cfg in (0, 1, 2, 3, 4, 5)] +
              [(0, dt, cfg) for dt in (0, 1) for cfg in (0, 1, 2)])
 
 

@@ -74,6 +74,7 @@ struct fi_plan {
   int cfg = 0;                       // index into kCfg
   int cfg_affected = 0;              // index into kCfg for the affected-tiles-only campaign
   int mcfg = -1;                     // index into kMulti, or -1: every trial through the single-trial kernel
+  int prop_cfg = -1;                 // index into kMulti for the next-layer batch, or -1: single-trial kernel
   int group = 32;                    // trials sharing a tile back to back
   int device = 0;
   std::vector<BatchScratch> batch;   // per stream, see BatchScratch
@@ -98,8 +99,16 @@ hipError_t launch_gemm(int mode, int dtype, int cfg, const GemmArgs& a, int n_bl
 hipError_t launch_multi(int dtype, int mcfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
 #define FI_CASE(DT, MC) \
   if (dtype == DT && mcfg == MC) return fi::launch_multi_d##DT##_c##MC(a, n_blocks, s)
-  FI_CASE(0, 0); FI_CASE(0, 1); FI_CASE(0, 2); FI_CASE(0, 3);
-  FI_CASE(1, 0); FI_CASE(1, 1); FI_CASE(1, 2); FI_CASE(1, 3);
+  FI_CASE(0, 0); FI_CASE(0, 1); FI_CASE(0, 2); FI_CASE(0, 3); FI_CASE(0, 4); FI_CASE(0, 5);
+  FI_CASE(1, 0); FI_CASE(1, 1); FI_CASE(1, 2); FI_CASE(1, 3); FI_CASE(1, 4); FI_CASE(1, 5);
+#undef FI_CASE
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_prop(int dtype, int mcfg, const GemmArgs& a, int n_blocks, hipStream_t s) {
+#define FI_CASE(DT, MC) \
+  if (dtype == DT && mcfg == MC) return fi::launch_prop_d##DT##_c##MC(a, n_blocks, s)
+  FI_CASE(0, 4); FI_CASE(0, 5); FI_CASE(1, 4); FI_CASE(1, 5);
 #undef FI_CASE
   return hipErrorInvalidValue;
 }
@@ -485,6 +494,7 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   p->cfg = pick_cfg(d);
   p->cfg_affected = d.N <= 64 ? 2 : 1;   // small tiles: only the reached part is of interest
   p->mcfg = pick_multi(d);
+  p->prop_cfg = d.K % 64 == 0 ? fi::kMultiOneTrial[0] : -1;
   p->group = 32;
   (void)hipGetDevice(&p->device);
   if (hipDeviceGetAttribute(&p->n_cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess ||
@@ -549,8 +559,17 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
   if (trial_group > 0) plan->group = trial_group;
   // C* does not depend on the tile shape: every shape feeds each output element the same
   // sequence of 16-wide MFMA steps in ascending k.
-  if (tile_config >= kNumCfg) plan->mcfg = tile_config - kNumCfg;
-  else if (tile_config >= 0) { plan->cfg = tile_config; plan->cfg_affected = tile_config; plan->mcfg = -1; }
+  if (tile_config >= kNumCfg) {
+    plan->mcfg = tile_config - kNumCfg;
+    if (kMulti[plan->mcfg].r == 1) plan->prop_cfg = plan->mcfg;
+  } else if (tile_config >= 0) {
+    plan->cfg = tile_config; plan->cfg_affected = tile_config;
+    // One trial per work item.  With whole 64-wide k-tiles the 256x256 and 128x128 shapes run as
+    // persistent workgroups (the multi-trial kernel's item loop with one trial per item).
+    const bool persistent = plan->d.K % 64 == 0 && tile_config < 2;
+    plan->mcfg = persistent ? fi::kMultiOneTrial[tile_config] : -1;
+    plan->prop_cfg = persistent ? fi::kMultiOneTrial[tile_config] : -1;
+  }
   (void)stream;
   return FI_OK;
 }
@@ -579,6 +598,10 @@ fi_status fi_plan_describe(const fi_plan* plan, char* h_buf, uint64_t n) {
   const char* dt = plan->d.dtype == FI_BF16 ? "bf16" : "fp16";
   if (plan->mcfg >= 0) {
     const MultiCfg m = kMulti[plan->mcfg];
+    if (m.r == 1)
+      snprintf(h_buf, n, "gemm_fi_multi_kernel<%s, one trial per item, %dx%d, %d threads, persistent x%d per CU>", dt,
+               m.bm, m.bn, m.wm * m.wn * 64, m.wgs);
+    else
     snprintf(h_buf, n, "gemm_fi_multi_kernel<%s, R=%d, %dx%d, %d threads, persistent x%d per CU> (a second, "
              "operand-patching instantiation for operand faults)", dt, m.r, m.bm, m.bn, m.wm * m.wn * 64, m.wgs);
   } else {
@@ -683,6 +706,11 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
     return fail(FI_INVALID_ARG, "trial_stride %llu is smaller than one operand ((M-1)*lda + K elements)",
                 (unsigned long long)trial_stride);
   GemmArgs a = base_args(plan);
+  if (plan->prop_cfg >= 0) {
+    const MultiCfg mc = kMulti[plan->prop_cfg];
+    a.tiles_m = (a.M + mc.bm - 1) / mc.bm;
+    a.tiles_n = (a.N + mc.bn - 1) / mc.bn;
+  }
   const uint64_t blocks = (uint64_t)a.tiles_m * a.tiles_n * n_trials;
   if (blocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
   hipStream_t s = as_stream(stream);
@@ -693,12 +721,20 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
   a.A = static_cast<const uint16_t*>(d_a_stack);
   a.a_trial_stride = trial_stride;
   a.n_trials = (int)n_trials;
-  // Trials share B but not A: keep a trial's tiles close together in the dispatch order (its A
-  // panels are then re-read from the XCD's L2, not from HBM) and only a few trials per B tile.
-  a.group = plan->group < 3 ? plan->group : 3;
+  // Trials share B but not A: a trial's tiles follow each other in the work list, so the column
+  // tiles of one A panel run at the same time on one XCD and the panel comes from HBM once
+  // (measured on 512 x 768 x 3072, 256 trials: 0.72 ms against 0.83 ms with three trials per tile).
+  a.group = 1;
   a.results = d_results;
   a.c_out = d_c_out;
   a.policy = (int)policy;
+  if (plan->prop_cfg >= 0) {
+    // persistent workgroups walking (tile, trial) items
+    const MultiCfg mc = kMulti[plan->prop_cfg];
+    const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8) * (uint64_t)mc.wgs;
+    FI_HIP(launch_prop((int)plan->d.dtype, plan->prop_cfg, a, (int)(blocks < cus ? blocks : cus), s));
+    return FI_OK;
+  }
   FI_HIP(launch_gemm(fi::MODE_PROPAGATE, (int)plan->d.dtype, plan->cfg, a, (int)blocks, s));
   return FI_OK;
 }

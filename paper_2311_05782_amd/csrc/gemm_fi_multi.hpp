@@ -40,8 +40,17 @@ namespace fi {
 
 constexpr int kMultiDescWords = 6;   // trial, row, col, event, w0, w1
 
-template <int DT, int R, int BM, int BN, int WM, int WN, bool OPS>
+// VAR: which part of the work this instantiation takes.
+enum { VAR_PLAIN = 0, VAR_OPERAND = 1, VAR_PROPAGATE = 2 };
+
+template <int DT, int R, int BM, int BN, int WM, int WN, int VAR>
 __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const GemmArgs p) {
+  constexpr bool OPS = VAR == VAR_OPERAND;
+  // PROP: the next layer of a two-layer workload.  Work item = (output tile, trial); trial t
+  // stages ITS OWN A operand (A + t * a_trial_stride) and the shared B, no fault is injected,
+  // and every output element is compared with the fault-free result.
+  constexpr bool PROP = VAR == VAR_PROPAGATE;
+  static_assert(!PROP || R == 1, "trials of the next layer share no A operand: one trial per item");
   constexpr int BK = 64;
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -52,6 +61,11 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   // Fetch the epilogue's threshold inputs when an item starts (hides their latency) where the
   // register budget has room for them; else when the epilogue starts.
   constexpr bool EARLY_T = TM * TN == 1;
+  // Large wave tiles leave few registers: the next item is located (its staging offsets
+  // computed, its descriptors requested) just before the current item's last k-tile instead of
+  // a whole item ahead, and golden values are fetched in the epilogue instead of up front.
+  constexpr bool LATE_NEXT = TM * TN >= 4;
+  constexpr bool PRE_GOLDEN = R >= 4;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a multiple of the 32x32 MFMA");
   static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "row groups divide among the waves");
   static_assert(R * TM * TN * 16 <= 128, "accumulators fit half the register file");
@@ -67,8 +81,9 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
 
   // ---- work list: n_tiles x ceil(n_fast / R) items, walked with the grid as stride
   // OPS: the second part of the batch; its descriptors follow the first part's, padded to 8.
-  const int n_fast = (int)p.part_counts[OPS ? 1 : 0];
-  const uint32_t* const desc = p.desc + (OPS ? (size_t)((p.part_counts[0] + 7u) & ~7u) * kMultiDescWords : 0);
+  const int n_fast = PROP ? p.n_trials : (int)p.part_counts[OPS ? 1 : 0];
+  const uint32_t* const desc =
+      PROP ? nullptr : p.desc + (OPS ? (size_t)((p.part_counts[0] + 7u) & ~7u) * kMultiDescWords : 0);
   const int n_groups = (n_fast + R - 1) / R;
   const uint32_t n_work = (uint32_t)(p.tiles_m * p.tiles_n) * (uint32_t)n_groups;
   uint32_t w_cur = blockIdx.x;
@@ -82,6 +97,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   struct Item {
     int m0, n0, grp;
     uint32_t a_goff[A_G], b_goff[B_G];
+    size_t a_base;                                       // PROP: element offset of the trial's A operand
   };
   Item cur, nxt;                                         // the current item and the one after it
   auto locate = [&](uint32_t w, Item& it) {
@@ -89,6 +105,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     work_of_index(w, n_work, p.tiles_m * p.tiles_n, n_groups, p.group, tile, it.grp);
     it.m0 = (tile / p.tiles_n) * BM;
     it.n0 = (tile % p.tiles_n) * BN;
+    it.a_base = PROP ? (size_t)it.grp * (size_t)p.a_trial_stride : 0;
 #pragma unroll
     for (int c = 0; c < A_G; ++c) {
       const int row = (wave * A_G + c) * 8 + lrow;
@@ -101,37 +118,40 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     }
   };
   auto issue_tile = [&](const Item& it, int kt, int stage) {
-    const int k0 = kt * BK;
+    const uint32_t k0 = (uint32_t)(kt * BK);
+    // the trial's operand base is wave-uniform; the per-lane part of an address stays 32 bits wide
+    const uint16_t* const Ab = PROP ? p.A + it.a_base : p.A;
     uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
     uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
 #pragma unroll
     for (int c = 0; c < A_G; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + it.a_goff[c] + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void*)(Ab + (it.a_goff[c] + k0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
 #pragma unroll
     for (int c = 0; c < B_G; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + it.b_goff[c] + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + (it.b_goff[c] + k0)), (lds_void*)(sB + c * 1024), 16, 0, 0);
   };
   // The same with the choice made at run time: the next k-tile of the current item, or (last)
   // the first k-tile of the next item.  Offsets are selected value by value, never through a
   // pointer to one of the two items (which would move them to scratch memory).
   auto issue_tile_of = [&](bool last, int kt, int stage) {
-    const int k0 = last ? 0 : (kt + 1) * BK;
+    const uint32_t k0 = last ? 0u : (uint32_t)((kt + 1) * BK);
     uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
     uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
 #pragma unroll
     for (int c = 0; c < A_G; ++c) {
       const uint32_t off = last ? nxt.a_goff[c] : cur.a_goff[c];
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + off + k0), (lds_void*)(sA + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + (off + k0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
     }
 #pragma unroll
     for (int c = 0; c < B_G; ++c) {
       const uint32_t off = last ? nxt.b_goff[c] : cur.b_goff[c];
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + off + k0), (lds_void*)(sB + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + (off + k0)), (lds_void*)(sB + c * 1024), 16, 0, 0);
     }
   };
   // A group's R descriptors, one word per lane; fields are picked out with v_readlane.
   auto load_desc = [&](int grp) -> uint32_t {
-    return lane < R * kMultiDescWords ? desc[(size_t)grp * (R * kMultiDescWords) + lane] : 0u;
+    if constexpr (PROP) return lane == 0 ? (uint32_t)grp : lane == 3 ? 0xFFFFFFFFu : 0u;   // {trial, -, -, no event}
+    else return lane < R * kMultiDescWords ? desc[(size_t)grp * (R * kMultiDescWords) + lane] : 0u;
   };
 
   // ---- fragments and accumulators
@@ -203,6 +223,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   float cs_pre[R][TN], sa_pre[R][TN];
   auto prefetch_row_golden = [&](auto rr) __attribute__((always_inline)) {
     constexpr int r = rr;
+    if constexpr (!PRE_GOLDEN) return;
     const size_t row_off = (size_t)desc_field(r, 1) * (size_t)p.N;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -219,7 +240,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
       constexpr int r = rr;
       trial[r] = (int)desc_field(r, 0);
       hook_step[r] = -1;
-      const int ev = (int)desc_field(r, 3);
+      const int ev = PROP ? -1 : (int)desc_field(r, 3);
       const int hs = ev & 0xFFFF;
       if (r < n_act && ev >= 0) {
         const int li = (int)desc_field(r, 1) - cur.m0, lj = (int)desc_field(r, 2) - cur.n0;
@@ -374,12 +395,16 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
       constexpr int i = tt / TN, j = tt % TN;
       const int col = col_base + 32 * j;
       f32x16 T;
+      // large wave tiles: the inputs of one 32 x 32 tile at a time, when it is looked at
+      const float cb_here = EARLY_T ? cbj[j] : p.cb[min(col, p.N - 1)];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
+        const f32x4 kra_here =
+            EARLY_T ? kra4[i][q] : *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int row = row_base + 32 * i + 8 * q + e;
-          const float t = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra4[i][q][e], cbj[j]), p.gamma);
+          const float t = p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra_here[e], cb_here), p.gamma);
           T[4 * q + e] = (row < p.M && col < p.N) ? t : __builtin_inff();
         }
       }
@@ -442,6 +467,101 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
       constexpr int r = rr;
       if (r < n_act && n_flag[r] != 0 && lane == 0) atomicAdd(&p.results[trial[r]].n_flagged, n_flag[r]);
     });
+    if constexpr (PROP) {
+      // Every element of the trial's output against the fault-free result.  Two phases per
+      // 32 x 32 tile: the fault-free words are fetched one tile ahead and compared bit for bit
+      // (most tiles of most trials are untouched by what the previous layer's fault changed: no
+      // counter can move there); only a tile with a differing (or NaN) element runs the full
+      // accounting, four rows at a time so that it needs few registers.
+      uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
+      float mx_pre = 0.0f, mx_post = 0.0f;
+      f32x16 cs_buf[2];
+      auto load_golden = [&](auto tt, f32x16& dst) __attribute__((always_inline)) {
+        constexpr int i = tt / TN, j = tt % TN;
+        const int col = min(col_base + 32 * j, p.N - 1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = min(row_base + 32 * i + 8 * (v >> 2) + (v & 3), p.M - 1);
+          dst[v] = p.c_star[(size_t)row * p.N + col];
+        }
+      };
+      load_golden(std::integral_constant<int, 0>{}, cs_buf[0]);
+      static_for<TM * TN>([&](auto tt) {
+        constexpr int i = tt / TN, j = tt % TN, cb = tt % 2;
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (tt + 1 < TM * TN) load_golden(std::integral_constant<int, tt + 1>{}, cs_buf[cb ^ 1]);
+        const f32x16 t = acc[0][i][j];
+        const f32x16 cs = cs_buf[cb];
+        const int col = col_base + 32 * j;
+        uint32_t differs = 0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
+          const bool act = !ragged || (row < p.M && col < p.N);
+          differs |= (act && (__float_as_uint(t[v]) != __float_as_uint(cs[v]) || t[v] != t[v])) ? 1u : 0u;
+        }
+        if (__ballot(differs != 0) != 0) {
+          static_for<4>([&](auto qq) {
+            constexpr int q = qq;
+            __builtin_amdgcn_sched_barrier(0);
+            const int row0 = row_base + 32 * i + 8 * q;
+            const f32x4 kra_q = *reinterpret_cast<const f32x4*>(p.kra + row0);
+            const float cb_j = p.cb[min(col, p.N - 1)];
+            float sa[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              sa[e] = p.s_abs[(size_t)min(row0 + e, p.M - 1) * p.N + min(col, p.N - 1)];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              constexpr int dummy = 0; (void)dummy;
+              const int v = 4 * q + e;
+              const bool act = row0 + e < p.M && col < p.N;
+              const float c = t[v], cse = cs[v];
+              const float Tv = !act ? __builtin_inff()
+                                    : p.bound_global ? p.t_global : __fmul_rn(__fmul_rn(kra_q[e], cb_j), p.gamma);
+              const float tau = sa[e] * 0.000244140625f;        // 2^-12, exact scaling
+              const bool flag = !(fabsf(c) <= Tv);
+              float cc = c;
+              if (flag && p.policy == FI_CORRECT_ZERO) cc = 0.0f;
+              if (flag && p.policy == FI_CORRECT_RECOMPUTE) cc = cse;
+              const float dpre = finite_or_inf(fabsf(c - cse));
+              const float dpost = finite_or_inf(fabsf(cc - cse));
+              const bool changed = act && __float_as_uint(c) != __float_as_uint(cse);
+              n_bit += changed ? 1u : 0u;
+              n_pre += (act && !(dpre <= tau)) ? 1u : 0u;
+              n_post += (act && !(dpost <= tau)) ? 1u : 0u;
+              mx_pre = fmaxf(mx_pre, act ? dpre : 0.0f);
+              mx_post = fmaxf(mx_post, act ? dpost : 0.0f);
+              const float band = fmaxf(2.0f * tau, Tv * 0.015625f);
+              const float mag = fabsf(c);
+              n_bT += (changed && mag <= 3.4028234e38f && fabsf(mag - Tv) <= band) ? 1u : 0u;
+              n_btau += (changed && tau > 0.0f && dpre >= 0.5f * tau && dpre <= 2.0f * tau) ? 1u : 0u;
+            }
+          });
+        }
+      });
+      // most trial tiles equal the fault-free result bit for bit: one ballot, nothing to reduce
+      if (__ballot((n_bit | n_pre | n_post) != 0) == 0) return;
+      uint32_t mp = __float_as_uint(mx_pre), mq = __float_as_uint(mx_post);   // non-negative: ordered like words
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        n_bit += __shfl_xor(n_bit, o, 64); n_pre += __shfl_xor(n_pre, o, 64); n_post += __shfl_xor(n_post, o, 64);
+        n_bT += __shfl_xor(n_bT, o, 64); n_btau += __shfl_xor(n_btau, o, 64);
+        const uint32_t a = __shfl_xor(mp, o, 64), b = __shfl_xor(mq, o, 64);
+        mp = a > mp ? a : mp; mq = b > mq ? b : mq;
+      }
+      if (lane == 0) {
+        fi_trial_result* res = p.results + trial[0];
+        if (n_bit) atomicAdd(&res->n_bitdiff, n_bit);
+        if (n_pre) atomicAdd(&res->n_dev_pre, n_pre);
+        if (n_post) atomicAdd(&res->n_dev_post, n_post);
+        if (n_bT) atomicAdd(&res->n_border_T, n_bT);
+        if (n_btau) atomicAdd(&res->n_border_tau, n_btau);
+        if (mp) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_pre), mp);
+        if (mq) atomicMax(reinterpret_cast<uint32_t*>(&res->max_dev_post), mq);
+      }
+      return;
+    }
     // Deviation counters of the trials whose fault can reach an element this wave holds (rare):
     // the wave owning the element, or the waves holding its output row (A) / column (B).
     // Counts are sums of lane masks (ballot + popcount: no cross-lane traffic); the two maxima
@@ -500,7 +620,16 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                 Tv = (v == sel_v) ? T[v] : Tv;
               }
               const int col = col_base + 32 * j;
-              account(lhi == sel_hi && (!need_col || col == site_col) && col < p.N, c, Tv, cs_pre[r][j], sa_pre[r][j]);
+              float cs = 0.0f, sabs = 0.0f;
+              if constexpr (PRE_GOLDEN) {
+                cs = cs_pre[r][j];
+                sabs = sa_pre[r][j];
+              } else {
+                const size_t idx = (size_t)site_row * (size_t)p.N + (size_t)min(col, p.N - 1);
+                cs = p.c_star[idx];
+                sabs = p.s_abs[idx];
+              }
+              account(lhi == sel_hi && (!need_col || col == site_col) && col < p.N, c, Tv, cs, sabs);
             }
           });
         } else {
@@ -561,10 +690,13 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   issue_tile(cur, 0, 0);
   uint32_t w_nxt = w_cur + gridDim.x;
   bool has_next = w_nxt < n_work;
-  if (has_next) {
-    locate(w_nxt, nxt);
-    desc_nxt = load_desc(nxt.grp);
-  }
+  auto locate_next = [&]() __attribute__((always_inline)) {
+    if (has_next) {
+      locate(w_nxt, nxt);
+      desc_nxt = load_desc(nxt.grp);
+    }
+  };
+  if constexpr (!LATE_NEXT) locate_next();
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
   __syncthreads();
   Frags f0, f1;
@@ -646,9 +778,10 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     using mid_tile = std::integral_constant<int, 0>;
     using last_tile = std::integral_constant<int, 1>;
     using any_tile = std::integral_constant<int, 2>;
-    if (!has_events) {
+    if (PROP || !has_events) {
       // Nearly every wave of nearly every item: no event check anywhere.
       if (nkt == 1) {
+        if constexpr (LATE_NEXT) locate_next();
         k_tile(no{}, yes{}, last_tile{}, dyn{}, 0);
       } else if ((nkt & 1) == 0 && stage == 0) {
         // an even number of k-tiles: every item starts in stage 0 and the stages alternate statically
@@ -661,13 +794,15 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
           }
           k_tile(no{}, no{}, mid_tile{}, st0{}, nkt - 2);
         }
+        if constexpr (LATE_NEXT) locate_next();
         k_tile(no{}, no{}, last_tile{}, st1{}, nkt - 1);
       } else {
         k_tile(no{}, yes{}, mid_tile{}, dyn{}, 0);
         for (int kt = 1; kt + 1 < nkt; ++kt) k_tile(no{}, no{}, mid_tile{}, dyn{}, kt);
+        if constexpr (LATE_NEXT) locate_next();
         k_tile(no{}, no{}, last_tile{}, dyn{}, nkt - 1);
       }
-    } else {
+    } else if constexpr (!PROP) {
       // A wave with events in this item alternates runs of check-free k-tiles with single
       // k-tiles of the checking copy, one per k-tile that holds an event.  (A choice between the
       // two copies inside one loop body - MFMAs over all accumulators in both arms of a branch -
@@ -676,6 +811,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
       // ones.  These copies keep to the running LDS stage, find out at run time whether a k-tile
       // is the item's last, and the accumulators are cleared up front: rare path, and every copy
       // of a k-tile costs code.
+      if constexpr (LATE_NEXT) locate_next();
       static_for<R * TM * TN>([&](auto t) {
         acc[t / (TM * TN)][(t / TN) % TM][t % TN] =
             f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -694,7 +830,6 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
       }
     }
 
-    if constexpr (!EARLY_T) fetch_threshold_inputs();
     epilogue();
     if (!has_next) break;                                // uniform: every wave leaves here
     cur = nxt;
@@ -702,10 +837,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     w_cur = w_nxt;
     w_nxt = w_cur + gridDim.x;
     has_next = w_nxt < n_work;
-    if (has_next) {
-      locate(w_nxt, nxt);
-      desc_nxt = load_desc(nxt.grp);
-    }
+    if constexpr (!LATE_NEXT) locate_next();
   }
 }
 

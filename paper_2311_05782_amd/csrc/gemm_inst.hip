@@ -42,14 +42,25 @@ hipError_t FI_NAME(launch_single_d, FI_INST_DT, FI_INST_CFG)(int mode, const Gem
 // Each finds its trial count on the device and exits at once if it is zero.
 hipError_t FI_NAME(launch_multi_d, FI_INST_DT, FI_INST_CFG)(const GemmArgs& a, int n_blocks, hipStream_t s) {
   constexpr MultiCfg c = kMulti[FI_INST_CFG];
-  hipLaunchKernelGGL((gemm_fi_multi_kernel<FI_INST_DT, c.r, c.bm, c.bn, c.wm, c.wn, false>), dim3(n_blocks),
+  hipLaunchKernelGGL((gemm_fi_multi_kernel<FI_INST_DT, c.r, c.bm, c.bn, c.wm, c.wn, VAR_PLAIN>), dim3(n_blocks),
                      dim3(c.wm * c.wn * 64), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm_fi_multi_kernel<FI_INST_DT, c.r, c.bm, c.bn, c.wm, c.wn, true>), dim3(n_blocks),
+  hipLaunchKernelGGL((gemm_fi_multi_kernel<FI_INST_DT, c.r, c.bm, c.bn, c.wm, c.wn, VAR_OPERAND>), dim3(n_blocks),
                      dim3(c.wm * c.wn * 64), 0, s, a);
   return hipGetLastError();
 }
+
+#if FI_INST_CFG >= 4
+// The next layer of a two-layer workload: one launch, every trial with its own A operand.
+hipError_t FI_NAME(launch_prop_d, FI_INST_DT, FI_INST_CFG)(const GemmArgs& a, int n_blocks, hipStream_t s) {
+  constexpr MultiCfg c = kMulti[FI_INST_CFG];
+  static_assert(c.r == 1, "one trial per item");
+  hipLaunchKernelGGL((gemm_fi_multi_kernel<FI_INST_DT, c.r, c.bm, c.bn, c.wm, c.wn, VAR_PROPAGATE>), dim3(n_blocks),
+                     dim3(c.wm * c.wn * 64), 0, s, a);
+  return hipGetLastError();
+}
+#endif
 
 #endif
 

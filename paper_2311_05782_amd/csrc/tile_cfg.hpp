@@ -29,7 +29,12 @@ constexpr MultiCfg kMulti[] = {
     {2, 128, 128, 4, 2, 1},   // each wave 32 x 64 for 2 trials
     {8, 128, 64, 4, 2, 1},    // each wave 32 x 32 for 8 trials
     {8, 64, 64, 2, 2, 2},     // each wave 32 x 32 for 8 trials, two workgroups per compute unit
+    {1, 256, 256, 4, 2, 1},   // one trial per item, each wave 64 x 128
+    {1, 128, 128, 2, 2, 2},   // one trial per item, each wave 64 x 64, two workgroups per compute unit
 };
+// The one-trial configurations also exist in a third instantiation for the next layer of a
+// two-layer workload (every trial with its own A operand).
+constexpr int kMultiOneTrial[2] = {4, 5};
 constexpr int kNumMulti = sizeof(kMulti) / sizeof(kMulti[0]);
 
 // mode: MODE_CAMPAIGN .. MODE_PROPAGATE of gemm_fi.hpp.
@@ -40,8 +45,12 @@ constexpr int kNumMulti = sizeof(kMulti) / sizeof(kMulti[0]);
   hipError_t launch_multi_d##DT##_c##MC(const GemmArgs& a, int n_blocks, hipStream_t s);
 FI_DECLARE_SINGLE(0, 0) FI_DECLARE_SINGLE(0, 1) FI_DECLARE_SINGLE(0, 2)
 FI_DECLARE_SINGLE(1, 0) FI_DECLARE_SINGLE(1, 1) FI_DECLARE_SINGLE(1, 2)
-FI_DECLARE_MULTI(0, 0) FI_DECLARE_MULTI(0, 1) FI_DECLARE_MULTI(0, 2) FI_DECLARE_MULTI(0, 3)
-FI_DECLARE_MULTI(1, 0) FI_DECLARE_MULTI(1, 1) FI_DECLARE_MULTI(1, 2) FI_DECLARE_MULTI(1, 3)
+#define FI_DECLARE_PROP(DT, MC) \
+  hipError_t launch_prop_d##DT##_c##MC(const GemmArgs& a, int n_blocks, hipStream_t s);
+FI_DECLARE_MULTI(0, 0) FI_DECLARE_MULTI(0, 1) FI_DECLARE_MULTI(0, 2) FI_DECLARE_MULTI(0, 3) FI_DECLARE_MULTI(0, 4) FI_DECLARE_MULTI(0, 5)
+FI_DECLARE_MULTI(1, 0) FI_DECLARE_MULTI(1, 1) FI_DECLARE_MULTI(1, 2) FI_DECLARE_MULTI(1, 3) FI_DECLARE_MULTI(1, 4) FI_DECLARE_MULTI(1, 5)
+FI_DECLARE_PROP(0, 4) FI_DECLARE_PROP(0, 5) FI_DECLARE_PROP(1, 4) FI_DECLARE_PROP(1, 5)
+#undef FI_DECLARE_PROP
 #undef FI_DECLARE_SINGLE
 #undef FI_DECLARE_MULTI
 

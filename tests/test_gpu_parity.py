@@ -257,7 +257,9 @@ def test_plan_describe_names_the_kernels_in_use():
     plan.tune(5)
     assert "gemm_fi_multi_kernel<bf16, R=8, 128x64" in plan.describe()
     plan.tune(1)
-    assert plan.describe() == "gemm_fi_kernel<bf16, 128x128, 256 threads>"
+    assert "one trial per item, 128x128, 256 threads, persistent x2 per CU" in plan.describe()
+    plan.tune(2)
+    assert plan.describe() == "gemm_fi_kernel<bf16, 256x64, 256 threads>"
     plan.tune(3)
     assert "R=4, 128x128" in plan.describe()
     plan.destroy()
