@@ -34,14 +34,34 @@ TRAFFIC = {
 
 
 def kernel_sources_digest():
-    import glob
-    import hashlib
-    h = hashlib.sha256()
-    files = sorted(glob.glob(os.path.join(ROOT, "paper_2311_05782_amd", "csrc", "*")))
-    for f in files + [os.path.join(ROOT, "include", "fi.h")]:
-        with open(f, "rb") as fh:
-            h.update(fh.read())
-    return h.hexdigest()
+    from paper_2311_05782_amd import build
+    return build.sources_digest()
+
+
+def mfma_loop_peak(torch, fi, fmt, n_cus, random_data, iters=150000, reps=3):
+    """What the matrix cores sustain on this machine when waves only issue MFMAs (fi_probe_mfma_loop):
+    the campaign kernel's occupancy, register-resident operands.  Returns TFLOP/s (median of
+    `reps` launches of about 80 ms) and the shader clock the last launch sustained."""
+    sink = torch.empty(n_cus * 512, dtype=torch.float32, device="cuda")
+    clk = torch.zeros(4, dtype=torch.int64, device="cuda")
+    fi.fi_probe_mfma_loop(fmt, random_data, iters // 10, n_cus, sink, clk)
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fi.fi_probe_mfma_loop(fmt, random_data, iters, n_cus, sink, clk)
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    flops = float(n_cus) * 8 * 2 * 8 * iters * 32768.0
+    return flops / (sorted(ms)[len(ms) // 2] * 1e-3) / 1e12, clock_ghz(clk.cpu().numpy())
+
+
+def clock_ghz(c):
+    """{cycles, 100 MHz ticks, cycles, ticks} of one launch -> sustained shader clock in GHz."""
+    ticks = int(c[3]) - int(c[1])
+    return round((int(c[2]) - int(c[0])) / (ticks / 1e8) / 1e9, 3) if ticks > 0 else None
 
 
 def cpu_baseline(w, budget_s=15.0):
@@ -138,6 +158,7 @@ def main():
     ap.add_argument("--sources-digest", action="store_true", help="print the kernel sources' digest and exit")
     ap.add_argument("--campaigns", action="store_true", help="also time the four other campaigns")
     ap.add_argument("--detector", action="store_true", help="also time the standalone detector kernel")
+    ap.add_argument("--no-loop-peak", action="store_true", help="skip the MFMA-loop probe (achievable peak)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference row for HBM byte counters)")
     args = ap.parse_args()
@@ -175,6 +196,8 @@ def main():
     d_r = fi.empty_results(n_trials)
     d_cls = torch.empty(n_trials, dtype=torch.uint8, device="cuda")
     d_cnt = torch.empty(3, dtype=torch.int64, device="cuda")
+    d_clk = torch.zeros(12, dtype=torch.int64, device="cuda")
+    plan.set_clock_sink(d_clk)
 
     def step():
         plan.fi_gemm_inject_batch(d_f, n_trials, policy, d_r)
@@ -206,6 +229,13 @@ def main():
     wall = time.perf_counter() - t0
 
     kern_ms = [a.elapsed_time(b) for a, b in ev]
+    clocks = d_clk.cpu().numpy()
+    plan.set_clock_sink(None)
+    n_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    loop_peak = loop_clock = loop_peak_const = loop_clock_const = None
+    if not args.no_loop_peak:
+        loop_peak, loop_clock = mfma_loop_peak(torch, fi, w.fmt, n_cus, 1)
+        loop_peak_const, loop_clock_const = mfma_loop_peak(torch, fi, w.fmt, n_cus, 0)
     flops_per_launch = w.flops_per_trial * n_trials
     ms_per_step = wall * 1e3 / args.steps
     tflops = flops_per_launch * args.steps / wall / 1e12
@@ -234,7 +264,18 @@ def main():
                      "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
                      "traffic_unit": "HBM bytes per launch (fetch + write)", "kernel": plan.describe(),
                      "flops_per_launch": flops_per_launch, "kernel_ms_avg": round(sum(kern_ms) / len(kern_ms), 3),
-                     "kernel_ms_min": round(min(kern_ms), 3)},
+                     "kernel_ms_median": round(sorted(kern_ms)[len(kern_ms) // 2], 3),
+                     "kernel_ms_min": round(min(kern_ms), 3),
+                     # the shader clock the last timed campaign launch sustained (the kernel's own counters)
+                     "sustained_clock_ghz": clock_ghz(clocks[0:4]), "nominal_clock_ghz": 2.4,
+                     # what an MFMA-only loop reaches on this machine, in the same occupancy: on random
+                     # operands of the campaign's format (the achievable peak: the part lowers its clock
+                     # under matrix load) and on constant operands
+                     "mfma_loop_peak": None if loop_peak is None else round(loop_peak, 1),
+                     "mfma_loop_clock_ghz": loop_clock,
+                     "mfma_loop_peak_constant_data": None if loop_peak_const is None else round(loop_peak_const, 1),
+                     "mfma_loop_clock_constant_data_ghz": loop_clock_const,
+                     "frac_of_mfma_loop_peak": None if not loop_peak else round(achieved / loop_peak, 4)},
     }
     # The standalone detector / corrector (fi_detect_correct) on materialised outputs of the same
     # problem: an HBM-bound kernel, 4 bytes read per element, priced against the 8 TB/s roof.

@@ -294,6 +294,24 @@ fi_status fi_sample_faults(uint64_t seed, uint32_t first_trial, uint32_t n_trial
                            const fi_plan_desc* desc, uint32_t kind_mode, uint32_t nbits,
                            fi_fault* h_out);
 
+/* Measurement aids (no counterpart in the paper; they serve the roofline report).
+ *
+ * fi_plan_set_clock_sink: d_clocks is NULL (off, the default) or DEVICE memory for 12 64-bit
+ * words, 8-byte aligned, alive while batches of this plan run.  Workgroup 0 of each persistent
+ * campaign kernel then writes {shader-clock counter, 100 MHz counter} when it starts and when it
+ * has finished its last item: words 0..3 for the launch over the trials that leave the operands
+ * alone, 4..7 for the operand-fault launch, 8..11 for fi_gemm_propagate_batch.  (cycles_end -
+ * cycles_start) / ((ticks_end - ticks_start) / 1e8) is the shader clock that launch sustained.
+ *
+ * fi_probe_mfma_loop: launches n_workgroups workgroups of 8 waves that do nothing but issue
+ * 2 * 8 * iters 32x32x16 MFMAs per wave on register-resident operands (random_data 0: all 1.0;
+ * else seeded values of magnitude in [1, 2) with random signs), i.e. 2 * 8 * iters * 32768
+ * flops per wave; the caller times it.  d_sink: DEVICE, n_workgroups * 512 floats, overwritten.
+ * d_clocks: NULL or DEVICE [4] words as above.  Errors: UNSUPPORTED (dtype), INVALID_ARG, STATE. */
+fi_status fi_plan_set_clock_sink(fi_plan* plan, uint64_t* d_clocks);
+fi_status fi_probe_mfma_loop(uint32_t dtype, uint32_t random_data, uint32_t iters, uint32_t n_workgroups,
+                             float* d_sink, uint64_t* d_clocks, void* stream);
+
 /* Thread-local description of the last failure on this thread. */
 const char* fi_last_error(void);
 

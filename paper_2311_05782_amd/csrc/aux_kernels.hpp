@@ -379,6 +379,68 @@ __global__ void __launch_bounds__(1024) deviation_histogram_kernel(const fi_faul
   if (threadIdx.x < 256) hist[threadIdx.x] = bins[threadIdx.x];
 }
 
+// Measurement aid: what the matrix cores sustain when a wave does nothing but issue MFMAs, in the
+// campaign kernel's occupancy (8 waves per workgroup, one workgroup per CU, 128 accumulator
+// registers per lane).  Each wave holds eight 32 x 32 accumulators and two sets of operand
+// fragments that alternate from step to step (so operand bits toggle as they do when fragments
+// arrive from LDS); random_data = 0 fills them with 1.0, else with seeded values in [-2, 2).
+// The part lowers its clock under matrix load depending on the data, so this - not the nominal
+// peak - is what a GEMM kernel on such data can approach.  Workgroup 0 records the counters
+// described at GemmArgs::clocks.  sink keeps the result alive.
+template <int DT>
+__global__ void __launch_bounds__(512, 2) mfma_loop_probe_kernel(int random_data, int iters, float* __restrict__ sink,
+                                                                unsigned long long* __restrict__ clocks) {
+  const int tid = threadIdx.x;
+  if (clocks && blockIdx.x == 0 && tid == 0) {
+    clocks[0] = __builtin_readcyclecounter();
+    clocks[1] = __builtin_amdgcn_s_memrealtime();
+  }
+  u32x4 fa[2][2], fb[2][4];
+  const uint32_t one = DT == FI_BF16 ? 0x3F803F80u : 0x3C003C00u;
+  uint32_t h = (uint32_t)(blockIdx.x * 512 + tid) * 2654435761u + 12345u;
+  auto word = [&]() -> uint32_t {
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
+    // two 16-bit values with random sign and mantissa, exponent of 1.0: magnitudes in [1, 2)
+    const uint32_t keep = DT == FI_BF16 ? 0x807F807Fu : 0x83FF83FFu;
+    return random_data ? ((h & keep) | one) : one;
+  };
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) fa[s][i][w] = word();
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) fb[s][j][w] = word();
+  }
+  f32x16 acc[2][4];
+  static_for<8>([&](auto t) {
+    acc[t / 4][t % 4] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  });
+  for (int it = 0; it < iters; ++it) {
+    static_for<2>([&](auto ss) {
+      constexpr int s = ss;
+      static_for<8>([&](auto t) {
+        constexpr int i = t / 4, j = t % 4;
+        acc[i][j] = mfma_32x32x16<DT>(fa[s][i], fb[s][j], acc[i][j]);
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  }
+  float x = 0.0f;
+  static_for<8>([&](auto t) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) x += acc[t / 4][t % 4][v];
+  });
+  sink[(size_t)blockIdx.x * 512 + tid] = x;
+  if (clocks && blockIdx.x == 0 && tid == 0) {
+    clocks[2] = __builtin_readcyclecounter();
+    clocks[3] = __builtin_amdgcn_s_memrealtime();
+  }
+}
+
 // Outcome per trial and campaign totals, one workgroup, no atomics:
 // DETECTED if anything was flagged, else SDC if anything deviates beyond the
 // tolerance, else MASKED.

@@ -80,6 +80,7 @@ struct fi_plan {
   std::vector<BatchScratch> batch;   // per stream, see BatchScratch
   int n_cus = 8;                     // compute units of the device: grid of the persistent kernel
   int product_check = FI_PCHECK_NONE;
+  unsigned long long* clocks = nullptr;   // caller's [12] counter sink, or NULL (fi_plan_set_clock_sink)
 };
 
 namespace {
@@ -142,6 +143,7 @@ GemmArgs base_args(const fi_plan* p, int cfg = -1) {
   a.bound_global = p->d.bound_mode != FI_BOUND_ROWCOL;
   a.t_global = p->t_global;
   a.c_star = p->c_star; a.s_abs = p->s_abs;
+  a.clocks = p->clocks;
   return a;
 }
 
@@ -580,6 +582,33 @@ fi_status fi_plan_reserve(fi_plan* plan, uint32_t max_trials, void* stream) {
   if (max_trials == 0) return fail(FI_INVALID_ARG, "max_trials is 0");
   BatchScratch* bs = nullptr;
   return batch_scratch(plan, as_stream(stream), max_trials, &bs);
+}
+
+fi_status fi_plan_set_clock_sink(fi_plan* plan, uint64_t* d_clocks) {
+  fi_status st = check_plan(plan);
+  if (st != FI_OK) return st;
+  if (reinterpret_cast<uintptr_t>(d_clocks) & 7u) return fail(FI_INVALID_ARG, "d_clocks must be 8-byte aligned");
+  plan->clocks = reinterpret_cast<unsigned long long*>(d_clocks);
+  return FI_OK;
+}
+
+fi_status fi_probe_mfma_loop(uint32_t dtype, uint32_t random_data, uint32_t iters, uint32_t n_workgroups,
+                             float* d_sink, uint64_t* d_clocks, void* stream) {
+  if (dtype != FI_FP16 && dtype != FI_BF16) return fail(FI_UNSUPPORTED, "dtype %u: only FP16 (0) and BF16 (1)", dtype);
+  if (!d_sink) return fail(FI_INVALID_ARG, "d_sink is NULL");
+  if (iters == 0 || n_workgroups == 0 || n_workgroups > 65536u || iters > (1u << 24))
+    return fail(FI_INVALID_ARG, "iters must be in 1..2^24 and n_workgroups in 1..65536");
+  fi_status st = check_device();
+  if (st != FI_OK) return st;
+  unsigned long long* clk = reinterpret_cast<unsigned long long*>(d_clocks);
+  if (dtype == FI_BF16)
+    hipLaunchKernelGGL(fi::mfma_loop_probe_kernel<FI_BF16>, dim3(n_workgroups), dim3(512), 0, as_stream(stream),
+                       (int)random_data, (int)iters, d_sink, clk);
+  else
+    hipLaunchKernelGGL(fi::mfma_loop_probe_kernel<FI_FP16>, dim3(n_workgroups), dim3(512), 0, as_stream(stream),
+                       (int)random_data, (int)iters, d_sink, clk);
+  FI_HIP(hipGetLastError());
+  return FI_OK;
 }
 
 fi_status fi_plan_set_product_check(fi_plan* plan, uint32_t mode) {

@@ -73,6 +73,11 @@ struct GemmArgs {
   const uint32_t* part_counts;
   const uint32_t* desc;
   uint64_t a_trial_stride;  // PROPAGATE: trial t reads A + t * a_trial_stride (elements)
+  // Measurement aid, nullable: workgroup 0 of the persistent kernel writes the shader-clock
+  // counter and the constant-rate (100 MHz) counter when it starts and when it has finished its
+  // last item - {cycles, ticks, cycles, ticks} at clocks + 4 * VAR - from which the host derives
+  // the shader clock the launch sustained.
+  unsigned long long* clocks;
 };
 
 template <int DT>

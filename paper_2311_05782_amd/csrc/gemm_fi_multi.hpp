@@ -88,6 +88,10 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   const uint32_t n_work = (uint32_t)(p.tiles_m * p.tiles_n) * (uint32_t)n_groups;
   uint32_t w_cur = blockIdx.x;
   if (w_cur >= n_work) return;                            // uniform, before any barrier
+  if (p.clocks && blockIdx.x == 0 && tid == 0) {
+    p.clocks[4 * VAR + 0] = __builtin_readcyclecounter();
+    p.clocks[4 * VAR + 1] = __builtin_amdgcn_s_memrealtime();
+  }
 
   // ---- staging: global -> LDS directly, as in gemm_fi_kernel
   const int lrow = lane >> 3, lslot = lane & 7;
@@ -838,6 +842,10 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     w_nxt = w_cur + gridDim.x;
     has_next = w_nxt < n_work;
     if constexpr (!LATE_NEXT) locate_next();
+  }
+  if (p.clocks && blockIdx.x == 0 && tid == 0) {
+    p.clocks[4 * VAR + 2] = __builtin_readcyclecounter();
+    p.clocks[4 * VAR + 3] = __builtin_amdgcn_s_memrealtime();
   }
 }
 

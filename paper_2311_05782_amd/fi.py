@@ -27,7 +27,7 @@ BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 
 # Symbols include/fi.h declares; the loader checks every one.
 EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
-           "fi_plan_set_product_check", "fi_plan_reserve", "fi_deviation_histogram",
+           "fi_plan_set_product_check", "fi_plan_reserve", "fi_plan_set_clock_sink", "fi_probe_mfma_loop", "fi_deviation_histogram",
            "fi_gemm_inject_batch", "fi_gemm_inject_batch_noalloc", "fi_gemm_inject_batch_affected", "fi_detect_correct", "fi_classify", "fi_sample_faults",
            "fi_activation_round", "fi_gemm_propagate_batch", "fi_last_error", "fi_build_info"]
 
@@ -91,6 +91,8 @@ def lib():
     L.fi_plan_describe.argtypes = [vp, C.c_char_p, C.c_uint64]
     L.fi_plan_set_product_check.argtypes = [vp, C.c_uint32]
     L.fi_plan_reserve.argtypes = [vp, C.c_uint32, vp]
+    L.fi_plan_set_clock_sink.argtypes = [vp, vp]
+    L.fi_probe_mfma_loop.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch_noalloc.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch_affected.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp]
@@ -147,6 +149,11 @@ def fi_sample_faults(seed, first_trial, n_trials, desc, kind_mode, nbits):
     return out
 
 
+def fi_probe_mfma_loop(dtype, random_data, iters, n_workgroups, d_sink, d_clocks=None, stream=None):
+    _check(lib().fi_probe_mfma_loop(dtype, random_data, iters, n_workgroups, _dptr(d_sink), _dptr(d_clocks),
+                                    _stream(stream)))
+
+
 def fi_activation_round(dtype, d_c, n, d_h, stream=None):
     _check(lib().fi_activation_round(dtype, _dptr(d_c), n, _dptr(d_h), _stream(stream)))
 
@@ -188,6 +195,10 @@ class Plan:
 
     def reserve(self, max_trials, stream=None):
         _check(lib().fi_plan_reserve(self._h, max_trials, _stream(stream)))
+
+    def set_clock_sink(self, d_clocks):
+        self._clock_keep = d_clocks
+        _check(lib().fi_plan_set_clock_sink(self._h, _dptr(d_clocks)))
 
     def set_product_check(self, mode):
         _check(lib().fi_plan_set_product_check(self._h, mode))
