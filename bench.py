@@ -158,6 +158,7 @@ def main():
     ap.add_argument("--sources-digest", action="store_true", help="print the kernel sources' digest and exit")
     ap.add_argument("--campaigns", action="store_true", help="also time the four other campaigns")
     ap.add_argument("--detector", action="store_true", help="also time the standalone detector kernel")
+    ap.add_argument("--two-layer", action="store_true", help="also time the two-layer chain")
     ap.add_argument("--no-loop-peak", action="store_true", help="skip the MFMA-loop probe (achievable peak)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference row for HBM byte counters)")
@@ -361,7 +362,7 @@ def main():
     # Two layers, Y = relu(X W1) W2 with a transformer feed-forward block's shapes: a fault in the
     # first GEMM, detector + corrector, ReLU and rounding to the operand format, then the second GEMM
     # of every trial in full; how many of the faults layer 1 does not mask still show at the output.
-    if extras or args.campaigns:
+    if extras or args.campaigns or args.two_layer:
         out["two_layer"] = two_layer(torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

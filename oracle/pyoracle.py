@@ -42,6 +42,13 @@ PCHECK_NONE, PCHECK_BOUND, PCHECK_RANGE_MAX, PCHECK_RANGE_FLIP = 0, 1, 2, 3
 DEFAULT_GAMMA = 1.0 + 2.0 ** -11
 
 
+# FI_ORACLE_SANITIZE=1 builds and loads an AddressSanitizer + UndefinedBehaviorSanitizer build of
+# the oracle instead (CPU only; run the interpreter with libasan preloaded).
+_SANITIZE = bool(os.environ.get("FI_ORACLE_SANITIZE"))
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libfi_oracle_san.so")
+
+
 def build(force=False):
     """Compile the oracle with gcc.  -ffp-contract=off keeps a*b+c as two roundings."""
     if os.path.exists(_LIB) and not force and os.path.getmtime(_LIB) >= max(
@@ -49,6 +56,8 @@ def build(force=False):
         return _LIB
     cmd = ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
            "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB, "-lm"]
+    if _SANITIZE:
+        cmd[1:1] = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"]
     subprocess.run(cmd, check=True)
     return _LIB
 

@@ -70,9 +70,17 @@ def build(force=True, verbose=False, jobs=None):
               "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     if os.environ.get("FI_SAVE_TEMPS"):
         common += ["-save-temps=obj"]
+    # FI_SANITIZE_HOST=1: AddressSanitizer + UndefinedBehaviorSanitizer on the HOST side of the
+    # ABI file only (argument checks, plan bookkeeping), into libfi_gfx950_san.so; load it through
+    # FI_LIBRARY with libasan preloaded.  Device code is never sanitized.
+    sanitize = bool(os.environ.get("FI_SANITIZE_HOST"))
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-g"] if sanitize else []
+    lib = os.path.join(HERE, "libfi_gfx950_san.so") if sanitize else LIB
     cmds, objs = [], []
     api_o = os.path.join(OBJ, "fi_api.o")
-    cmds.append(common + ['-DFI_SOURCES_SHA256="%s"' % digest, "-c", os.path.join(CSRC, "fi_api.hip"), "-o", api_o])
+    if sanitize:
+        api_o = os.path.join(OBJ, "fi_api_san.o")
+    cmds.append(common + san + ['-DFI_SOURCES_SHA256="%s"' % digest, "-c", os.path.join(CSRC, "fi_api.hip"), "-o", api_o])
     objs.append(api_o)
     for fam, dt, cfg in INSTANCES:
         o = os.path.join(OBJ, "gemm_f%d_d%d_c%d.o" % (fam, dt, cfg))
@@ -82,8 +90,8 @@ def build(force=True, verbose=False, jobs=None):
     jobs = jobs or int(os.environ.get("MAX_JOBS", 0)) or min(16, os.cpu_count() or 4)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose)
-    return LIB
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", lib], verbose)
+    return lib
 
 
 if __name__ == "__main__":

@@ -121,35 +121,48 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
       it.b_goff[c] = (uint32_t)min(it.n0 + row, p.N - 1) * p.ldb + (uint32_t)((lslot ^ lds_swizzle(row)) * 8);
     }
   };
+  // Staging goes through buffer loads with the LDS as destination: the operand's base sits in a
+  // scalar resource descriptor, the lane's part of the address is one 32-bit byte offset that
+  // never changes within an item, and the k offset is a scalar - a load needs no vector
+  // arithmetic and ships 4 bytes of address per lane instead of 8.  num_records is the operand's
+  // extent, so a load beyond it (there is none) would return zeros instead of faulting.
+  const uint32_t a_bytes = (uint32_t)(((size_t)(p.M - 1) * p.lda + (size_t)p.K) * 2);
+  const uint32_t b_bytes = (uint32_t)(((size_t)(p.N - 1) * p.ldb + (size_t)p.K) * 2);
+  const __amdgpu_buffer_rsrc_t rsrc_b =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.B), 0, (int)b_bytes, 0x00020000);
+  auto rsrc_a_of = [&](const Item& it) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(PROP ? p.A + it.a_base : p.A), 0, (int)a_bytes,
+                                             0x00020000);
+  };
   auto issue_tile = [&](const Item& it, int kt, int stage) {
-    const uint32_t k0 = (uint32_t)(kt * BK);
-    // the trial's operand base is wave-uniform; the per-lane part of an address stays 32 bits wide
-    const uint16_t* const Ab = PROP ? p.A + it.a_base : p.A;
+    const int kb0 = kt * BK * 2;                           // bytes
+    const __amdgpu_buffer_rsrc_t rsrc_a = rsrc_a_of(it);
     uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
     uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
 #pragma unroll
     for (int c = 0; c < A_G; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void*)(Ab + (it.a_goff[c] + k0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_void*)(sA + c * 1024), 16, (int)(it.a_goff[c] * 2u), kb0, 0, 0);
 #pragma unroll
     for (int c = 0; c < B_G; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + (it.b_goff[c] + k0)), (lds_void*)(sB + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_void*)(sB + c * 1024), 16, (int)(it.b_goff[c] * 2u), kb0, 0, 0);
   };
   // The same with the choice made at run time: the next k-tile of the current item, or (last)
   // the first k-tile of the next item.  Offsets are selected value by value, never through a
   // pointer to one of the two items (which would move them to scratch memory).
   auto issue_tile_of = [&](bool last, int kt, int stage) {
-    const uint32_t k0 = last ? 0u : (uint32_t)((kt + 1) * BK);
+    const int kb0 = last ? 0 : (kt + 1) * BK * 2;
+    const __amdgpu_buffer_rsrc_t rsrc_a = rsrc_a_of(cur);  // items with events exist in campaigns only: one A
     uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
     uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
 #pragma unroll
     for (int c = 0; c < A_G; ++c) {
       const uint32_t off = last ? nxt.a_goff[c] : cur.a_goff[c];
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.A + (off + k0)), (lds_void*)(sA + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_void*)(sA + c * 1024), 16, (int)(off * 2u), kb0, 0, 0);
     }
 #pragma unroll
     for (int c = 0; c < B_G; ++c) {
       const uint32_t off = last ? nxt.b_goff[c] : cur.b_goff[c];
-      __builtin_amdgcn_global_load_lds((glb_void*)(p.B + (off + k0)), (lds_void*)(sB + c * 1024), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_void*)(sB + c * 1024), 16, (int)(off * 2u), kb0, 0, 0);
     }
   };
   // A group's R descriptors, one word per lane; fields are picked out with v_readlane.
