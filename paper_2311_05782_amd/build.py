@@ -91,6 +91,13 @@ def build(force=True, verbose=False, jobs=None):
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", lib], verbose)
+    # A kernel whose host-side instantiation was dropped shows up only at load time, as an
+    # undefined launch stub: refuse such a library here.
+    nm = subprocess.run(["nm", "-D", "--undefined-only", lib], stdout=subprocess.PIPE, text=True).stdout
+    missing = [ln.split()[-1] for ln in nm.splitlines() if "__device_stub__" in ln or " _ZN2fi" in ln]
+    if missing:
+        os.remove(lib)
+        raise RuntimeError("libfi_gfx950.so would have undefined symbols: " + ", ".join(missing[:4]))
     return lib
 
 

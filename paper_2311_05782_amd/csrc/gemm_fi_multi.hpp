@@ -146,6 +146,20 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     for (int c = 0; c < B_G; ++c)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_void*)(sB + c * 1024), 16, (int)(it.b_goff[c] * 2u), kb0, 0, 0);
   };
+  // One of the NLOADS loads of issue_tile (k < A_G: the k-th A row group, else B).
+  auto issue_one = [&](const Item& it, int kt, int stage, auto kk) __attribute__((always_inline)) {
+    constexpr int k = decltype(kk)::value;
+    const int kb0 = kt * BK * 2;
+    if constexpr (k < A_G) {
+      uint8_t* sA = smem + stage * STAGE + wave * (A_G * 1024);
+      const __amdgpu_buffer_rsrc_t rsrc_a = rsrc_a_of(it);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_void*)(sA + k * 1024), 16, (int)(it.a_goff[k] * 2u), kb0, 0, 0);
+    } else {
+      constexpr int c = k - A_G;
+      uint8_t* sB = smem + stage * STAGE + BM * 128 + wave * (B_G * 1024);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_void*)(sB + c * 1024), 16, (int)(it.b_goff[c] * 2u), kb0, 0, 0);
+    }
+  };
   // The same with the choice made at run time: the next k-tile of the current item, or (last)
   // the first k-tile of the next item.  Offsets are selected value by value, never through a
   // pointer to one of the two items (which would move them to scratch memory).
@@ -191,37 +205,46 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   // an item never spends vector instructions on clearing 128 accumulator registers.  `mid` (a
   // fragment read for the next step) is issued after the first few MFMAs: the read lands under
   // the rest of the burst instead of being waited for in front of it.
-  auto mma_step_mid = [&](const Frags& f, auto first, auto&& mid) __attribute__((always_inline)) {
+  // `load(k)` issues the k-th staging load of the next k-tile (k a compile-time index that
+  // runs over the steps of a k-tile): the loads go out one by one between the MFMAs of the
+  // bursts, LOAD_STRIDE MFMAs apart, instead of in one block in front of a burst.
+  constexpr int NMMA = R * TM * TN;                      // MFMAs per step and wave
+  constexpr int NLOADS = A_G + B_G;                      // staging loads per k-tile and wave
+  constexpr int LOAD_STRIDE = NLOADS <= 3 * ((NMMA - 2) / 2 + 1) ? 2 : 1;
+  constexpr int LOADS_PER_STEP = (NMMA - 2) / LOAD_STRIDE + 1;   // after MFMA 1, 1 + stride, ...
+  static_assert(NMMA >= 2 && NLOADS <= 3 * LOADS_PER_STEP, "the loads of a k-tile fit its first three bursts");
+  auto mma_step_mid = [&](const Frags& f, auto first, auto step_in_tile, auto&& mid, auto&& load) __attribute__((always_inline)) {
     constexpr bool FIRST = decltype(first)::value;
-    if constexpr (FIRST) {
-      // The R trials start from the same zero with the same fragments, so their first MFMAs are
-      // equal expressions and a compiler may compute one and copy it R - 1 times.  Every trial
-      // executes its own MFMAs: between trials one fragment register passes through an empty asm
-      // statement (no instruction, no extra register), after which the compiler can no longer
-      // take the next trial's inputs to be the previous trial's.
-      Frags q = f;
-      static_for<R * TM * TN>([&](auto t) {
-        constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
-        if constexpr (t == (R * TM * TN >= 8 ? 2 : 1)) {
+    constexpr int SIT = decltype(step_in_tile)::value;   // 0 .. 3; loads go with 0 .. 2
+    [[maybe_unused]] Frags q = f;
+    static_for<NMMA>([&](auto t) {
+      constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
+      if constexpr (t == (NMMA >= 8 ? 2 : 1)) {
+        __builtin_amdgcn_sched_barrier(0);
+        mid();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (SIT < 3 && t >= 1 && (t - 1) % LOAD_STRIDE == 0) {
+        constexpr int k = SIT * LOADS_PER_STEP + (t - 1) / LOAD_STRIDE;
+        if constexpr (k < NLOADS) {
           __builtin_amdgcn_sched_barrier(0);
-          mid();
+          load(std::integral_constant<int, k>{});
           __builtin_amdgcn_sched_barrier(0);
         }
+      }
+      if constexpr (FIRST) {
+        // The R trials start from the same zero with the same fragments, so their first MFMAs
+        // are equal expressions and a compiler may compute one and copy it R - 1 times.  Every
+        // trial executes its own MFMAs: between trials one fragment register passes through an
+        // empty asm statement (no instruction, no extra register), after which the compiler can
+        // no longer take the next trial's inputs to be the previous trial's.
         if constexpr (r > 0 && i == 0 && j == 0) asm volatile("" : "+v"(q.a[0]));
         acc[r][i][j] = mfma_32x32x16<DT>(q.a[i], q.b[j],
             f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f});
-      });
-    } else {
-      static_for<R * TM * TN>([&](auto t) {
-        constexpr int r = t / (TM * TN), i = (t / TN) % TM, j = t % TN;
-        if constexpr (t == (R * TM * TN >= 8 ? 2 : 1)) {
-          __builtin_amdgcn_sched_barrier(0);
-          mid();
-          __builtin_amdgcn_sched_barrier(0);
-        }
+      } else {
         acc[r][i][j] = mfma_32x32x16<DT>(f.a[i], f.b[j], acc[r][i][j]);
-      });
-    }
+      }
+    });
   };
 
   // ---- state of the current item
@@ -756,35 +779,50 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if constexpr (LM == 0) issue_tile(cur, kt + 1, stage ^ 1);
-      else if constexpr (LM == 1) { if (has_next) issue_tile(nxt, 0, stage ^ 1); }
-      else if (more) issue_tile_of(last, kt, stage ^ 1);
+      // The next k-tile's loads: spread over the bursts of steps 0 .. 2 in the check-free copies
+      // that know at compile time what follows; in one block up front in the rare copies.
+      constexpr bool SPREAD = !EV && LM != 2;
+      if constexpr (!SPREAD) {
+        if constexpr (LM == 0) issue_tile(cur, kt + 1, stage ^ 1);
+        else if constexpr (LM == 1) { if (has_next) issue_tile(nxt, 0, stage ^ 1); }
+        else if (more) issue_tile_of(last, kt, stage ^ 1);
+      }
       const uint8_t* s = smem + stage * STAGE;
       const uint8_t* s_other = smem + (stage ^ 1) * STAGE;
-      auto step = [&](Frags& f, int g, auto first, auto&& mid) __attribute__((always_inline)) {
+      auto load = [&](auto kk) __attribute__((always_inline)) {
+        if constexpr (SPREAD) {
+          if constexpr (LM == 0) issue_one(cur, kt + 1, stage ^ 1, kk);
+          else if (has_next) issue_one(nxt, 0, stage ^ 1, kk);
+        }
+      };
+      auto step = [&](Frags& f, int g, auto first, auto sit, auto&& mid) __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (EV) {
           const uint32_t m = hit_mask(g);
           if constexpr (OPS) {
             mma_step_ops(f, m, mid);
           } else {
-            mma_step_mid(f, first, mid);
+            mma_step_mid(f, first, sit, mid, load);
             __builtin_amdgcn_sched_barrier(0);
             if (__builtin_expect(m != 0, 0)) hooks(m);
           }
         } else {
-          mma_step_mid(f, first, mid);
+          mma_step_mid(f, first, sit, mid, load);
         }
         __builtin_amdgcn_sched_barrier(0);
       };
-      step(f0, 4 * kt, std::integral_constant<bool, FIRST>{}, [&]() { read_frags(f1, s, 1); });
-      step(f1, 4 * kt + 1, std::false_type{}, [&]() { read_frags(f0, s, 2); });
-      step(f0, 4 * kt + 2, std::false_type{}, [&]() { read_frags(f1, s, 3); });
+      using s0 = std::integral_constant<int, 0>;
+      using s1 = std::integral_constant<int, 1>;
+      using s2 = std::integral_constant<int, 2>;
+      using s3 = std::integral_constant<int, 3>;
+      step(f0, 4 * kt, std::integral_constant<bool, FIRST>{}, s0{}, [&]() { read_frags(f1, s, 1); });
+      step(f1, 4 * kt + 1, std::false_type{}, s1{}, [&]() { read_frags(f0, s, 2); });
+      step(f0, 4 * kt + 2, std::false_type{}, s2{}, [&]() { read_frags(f1, s, 3); });
       // Every fragment of this stage is in registers (the barrier's fence waits for the reads);
       // once all waves are here the next tile has landed and this stage may be overwritten.
       if (more) __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads have landed
       __syncthreads();
-      step(f1, 4 * kt + 3, std::false_type{}, [&]() { if (more) read_frags(f0, s_other, 0); });
+      step(f1, 4 * kt + 3, std::false_type{}, s3{}, [&]() { if (more) read_frags(f0, s_other, 0); });
       stage ^= 1;
     };
     using dyn = std::integral_constant<int, -1>;
