@@ -72,7 +72,7 @@ def build(force=True, verbose=False, jobs=None):
         common += ["-save-temps=obj"]
     # FI_SANITIZE_HOST=1: AddressSanitizer + UndefinedBehaviorSanitizer on the HOST side of the
     # ABI file only (argument checks, plan bookkeeping), into libfi_gfx950_san.so; load it through
-    # FI_LIBRARY with libasan preloaded.  Device code is never sanitized.
+    # FI_LIBRARY with clang's libclang_rt.asan-x86_64.so preloaded.  Device code is never sanitized.
     sanitize = bool(os.environ.get("FI_SANITIZE_HOST"))
     san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-g"] if sanitize else []
     lib = os.path.join(HERE, "libfi_gfx950_san.so") if sanitize else LIB
@@ -90,7 +90,9 @@ def build(force=True, verbose=False, jobs=None):
     jobs = jobs or int(os.environ.get("MAX_JOBS", 0)) or min(16, os.cpu_count() or 4)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", lib], verbose)
+    # the sanitized build links clang's shared sanitizer runtime (to be preloaded by the loader)
+    link_san = ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan", "-fno-gpu-sanitize"] if sanitize else []
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + link_san + objs + ["-o", lib], verbose)
     # A kernel whose host-side instantiation was dropped shows up only at load time, as an
     # undefined launch stub: refuse such a library here.
     nm = subprocess.run(["nm", "-D", "--undefined-only", lib], stdout=subprocess.PIPE, text=True).stdout

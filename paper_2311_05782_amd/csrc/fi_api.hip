@@ -38,6 +38,9 @@ fi_status fail(fi_status code, const char* fmt, ...) {
   } while (0)
 
 constexpr int PAD = 512;                       // row/column vectors are zero padded to this multiple
+size_t padded(uint32_t n) { return ((size_t)n + PAD - 1) / PAD * PAD; }
+// elements of the fault-free result's allocation: whole tiles of rows plus one tile width
+size_t golden_elems(const fi_plan_desc& d) { return padded((uint32_t)d.M) * (size_t)d.N + PAD; }
 
 using fi::kCfg;
 using fi::kMulti;
@@ -143,6 +146,8 @@ GemmArgs base_args(const fi_plan* p, int cfg = -1) {
   a.bound_global = p->d.bound_mode != FI_BOUND_ROWCOL;
   a.t_global = p->t_global;
   a.c_star = p->c_star; a.s_abs = p->s_abs;
+  const size_t gold_bytes = golden_elems(p->d) * sizeof(float);
+  a.c_star_bytes = gold_bytes < (1ull << 32) ? (uint32_t)gold_bytes : 0u;
   a.clocks = p->clocks;
   return a;
 }
@@ -247,12 +252,15 @@ fi_status batch_scratch(fi_plan* p, hipStream_t stream, uint32_t n, BatchScratch
   return FI_OK;
 }
 
-size_t padded(uint32_t n) { return ((size_t)n + PAD - 1) / PAD * PAD; }
 
 fi_status build_plan(fi_plan* p, const void* d_A, const void* d_B, hipStream_t s) {
   const fi_plan_desc& d = p->d;
   const size_t mn = (size_t)d.M * d.N;
-  FI_HIP(hipMalloc(&p->c_star, mn * sizeof(float)));
+  // C* is padded to whole 256-row tiles plus one tile width (zeros): the next layer's kernel
+  // reads the tile-shaped neighbourhood of its outputs without clamping rows or columns.
+  const size_t mn_pad = golden_elems(d);
+  FI_HIP(hipMalloc(&p->c_star, mn_pad * sizeof(float)));
+  FI_HIP(hipMemsetAsync(p->c_star + mn, 0, (mn_pad - mn) * sizeof(float), s));
   FI_HIP(hipMalloc(&p->s_abs, mn * sizeof(float)));
   FI_HIP(hipMalloc(&p->kra, padded(d.M) * sizeof(float)));
   FI_HIP(hipMalloc(&p->cb, padded(d.N) * sizeof(float)));
@@ -496,7 +504,12 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   p->cfg = pick_cfg(d);
   p->cfg_affected = d.N <= 64 ? 2 : 1;   // small tiles: only the reached part is of interest
   p->mcfg = pick_multi(d);
-  p->prop_cfg = d.K % 64 == 0 ? fi::kMultiOneTrial[0] : -1;
+  // Next-layer launches: on problems below 2^35 multiply-adds the 128 x 128 shape with two
+  // workgroups per CU measured faster (one's epilogue runs under the other's MFMAs: 0.75 against
+  // 0.81 ms on 512 x 768 x 3072, 256 trials), above it the 256 x 256 shape (less LDS traffic per flop).
+  p->prop_cfg = d.K % 64 != 0 ? -1
+                              : (double)d.M * (double)d.N * (double)d.K >= 34359738368.0 ? fi::kMultiOneTrial[0]
+                                                                                       : fi::kMultiOneTrial[1];
   p->group = 32;
   (void)hipGetDevice(&p->device);
   if (hipDeviceGetAttribute(&p->n_cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess ||
@@ -735,7 +748,8 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
     return fail(FI_INVALID_ARG, "trial_stride %llu is smaller than one operand ((M-1)*lda + K elements)",
                 (unsigned long long)trial_stride);
   GemmArgs a = base_args(plan);
-  if (plan->prop_cfg >= 0) {
+  const bool persistent = plan->prop_cfg >= 0 && a.c_star_bytes != 0;
+  if (persistent) {
     const MultiCfg mc = kMulti[plan->prop_cfg];
     a.tiles_m = (a.M + mc.bm - 1) / mc.bm;
     a.tiles_n = (a.N + mc.bn - 1) / mc.bn;
@@ -757,7 +771,7 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
   a.results = d_results;
   a.c_out = d_c_out;
   a.policy = (int)policy;
-  if (plan->prop_cfg >= 0) {
+  if (persistent) {
     // persistent workgroups walking (tile, trial) items
     const MultiCfg mc = kMulti[plan->prop_cfg];
     const uint64_t cus = (uint64_t)(plan->n_cus / 8 * 8) * (uint64_t)mc.wgs;

@@ -63,6 +63,9 @@ struct GemmArgs {
   float t_global;
   const float* c_star;      // [M][N] fault-free result  (campaign)
   const float* s_abs;       // [M][N] sum_k |a b|        (campaign)
+  // Bytes the c_star allocation spans, or 0.  The plan pads it to whole 256-row tiles plus one
+  // tile width, so that a tile reaching over the edge of a ragged problem reads allocated memory.
+  uint32_t c_star_bytes;
   float* c_out;             // campaign: nullable [n_trials][M][N]; golden: [M][N]
   int policy;
   int product_check;        // FI_PCHECK_* applied to the erroneous product of PRODUCT faults

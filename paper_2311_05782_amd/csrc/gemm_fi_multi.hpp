@@ -17,18 +17,20 @@
 // w0 = the XOR mask; a product-term fault has bit 30 of event set and w0, w1 = the words of re
 // and re_err; an operand fault has bit 29 set, w0 = the 16-bit mask, w1 = FI_SITE_A / _B.
 //
-// Operand faults run in a second instantiation (OPS = true) of the same kernel: the staged
+// Operand faults run in a second instantiation (VAR_OPERAND) of the same kernel: the staged
 // tile is shared and stays clean; at the one MFMA step that consumes the faulted word, the
-// waves whose fragment holds it feed THAT trial a patched copy of the fragment registers - the
-// same MFMA inputs a trial of its own would have staged.  The extra code sits in the k-loop,
-// which costs the plain instantiation's speed (-14 % measured), hence two instantiations.
+// waves whose fragment registers hold it XOR the word in those registers just before THAT
+// trial's MFMAs and XOR it back after them - the trial sees the MFMA inputs a trial of its own
+// would have staged, the other trials see clean ones.  The extra code sits in copies of the
+// k-tile that only waves with an event in the current item execute; two instantiations keep
+// it out of the plain one altogether.
 //
 // Work item = (output tile, group of R trials).  The register budget (R*TM*TN*16 accumulator
-// VGPRs per lane) admits one workgroup per CU, so nothing would hide a workgroup's start-up
-// (descriptor fetch, first operand tile) or wind-down behind another's MFMAs.  Instead the grid
-// is one workgroup per CU and each walks its items with the k-loop running straight through:
-// during the last k-tile of an item the first k-tile of the next item is already loading into
-// the free LDS stage, and the next item's descriptors were fetched an item earlier.
+// VGPRs per lane) admits one or two workgroups per CU, so little would hide a workgroup's
+// start-up (descriptor fetch, first operand tile) or wind-down behind another's MFMAs.  Instead
+// the grid is one or two workgroups per CU and each walks its items with the k-loop running
+// straight through: during the last k-tile of an item the first k-tile of the next item is
+// already loading into the free LDS stage, and the next item's descriptors were fetched earlier.
 //
 // The per-element arithmetic is that of gemm_fi_kernel: the same sequence of
 // v_mfma_f32_32x32x16 steps in ascending k, hence bit-identical fault-free results.
@@ -61,6 +63,9 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   // Fetch the epilogue's threshold inputs when an item starts (hides their latency) where the
   // register budget has room for them; else when the epilogue starts.
   constexpr bool EARLY_T = TM * TN == 1;
+  // The threshold inputs of the whole wave tile sit in registers during the epilogue (else they
+  // are loaded tile by tile: 8 tiles' worth would spill).
+  constexpr bool HAVE_T = TM * TN <= 4;
   // Large wave tiles leave few registers: the next item is located (its staging offsets
   // computed, its descriptors requested) just before the current item's last k-tile instead of
   // a whole item ahead, and golden values are fetched in the epilogue instead of up front.
@@ -412,7 +417,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   // deviation counters where the trial's fault can reach.  Thresholds are the same for every
   // trial (same rows and columns), so they are formed once; elements outside the problem get
   // T = +Inf and, in ragged tiles, a zeroed accumulator (clamped staging rows made them copies
-  // of the last row).  kra4 / cbj were fetched when the item started.
+  // of the last row).  kra4 / cbj: the rows' and columns' threshold factors this lane needs.
   f32x4 kra4[TM][4];
   float cbj[TN];
   auto fetch_threshold_inputs = [&]() {                 // arrays are padded: no guards
@@ -427,6 +432,9 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     for (int j = 0; j < TN; ++j) cbj[j] = p.cb[min(col_base + 32 * j, p.N - 1)];
   };
   auto epilogue = [&]() {
+    // Larger wave tiles have no registers for the threshold inputs while the k-loop runs: they
+    // are fetched here, all at once (one memory round trip for the whole item, not one per tile).
+    if constexpr (HAVE_T && !EARLY_T) fetch_threshold_inputs();
     const int m0 = cur.m0, n0 = cur.n0;
     const int row_base = m0 + wm * WTM + 4 * lhi;       // + 32*i + 8*q + e
     const int col_base = n0 + wn * WTN + l32;           // + 32*j
@@ -435,12 +443,11 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
       constexpr int i = tt / TN, j = tt % TN;
       const int col = col_base + 32 * j;
       f32x16 T;
-      // large wave tiles: the inputs of one 32 x 32 tile at a time, when it is looked at
-      const float cb_here = EARLY_T ? cbj[j] : p.cb[min(col, p.N - 1)];
+      const float cb_here = HAVE_T ? cbj[j] : p.cb[min(col, p.N - 1)];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const f32x4 kra_here =
-            EARLY_T ? kra4[i][q] : *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
+            HAVE_T ? kra4[i][q] : *reinterpret_cast<const f32x4*>(p.kra + row_base + 32 * i + 8 * q);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int row = row_base + 32 * i + 8 * q + e;
@@ -465,6 +472,33 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     // Detector (and corrector, when outputs are wanted) on every element of every trial.  Without
     // outputs the common case costs one compare and one scalar OR per element: lane masks of
     // the flags are merged, and only a trial-tile with any flag set is counted exactly.
+    // PROP: the fault-free words of this wave's 32 x 32 tiles travel kGoldAhead tiles ahead of
+    // their use; the first ones are requested here, before the detector pass.
+    constexpr int kGoldAhead = 2;
+    [[maybe_unused]] f32x16 cs_buf[PROP ? kGoldAhead + 1 : 1];
+    // They come through buffer loads: the lane's part of the address is one 32-bit offset for the
+    // whole item, the tile's and row's part is scalar - no vector address arithmetic, no address
+    // registers per load.  The allocation is padded to whole tiles, so rows and columns beyond a
+    // ragged problem read allocated memory (such elements are never compared).
+    const __amdgpu_buffer_rsrc_t rsrc_gold =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.c_star), 0, (int)p.c_star_bytes, 0x00020000);
+    const int gold_lane = (4 * lhi * p.N + l32) * 4;                  // bytes
+    auto load_golden = [&](auto tt, f32x16& dst) __attribute__((always_inline)) {
+      constexpr int i = tt / TN, j = tt % TN;
+      const uint32_t tile_off = __builtin_amdgcn_readfirstlane(
+          (int)((((uint32_t)(m0 + wm * WTM + 32 * i) * (uint32_t)p.N) + (uint32_t)(n0 + wn * WTN + 32 * j)) * 4u));
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const uint32_t row_off = (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N * 4u;
+        dst[v] = __uint_as_float(
+            __builtin_amdgcn_raw_buffer_load_b32(rsrc_gold, gold_lane, (int)(tile_off + row_off), 0));
+      }
+    };
+    if constexpr (PROP) {
+      static_for<kGoldAhead>([&](auto tt) {
+        if constexpr (tt < TM * TN) load_golden(tt, cs_buf[tt]);
+      });
+    }
     uint32_t n_flag[R];
     static_for<R>([&](auto rr) { n_flag[rr] = 0; });
     auto detect = [&](auto with_out) __attribute__((always_inline)) {
@@ -509,27 +543,17 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     });
     if constexpr (PROP) {
       // Every element of the trial's output against the fault-free result.  Two phases per
-      // 32 x 32 tile: the fault-free words are fetched one tile ahead and compared bit for bit
+      // 32 x 32 tile: the fault-free words (requested tiles ahead) are compared bit for bit
       // (most tiles of most trials are untouched by what the previous layer's fault changed: no
       // counter can move there); only a tile with a differing (or NaN) element runs the full
       // accounting, four rows at a time so that it needs few registers.
       uint32_t n_bit = 0, n_pre = 0, n_post = 0, n_bT = 0, n_btau = 0;
       float mx_pre = 0.0f, mx_post = 0.0f;
-      f32x16 cs_buf[2];
-      auto load_golden = [&](auto tt, f32x16& dst) __attribute__((always_inline)) {
-        constexpr int i = tt / TN, j = tt % TN;
-        const int col = min(col_base + 32 * j, p.N - 1);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = min(row_base + 32 * i + 8 * (v >> 2) + (v & 3), p.M - 1);
-          dst[v] = p.c_star[(size_t)row * p.N + col];
-        }
-      };
-      load_golden(std::integral_constant<int, 0>{}, cs_buf[0]);
       static_for<TM * TN>([&](auto tt) {
-        constexpr int i = tt / TN, j = tt % TN, cb = tt % 2;
+        constexpr int i = tt / TN, j = tt % TN, cb = tt % (kGoldAhead + 1);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (tt + 1 < TM * TN) load_golden(std::integral_constant<int, tt + 1>{}, cs_buf[cb ^ 1]);
+        if constexpr (tt + kGoldAhead < TM * TN)
+          load_golden(std::integral_constant<int, tt + kGoldAhead>{}, cs_buf[(tt + kGoldAhead) % (kGoldAhead + 1)]);
         const f32x16 t = acc[0][i][j];
         const f32x16 cs = cs_buf[cb];
         const int col = col_base + 32 * j;
@@ -545,8 +569,8 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
             constexpr int q = qq;
             __builtin_amdgcn_sched_barrier(0);
             const int row0 = row_base + 32 * i + 8 * q;
-            const f32x4 kra_q = *reinterpret_cast<const f32x4*>(p.kra + row0);
-            const float cb_j = p.cb[min(col, p.N - 1)];
+            const f32x4 kra_q = HAVE_T ? kra4[i][q] : *reinterpret_cast<const f32x4*>(p.kra + row0);
+            const float cb_j = HAVE_T ? cbj[j] : p.cb[min(col, p.N - 1)];
             float sa[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
