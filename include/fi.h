@@ -201,6 +201,21 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
                                uint32_t policy, fi_trial_result* d_results, float* d_c_out,
                                void* stream);
 
+/* fi_gemm_inject_batch with the hand-over to a next layer fused into its epilogue (Sec. I:
+ * what an error in one GEMM does to what is computed from it; Sec. V-B (i): activations zero
+ * many values): instead of FP32 outputs it writes d_h_out[t][i][j] = RNE_fmt(relu(c)), c the
+ * corrected output (policy FI_CORRECT_NONE: the raw faulty one) - 16-bit words of the plan's
+ * operand format, [n_trials][M][N], device memory owned by the caller.  Bit-identical to
+ * fi_gemm_inject_batch with d_c_out followed by fi_activation_round, without writing and
+ * re-reading 4 bytes per element.  Records as fi_gemm_inject_batch.  Allocation and
+ * synchronisation as fi_gemm_inject_batch (per-stream scratch).
+ * Errors: INVALID_ARG (NULLs, bad policy, n_trials == 0); UNSUPPORTED when d_h_out is not
+ * 2-byte aligned or the plan runs the one-trial kernel (K not a multiple of 64, or
+ * fi_plan_tune(plan, 2, ...)). */
+fi_status fi_gemm_inject_batch_act(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
+                                   uint32_t policy, fi_trial_result* d_results, void* d_h_out,
+                                   void* stream);
+
 /* fi_gemm_inject_batch for callers that cannot allocate device memory or synchronise: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, same kernels, same records and outputs; the trial order, the part counts and the

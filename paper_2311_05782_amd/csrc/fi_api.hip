@@ -375,7 +375,8 @@ fi_status check_batch_args(const fi_plan* plan, const fi_fault* d_faults, uint32
 // One campaign batch: record fill, then either the partition kernel and the two launches of
 // the multi-trial kernel (scratch in `ts`), or one launch of the one-trial kernel.
 fi_status inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
-                       fi_trial_result* d_results, float* d_c_out, hipStream_t s, const TrialScratch& ts) {
+                       fi_trial_result* d_results, float* d_c_out, hipStream_t s, const TrialScratch& ts,
+                       uint16_t* d_h_out = nullptr) {
   GemmArgs a = base_args(plan);
   const uint64_t blocks = (uint64_t)a.tiles_m * a.tiles_n * n_trials;
   if (blocks >= (1ull << 31)) return fail(FI_UNSUPPORTED, "tiles x trials exceeds 2^31 workgroups; split the batch");
@@ -404,6 +405,7 @@ fi_status inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trial
     g->faults = d_faults;
     g->results = d_results;
     g->c_out = d_c_out;
+    g->h_out = d_h_out;
     g->policy = (int)policy;
     g->product_check = plan->product_check;
   }
@@ -666,6 +668,24 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
   return inject_batch(plan, d_faults, n_trials, policy, d_results, d_c_out, as_stream(stream), ts);
 }
 
+fi_status fi_gemm_inject_batch_act(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
+                                   fi_trial_result* d_results, void* d_h_out, void* stream) {
+  fi_status st = check_batch_args(plan, d_faults, n_trials, policy, d_results);
+  if (st != FI_OK) return st;
+  if (!d_h_out) return fail(FI_INVALID_ARG, "d_h_out is NULL");
+  if (reinterpret_cast<uintptr_t>(d_h_out) & 1u) return fail(FI_UNSUPPORTED, "d_h_out must be 2-byte aligned");
+  if (plan->mcfg < 0)
+    return fail(FI_UNSUPPORTED, "the fused hand-over needs K to be a multiple of 64 (and a tile_config that is "
+                "not 2); use fi_gemm_inject_batch with d_c_out and fi_activation_round");
+  BatchScratch* bs = nullptr;
+  st = batch_scratch(plan, as_stream(stream), n_trials, &bs);
+  if (st != FI_OK) return st;
+  TrialScratch ts;
+  ts.perm = bs->perm; ts.counts = bs->perm + bs->cap; ts.desc = bs->desc;
+  return inject_batch(plan, d_faults, n_trials, policy, d_results, nullptr, as_stream(stream), ts,
+                      static_cast<uint16_t*>(d_h_out));
+}
+
 fi_status fi_gemm_inject_batch_noalloc(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials, uint32_t policy,
                                        fi_trial_result* d_results, float* d_c_out, void* stream) {
   fi_status st = check_batch_args(plan, d_faults, n_trials, policy, d_results);
@@ -748,7 +768,7 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
     return fail(FI_INVALID_ARG, "trial_stride %llu is smaller than one operand ((M-1)*lda + K elements)",
                 (unsigned long long)trial_stride);
   GemmArgs a = base_args(plan);
-  const bool persistent = plan->prop_cfg >= 0 && a.c_star_bytes != 0;
+  const bool persistent = plan->prop_cfg >= 0 && a.c_star_bytes != 0;   // C* is addressed with 32 bits
   if (persistent) {
     const MultiCfg mc = kMulti[plan->prop_cfg];
     a.tiles_m = (a.M + mc.bm - 1) / mc.bm;

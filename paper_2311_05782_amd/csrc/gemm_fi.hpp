@@ -67,6 +67,10 @@ struct GemmArgs {
   // tile width, so that a tile reaching over the edge of a ragged problem reads allocated memory.
   uint32_t c_star_bytes;
   float* c_out;             // campaign: nullable [n_trials][M][N]; golden: [M][N]
+  // Campaign (multi-trial kernel), nullable: [n_trials][M][N] words of the operand format, the
+  // corrected output after ReLU and rounding - the next layer's operand, written by the epilogue
+  // instead of an FP32 output that a second kernel would read back.
+  uint16_t* h_out;
   int policy;
   int product_check;        // FI_PCHECK_* applied to the erroneous product of PRODUCT faults
   // For the multi-trial kernel: the batch split in two parts (trials that leave the operands

@@ -520,7 +520,36 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                 n_flag[r] += (uint32_t)__builtin_popcountll(__ballot(!(fabsf(t[v]) <= T[v])));
             }
             if constexpr (OUT) {
-              float* cout = p.c_out + (size_t)trial[r] * (size_t)p.M * (size_t)p.N;
+              const size_t out0 = (size_t)trial[r] * (size_t)p.M * (size_t)p.N;
+              // Nearly every trial-tile: nothing flagged, no ragged edge.  The values go out as
+              // they are, through buffer stores whose address is a per-item lane offset plus a
+              // scalar (trial, tile, row) offset: no vector arithmetic, no branch per element.
+              if (any == 0 && !ragged && p.c_star_bytes != 0) {
+                const uint32_t tile_off = (uint32_t)(m0 + wm * WTM + 32 * i) * (uint32_t)p.N +
+                                          (uint32_t)(n0 + wn * WTN + 32 * j);           // elements
+                const int lane_off = 4 * lhi * p.N + l32;
+                const uint32_t mn = (uint32_t)p.M * (uint32_t)p.N;
+                if (p.c_out) {
+                  const __amdgpu_buffer_rsrc_t rs =
+                      __builtin_amdgcn_make_buffer_rsrc(p.c_out + out0, 0, (int)(mn * 4u), 0x00020000);
+#pragma unroll
+                  for (int v = 0; v < 16; ++v)
+                    __builtin_amdgcn_raw_buffer_store_b32(
+                        __float_as_uint(t[v]), rs, lane_off * 4,
+                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 4u), 0);
+                }
+                if (p.h_out) {
+                  const __amdgpu_buffer_rsrc_t rs =
+                      __builtin_amdgcn_make_buffer_rsrc(p.h_out + out0, 0, (int)(mn * 2u), 0x00020000);
+#pragma unroll
+                  for (int v = 0; v < 16; ++v) {
+                    const float cc = t[v];
+                    __builtin_amdgcn_raw_buffer_store_b16(
+                        (unsigned short)round16<DT>((cc > 0.0f || cc != cc) ? cc : 0.0f), rs, lane_off * 2,
+                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 2u), 0);
+                  }
+                }
+              } else
 #pragma unroll
               for (int v = 0; v < 16; ++v) {
                 const int row = row_base + 32 * i + 8 * (v >> 2) + (v & 3);
@@ -529,14 +558,20 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                   if (p.policy == FI_CORRECT_ZERO) cc = 0.0f;
                   else if (p.policy == FI_CORRECT_RECOMPUTE) cc = p.c_star[(size_t)row * p.N + col];
                 }
-                if (row < p.M && col < p.N) cout[(size_t)row * p.N + col] = cc;
+                if (row < p.M && col < p.N) {
+                  const size_t at = out0 + (size_t)row * p.N + col;
+                  if (p.c_out) p.c_out[at] = cc;
+                  // the hand-over between two layers fused into this epilogue: relu keeps a NaN
+                  // and maps negatives and -0 to +0, then the integer round-to-format
+                  if (p.h_out) p.h_out[at] = (uint16_t)round16<DT>((cc > 0.0f || cc != cc) ? cc : 0.0f);
+                }
               }
             }
           }
         });
       });
     };
-    if (p.c_out) detect(std::true_type{}); else detect(std::false_type{});
+    if (p.c_out || p.h_out) detect(std::true_type{}); else detect(std::false_type{});
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
       if (r < n_act && n_flag[r] != 0 && lane == 0) atomicAdd(&p.results[trial[r]].n_flagged, n_flag[r]);

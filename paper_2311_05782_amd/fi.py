@@ -28,7 +28,7 @@ BUF_C_STAR, BUF_S_ABS, BUF_KRA, BUF_CB = 0, 1, 2, 3
 # Symbols include/fi.h declares; the loader checks every one.
 EXPORTS = ["fi_plan_create", "fi_plan_destroy", "fi_plan_buffer", "fi_plan_tune", "fi_plan_describe",
            "fi_plan_set_product_check", "fi_plan_reserve", "fi_plan_set_clock_sink", "fi_probe_mfma_loop", "fi_deviation_histogram",
-           "fi_gemm_inject_batch", "fi_gemm_inject_batch_noalloc", "fi_gemm_inject_batch_affected", "fi_detect_correct", "fi_classify", "fi_sample_faults",
+           "fi_gemm_inject_batch", "fi_gemm_inject_batch_act", "fi_gemm_inject_batch_noalloc", "fi_gemm_inject_batch_affected", "fi_detect_correct", "fi_classify", "fi_sample_faults",
            "fi_activation_round", "fi_gemm_propagate_batch", "fi_last_error", "fi_build_info"]
 
 FAULT_DTYPE = np.dtype([("kind", "<u4"), ("row", "<u4"), ("col", "<u4"), ("kblock", "<u4"),
@@ -95,6 +95,7 @@ def lib():
     L.fi_probe_mfma_loop.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch_noalloc.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
+    L.fi_gemm_inject_batch_act.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_gemm_inject_batch_affected.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp]
     L.fi_detect_correct.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, vp, vp]
     L.fi_activation_round.argtypes = [C.c_uint32, vp, C.c_uint64, vp, vp]
@@ -211,6 +212,10 @@ class Plan:
     def fi_gemm_inject_batch(self, d_faults, n_trials, policy, d_results, d_c_out=None, stream=None):
         _check(lib().fi_gemm_inject_batch(self._h, _dptr(d_faults), n_trials, policy, _dptr(d_results),
                                           _dptr(d_c_out), _stream(stream)))
+
+    def fi_gemm_inject_batch_act(self, d_faults, n_trials, policy, d_results, d_h_out, stream=None):
+        _check(lib().fi_gemm_inject_batch_act(self._h, _dptr(d_faults), n_trials, policy, _dptr(d_results),
+                                              _dptr(d_h_out), _stream(stream)))
 
     def fi_gemm_inject_batch_noalloc(self, d_faults, n_trials, policy, d_results, d_c_out=None, stream=None):
         _check(lib().fi_gemm_inject_batch_noalloc(self._h, _dptr(d_faults), n_trials, policy, _dptr(d_results),

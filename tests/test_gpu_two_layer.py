@@ -129,6 +129,13 @@ def test_two_layers_end_to_end_against_the_oracle_chain(fmt):
     recs1, c1 = gu.gpu_campaign(plan1, faults, orc.CORRECT_ZERO, want_c=True)
     h_gpu = _activation_gpu(c1, fmt)
     hstar_gpu = _activation_gpu(plan1.buffer_to_host(fi.BUF_C_STAR), fmt)
+    # the fused form of the same two calls hands on the same words and the same records
+    d_hf = torch.empty((n, M, H), dtype=torch.int16, device="cuda")
+    d_rf = fi.empty_results(n)
+    plan1.fi_gemm_inject_batch_act(fi.to_device(faults), n, orc.CORRECT_ZERO, d_rf, d_hf)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_hf.cpu().numpy().view(np.uint16), h_gpu)
+    assert fi.results_to_host(d_rf).tobytes() == recs1.tobytes()
     # the oracle's chain
     of = gu.to_orc_faults(faults)
     occ = np.stack([orc.trial(p1, Xw, W1w, of[t:t + 1], orc.CORRECT_ZERO, want_outputs=True)[2] for t in range(n)])
@@ -149,6 +156,63 @@ def test_two_layers_end_to_end_against_the_oracle_chain(fmt):
     assert (sdc1 & masked2).sum() > 5 and (sdc1 & ~masked2).sum() > 5
     assert not (~sdc1 & ~masked2 & (recs1["n_bitdiff"] == 0)).any()
     plan1.destroy(); plan2.destroy()
+
+
+@pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
+@pytest.mark.parametrize("cfg", [None, 0, 1, 3, 4, 5, 6])
+@pytest.mark.parametrize("shape", [(300, 200, 192, 32), (257, 65, 128, 64), (64, 64, 64, 16)])
+def test_fused_hand_over_equals_campaign_then_activation_round(fmt, cfg, shape):
+    # fi_gemm_inject_batch_act against fi_gemm_inject_batch + fi_activation_round: same words (NaN
+    # payloads included: both round the same corrected value with the same integer code), same
+    # records; Gaussian operands, every fault kind, flips that make Inf / NaN / negative values.
+    import torch
+    M, N, K, kb = shape
+    Aw, Bw = wl.gaussian(M, N, K, fmt, seed=M + N)
+    plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=cfg, group=3)
+    n = 61
+    rows = []
+    rng = np.random.default_rng(K + (cfg or 0))
+    for t in range(n):
+        kind = [orc.SITE_ACC, orc.SITE_A, orc.SITE_B, orc.SITE_PRODUCT, orc.SITE_NONE][t % 5]
+        i, j, k = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(K))
+        if kind == orc.SITE_ACC:
+            rows.append((kind, i, j, int(rng.integers(K // kb)), 1 << [30, 31, 23, 22, 29][t // 5 % 5]))
+        elif kind == orc.SITE_A:
+            rows.append((kind, i, k, 0, [0x4000, 0x8000, 0x0200][t // 5 % 3]))
+        elif kind == orc.SITE_B:
+            rows.append((kind, k, j, 0, [0x4000, 0x8000, 0x0200][t // 5 % 3]))
+        elif kind == orc.SITE_PRODUCT:
+            rows.append((kind, i, j, k, 0x4000))
+        else:
+            rows.append((kind, 0, 0, 0, 0))
+    faults = orc.make_faults(rows)
+    d_f = fi.to_device(faults)
+    for policy in (orc.CORRECT_NONE, orc.CORRECT_ZERO, orc.CORRECT_RECOMPUTE):
+        d_c = torch.empty((n, M, N), dtype=torch.float32, device="cuda")
+        d_h2 = torch.empty((n, M, N), dtype=torch.int16, device="cuda")
+        d_h1 = torch.full((n, M, N), 0x5555, dtype=torch.int16, device="cuda")
+        r1, r2 = fi.empty_results(n), fi.empty_results(n)
+        plan.fi_gemm_inject_batch(d_f, n, policy, r2, d_c)
+        fi.fi_activation_round(fmt, d_c, n * M * N, d_h2)
+        plan.fi_gemm_inject_batch_act(d_f, n, policy, r1, d_h1)
+        torch.cuda.synchronize()
+        assert torch.equal(d_h1, d_h2), (policy, int((d_h1 != d_h2).sum()))
+        assert fi.results_to_host(r1).tobytes() == fi.results_to_host(r2).tobytes()
+        c = d_c.cpu().numpy()
+        if policy == orc.CORRECT_NONE:
+            assert np.isnan(c).any() or np.isinf(c).any()        # the specials were really there
+    plan.destroy()
+
+
+def test_fused_hand_over_is_refused_where_the_one_trial_kernel_runs():
+    Aw, Bw = wl.gaussian(64, 64, 96, orc.BF16, seed=5)           # K = 96: a ragged k-tile
+    plan = gu.make_plan(Aw, Bw, 32, orc.BF16)
+    import torch
+    d_h = torch.empty((2, 64, 64), dtype=torch.int16, device="cuda")
+    with pytest.raises(fi.FiError):
+        plan.fi_gemm_inject_batch_act(fi.to_device(orc.make_faults([(orc.SITE_NONE, 0, 0, 0, 0)] * 2)), 2, 0,
+                                      fi.empty_results(2), d_h)
+    plan.destroy()
 
 
 def test_the_chain_replays_correctly_from_a_hip_graph():
