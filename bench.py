@@ -27,9 +27,9 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "21997ad0578a4db3073c4f1c6ffe29dd911d6514a88fc69d13c05e8b4e760ed4",
-    "fetch_bytes": 2.18893e6 * 2.0 * 1024,
-    "write_bytes": 151.312 * 1.0 * 1024,
+    "sources_sha256": "134c0fde9e36a9af4861958cd43901c9f5651bad82652ed72ea623f9fd2147c8",
+    "fetch_bytes": 2.16748e6 * 2.0 * 1024,
+    "write_bytes": 151.375 * 1.0 * 1024,
 }
 
 
