@@ -258,9 +258,18 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
   __shared__ uint32_t bucket[1024];
   const uint32_t tiles_m = (M + bm - 1) / bm, n_keys = tiles_m + (N + bn - 1) / bn;
   uint32_t key_shift = 0;
-  while ((n_keys >> key_shift) > 1024u) ++key_shift;
+  while (((n_keys - 1u) >> key_shift) >= 1024u) ++key_shift;
+  const uint32_t n_major = ((n_keys - 1u) >> key_shift) + 1u;            // <= 1024
+  // Inside a tile row / column the trials are ordered by the 64-wide k-tile of the faulted word
+  // (as finely as the buckets left over allow): the R trials of a group then have their events
+  // in the same k-tile or in neighbouring ones, and a work item runs one or two k-tiles of the
+  // checking copy of the loop instead of up to R.
+  const uint32_t n_kt = (K + 63) / 64;
+  const uint32_t kq = max(1u, min(n_kt, 1024u / n_major));               // keys < n_major * kq <= 1024
   auto key_of = [&](const fi_fault& x) -> uint32_t {
-    return (x.kind == FI_SITE_A ? x.row / bm : tiles_m + x.col / bn) >> key_shift;
+    const uint32_t major = (x.kind == FI_SITE_A ? x.row / bm : tiles_m + x.col / bn) >> key_shift;
+    const uint32_t kt = min((x.kind == FI_SITE_A ? x.col : x.row) / 64u, n_kt - 1u);
+    return major * kq + kt * kq / n_kt;
   };
   bucket[threadIdx.x] = 0;
   __syncthreads();

@@ -670,6 +670,26 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     if (owned == 0) return;
     float mxp[R], mxq[R];                                   // per lane: largest deviation before / after correction
     static_for<R>([&](auto rr) { mxp[rr] = 0.0f; mxq[rr] = 0.0f; });
+    // B-operand faults reach one output column.  Lane k < 32 takes row k of each 32-row tile of
+    // this wave: its threshold factor, and per trial the fault-free value and the magnitude sum
+    // of (row, faulted column) - requested for all trials before any is looked at, so that the
+    // trials share one memory round trip.
+    constexpr bool COL_GATHER = OPS && TM * TN <= 4;
+    [[maybe_unused]] float col_kra[TM], col_cs[COL_GATHER ? R : 1][TM], col_sa[COL_GATHER ? R : 1][TM];
+    if constexpr (COL_GATHER) {
+      static_for<TM>([&](auto ii) { col_kra[ii] = p.kra[m0 + wm * WTM + 32 * ii + l32]; });   // padded array
+      static_for<R>([&](auto rr) {
+        constexpr int r = rr;
+        if (((owned >> r) & 1u) && ((desc_field(r, 3) >> 29) & 1u) && desc_field(r, 5) == FI_SITE_B) {
+          const size_t col = desc_field(r, 2);
+          static_for<TM>([&](auto ii) {
+            const size_t idx = (size_t)min(m0 + wm * WTM + 32 * ii + l32, p.M - 1) * (size_t)p.N + col;
+            col_cs[r][ii] = p.c_star[idx];
+            col_sa[r][ii] = p.s_abs[idx];
+          });
+        }
+      });
+    }
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
       if ((owned >> r) & 1u) {
@@ -731,8 +751,36 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
               account(lhi == sel_hi && (!need_col || col == site_col) && col < p.N, c, Tv, cs, sabs);
             }
           });
-        } else {
-          // One column: the lanes holding it read their rows' golden values; the other lanes read
+        } else if constexpr (COL_GATHER) {
+          // One column: it lives in one 32-column tile and one lane of each half-wave, spread
+          // over the 16 accumulator registers (rows).  Its 32 values per tile are gathered into
+          // lanes 0 .. 31 (row k to lane k) and accounted for in one pass.
+          const int wc = site_col - n0 - wn * WTN;            // 0 .. WTN-1: this wave holds the column
+          const int sel = wc & 31;
+          const float cb_c = p.cb[site_col];
+          static_for<TM * TN>([&](auto tt) {
+            constexpr int i = tt / TN, j = tt % TN;
+            if (j == (wc >> 5)) {
+              const f32x16 t = acc[r][i][j];
+              int x = 0;
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int w = (int)__float_as_uint(t[v]);
+                const int k0 = 8 * (v >> 2) + (v & 3);          // row of register v in lanes 0 .. 31; + 4 in lanes 32 .. 63
+                const int s_lo = __builtin_amdgcn_readlane(w, sel), s_hi = __builtin_amdgcn_readlane(w, sel + 32);
+                x = lane == k0 ? s_lo : x;
+                x = lane == k0 + 4 ? s_hi : x;
+              }
+              const int row = m0 + wm * WTM + 32 * i + l32;
+              const float Tv = row >= p.M        ? __builtin_inff()
+                               : p.bound_global ? p.t_global
+                                                : __fmul_rn(__fmul_rn(col_kra[i], cb_c), p.gamma);
+              account(lane < 32 && row < p.M, __uint_as_float((uint32_t)x), Tv, col_cs[r][i], col_sa[r][i]);
+            }
+          });
+        } else if constexpr (OPS) {
+          // One column, wave tiles of 8 accumulator tiles (no registers to spare for the gather):
+          // the lanes holding the column read their rows' golden values; the other lanes read
           // their own columns of the same rows (same cache lines) and count nothing.
           static_for<TM * TN>([&](auto tt) {
             constexpr int i = tt / TN, j = tt % TN;

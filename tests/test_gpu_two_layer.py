@@ -261,4 +261,19 @@ def test_the_chain_replays_correctly_from_a_hip_graph():
             g.replay()
             torch.cuda.synchronize()
             assert (fi.results_to_host(r1).tobytes(), fi.results_to_host(r2).tobytes()) == eager[k], (rep, k)
+    # the two-call form (hand-over fused into the campaign) captured the same way
+    def fused(stream=None):
+        plan1.fi_gemm_inject_batch_act(d_f, n, orc.CORRECT_ZERO, r1, d_h, stream=stream)
+        plan2.fi_gemm_propagate_batch(d_h, M * H, n, orc.CORRECT_NONE, r2, stream=stream)
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g2, stream=side):
+            fused(stream=torch.cuda.current_stream().cuda_stream)
+    for k, f in enumerate(lists):
+        d_f.copy_(fi.to_device(f))
+        r1.zero_(); r2.fill_(0xFF); d_h.fill_(0x1234)
+        torch.cuda.synchronize()
+        g2.replay()
+        torch.cuda.synchronize()
+        assert (fi.results_to_host(r1).tobytes(), fi.results_to_host(r2).tobytes()) == eager[k], ("fused", k)
     plan1.destroy(); plan2.destroy()
