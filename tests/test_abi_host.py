@@ -87,12 +87,16 @@ def test_argument_errors_need_no_device():
     assert _status(lambda: fi._check(L.fi_gemm_propagate_batch(None, A, 0, 1, 0, B, None, None)))[0] == fi.INVALID_ARG
     assert _status(lambda: fi._check(L.fi_gemm_inject_batch_affected(None, A, 1, 0, B, None)))[0] == fi.INVALID_ARG
     assert _status(lambda: fi._check(L.fi_plan_reserve(None, 16, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_gemm_inject_batch_act(None, A, 1, 0, B, A, None)))[0] == fi.INVALID_ARG
+    assert _status(lambda: fi._check(L.fi_gemm_inject_batch_noalloc(None, A, 1, 0, B, None, None)))[0] == fi.INVALID_ARG
     # a handle that is not a live plan (never created, or destroyed) is looked up, not dereferenced
     bogus = C.c_void_p(0x1000)
     assert _status(lambda: fi._check(L.fi_plan_destroy(bogus)))[0] == fi.STATE
     assert _status(lambda: fi._check(L.fi_plan_reserve(bogus, 16, None)))[0] == fi.STATE
     assert _status(lambda: fi._check(L.fi_gemm_inject_batch(bogus, A, 1, 0, B, None, None)))[0] == fi.STATE
     assert _status(lambda: fi._check(L.fi_classify(bogus, A, 1, None, B, None)))[0] == fi.STATE
+    assert _status(lambda: fi._check(L.fi_gemm_inject_batch_act(bogus, A, 1, 0, B, A, None)))[0] == fi.STATE
+    assert _status(lambda: fi._check(L.fi_gemm_inject_batch_noalloc(bogus, A, 1, 0, B, None, None)))[0] == fi.STATE
     # the hand-over kernel's arguments
     assert _status(lambda: fi._check(L.fi_activation_round(2, A, 16, B, None)))[0] == fi.UNSUPPORTED
     assert _status(lambda: fi._check(L.fi_activation_round(fi.BF16, None, 16, B, None)))[0] == fi.INVALID_ARG
