@@ -238,7 +238,7 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
 // with fault-free entries up to the next multiple of 8 positions.  The operand faults' descriptors
 // follow from that position on: event = k/16 with bit 29 set, w0 = the 16-bit mask, w1 = kind;
 // their site words (the operand word before and after) are written here.  B is [N][ldb], k contiguous.
-// One workgroup; each thread owns a contiguous chunk of the list.
+// One workgroup.
 template <int DT>
 __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* __restrict__ f, uint32_t n,
                                                                uint32_t M, uint32_t N, uint32_t K, uint32_t kb,
@@ -250,7 +250,6 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
                                                                uint32_t* __restrict__ counts,
                                                                uint32_t* __restrict__ desc,
                                                                fi_trial_result* __restrict__ results) {
-  __shared__ uint32_t offs[1024];
   __shared__ uint32_t total_fast;
   // Operand faults are ordered by the tile row (A) or tile column (B) their fault reaches, so
   // that the R trials of a group mostly share it: the other tiles' work items then carry no
@@ -284,41 +283,100 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
     if (x.kind == FI_SITE_B) return (x.row < K && x.col < N) ? 0 : 3;
     return x.kind == FI_SITE_NONE ? 1 : 3;
   };
-  uint32_t c = 0;
-  for (uint32_t t = lo; t < hi; ++t) {
-    const fi_fault x = f[t];
-    if (kind_of(x) != 0) c += 1u;
-    else atomicAdd(&bucket[key_of(x)], 1u);
+  // Batches of up to 8 x 1024 trials: step i of thread tid looks at trial i * 1024 + tid, so a
+  // wave reads 64 consecutive fault records and writes the descriptors of consecutive positions
+  // (a thread walking a contiguous chunk of its own made every access of a wave touch 64
+  // different cache lines: 40 us for 8192 trials, most of it this one CU's memory pipeline).  The
+  // records are read once, all loads in flight together, and kept in registers for both passes.
+  // Positions in the first part follow list order: a table of counts per (step, wave), scanned
+  // once, plus the lane's rank among the wave's fast trials of that step.  Longer batches: each
+  // thread walks a contiguous chunk, reading it in place.
+  constexpr int kLocal = 8;
+  const bool local = n <= (uint32_t)kLocal * 1024u;
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  __shared__ uint32_t tab[kLocal * 16];
+  fi_fault loc[kLocal];
+  uint32_t wa[kLocal], wb[kLocal];          // operand words the second pass needs
+  unsigned long long fast_mask[kLocal];     // the wave's fast trials of step i
+  uint32_t c = 0;                           // long batches: fast trials in my chunk
+  auto operand_words = [&](const fi_fault& x, int k, uint32_t& w0, uint32_t& w1) {
+    w0 = 0; w1 = 0;
+    if (k == 0) w0 = x.kind == FI_SITE_A ? A[(size_t)x.row * lda + x.col] : B[(size_t)x.col * ldb + x.row];
+    if (k == 4) { w0 = A[(size_t)x.row * lda + x.kblock]; w1 = B[(size_t)x.col * ldb + x.kblock]; }
+  };
+  if (local) {
+#pragma unroll
+    for (int i = 0; i < kLocal; ++i) {
+      const uint32_t t = (uint32_t)i * 1024u + threadIdx.x;
+      fi_fault x;
+      x.kind = 0xFFFFFFFFu; x.row = 0; x.col = 0; x.kblock = 0; x.xor_mask = 0;
+      if (t < n) x = f[t];
+      loc[i] = x;
+    }
+#pragma unroll
+    for (int i = 0; i < kLocal; ++i) {
+      const bool valid = (uint32_t)i * 1024u + threadIdx.x < n;
+      const int k = valid ? kind_of(loc[i]) : 3;
+      wa[i] = 0; wb[i] = 0;
+      if (valid) operand_words(loc[i], k, wa[i], wb[i]);
+      fast_mask[i] = __ballot(valid && k != 0);
+      if (lane == 0) tab[i * 16 + wave] = (uint32_t)__builtin_popcountll(fast_mask[i]);
+      if (valid && k == 0) atomicAdd(&bucket[key_of(loc[i])], 1u);
+    }
+  } else {
+    for (uint32_t t = lo; t < hi; ++t) {
+      const fi_fault x = f[t];
+      if (kind_of(x) != 0) c += 1u;
+      else atomicAdd(&bucket[key_of(x)], 1u);
+    }
   }
-  offs[threadIdx.x] = c;
   __syncthreads();
-  // exclusive prefix sum of the buckets (Hillis-Steele, one bucket per thread)
+  // exclusive prefix sums of the buckets and of the per-thread counts, one entry per thread:
+  // a shuffle scan inside each wave, then one wave scans the 16 wave totals (three barriers)
+  uint32_t pf = 0;                                       // long batches: fast trials before my chunk
   {
-    const uint32_t own = bucket[threadIdx.x];
-    uint32_t incl = own;
-    for (int d = 1; d < 1024; d <<= 1) {
-      __syncthreads();
-      const uint32_t other = threadIdx.x >= (uint32_t)d ? bucket[threadIdx.x - d] : 0u;
-      __syncthreads();
-      incl += other;
-      bucket[threadIdx.x] = incl;
+    __shared__ uint32_t wave_tot[16], wave_tot_c[16];
+    auto wave_scan = [&](uint32_t v) -> uint32_t {       // inclusive
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t u = __shfl_up(v, o, 64);
+        v += lane >= (uint32_t)o ? u : 0u;
+      }
+      return v;
+    };
+    const uint32_t own = bucket[threadIdx.x], own_c = c;
+    uint32_t incl = wave_scan(own), incl_c = wave_scan(own_c);
+    if (lane == 63u) { wave_tot[wave] = incl; wave_tot_c[wave] = incl_c; }
+    __syncthreads();
+    if (wave == 0) {
+      const uint32_t v = lane < 16u ? wave_tot[lane] : 0u, vc = lane < 16u ? wave_tot_c[lane] : 0u;
+      const uint32_t sc = wave_scan(v), scc = wave_scan(vc);
+      if (lane < 16u) { wave_tot[lane] = sc - v; wave_tot_c[lane] = scc - vc; }
+      uint32_t total = scc;                              // long batches: read at lane 15
+      if (local) {
+        // the (step, wave) table in list order, two entries per lane
+        static_assert(kLocal * 16 == 128, "two table entries per lane");
+        const uint32_t a = tab[2 * lane], b = tab[2 * lane + 1];
+        const uint32_t st = wave_scan(a + b);
+        tab[2 * lane] = st - (a + b);
+        tab[2 * lane + 1] = st - b;
+        total = __shfl(st, 63, 64);
+      }
+      if (lane == 15u) {
+        total_fast = total;
+        counts[0] = total;
+        counts[1] = n - total;
+      }
     }
     __syncthreads();
-    bucket[threadIdx.x] = incl - own;
+    bucket[threadIdx.x] = incl - own + wave_tot[wave];
+    pf = incl_c - own_c + wave_tot_c[wave];
     __syncthreads();
   }
-  if (threadIdx.x == 0) {            // 1024 additions: negligible next to the batch itself
-    uint32_t run = 0;
-    for (int i = 0; i < 1024; ++i) { uint32_t v = offs[i]; offs[i] = run; run += v; }
-    total_fast = run;
-    counts[0] = run;
-    counts[1] = n - run;
-  }
-  __syncthreads();
-  uint32_t pf = offs[threadIdx.x];                       // fast trials before my chunk
   const uint32_t n_fast = total_fast;
-  for (uint32_t t = lo; t < hi; ++t) {
-    const fi_fault x = f[t];
+  // x: the fault of trial t; w0, w1: the operand words it needs (an operand fault: the faulted
+  // word; a product-term fault: a_ik and b_kj); q: its position if it belongs to the first part
+  auto place_one = [&](uint32_t t, const fi_fault& x, uint32_t w0, uint32_t w1, uint32_t q) {
     const int k = kind_of(x);
     if (k == 0) {
       // operand fault: second part of the batch; its descriptors start at the next multiple of 8
@@ -327,28 +385,44 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
       const uint32_t pos = atomicAdd(&bucket[key_of(x)], 1u);      // order inside a bucket is arbitrary
       uint32_t* d = desc + ((size_t)((n_fast + 7u) & ~7u) + pos) * 6;
       d[0] = t; d[1] = x.row; d[2] = x.col; d[3] = (kk / 16) | 0x20000000u; d[4] = m16; d[5] = x.kind;
-      const uint32_t w = isA ? A[(size_t)x.row * lda + x.col] : B[(size_t)x.col * ldb + x.row];
-      results[t].site_word_before = w;
-      results[t].site_word_after = w ^ m16;
+      results[t].site_word_before = w0;
+      results[t].site_word_after = w0 ^ m16;
       perm[n_fast + pos] = t;
-      continue;
+      return;
     }
-    uint32_t* d = desc + (size_t)pf * 6;
+    uint32_t* d = desc + (size_t)q * 6;
     d[0] = t; d[1] = x.row; d[2] = x.col;
     if (k == 2) {
       d[3] = (x.kblock + 1) * kb / 16 - 1; d[4] = x.xor_mask; d[5] = 0;
     } else if (k == 4) {
       float re, re_err;
       bool fired;
-      product_fault_terms<DT>(A[(size_t)x.row * lda + x.kblock], B[(size_t)x.col * ldb + x.kblock], x.xor_mask,
-                              product_check_mode, re, re_err, fired);
+      product_fault_terms<DT>((uint16_t)w0, (uint16_t)w1, x.xor_mask, product_check_mode, re, re_err, fired);
       if (fired) results[t].product_flag = 1;
       d[3] = (x.kblock / 16) | 0x40000000u; d[4] = __float_as_uint(re); d[5] = __float_as_uint(re_err);
     } else {
       d[3] = 0xFFFFFFFFu; d[4] = 0; d[5] = 0;
     }
     if (k == 3) results[t].status = 1;
-    perm[pf++] = t;
+    perm[q] = t;
+  };
+  if (local) {
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < kLocal; ++i) {
+      const uint32_t t = (uint32_t)i * 1024u + threadIdx.x;
+      if (t < n)
+        place_one(t, loc[i], wa[i], wb[i], tab[i * 16 + wave] + (uint32_t)__builtin_popcountll(fast_mask[i] & below));
+    }
+  } else {
+    for (uint32_t t = lo; t < hi; ++t) {
+      const fi_fault x = f[t];
+      const int k = kind_of(x);
+      uint32_t w0, w1;
+      operand_words(x, k, w0, w1);
+      place_one(t, x, w0, w1, pf);
+      if (k != 0) ++pf;
+    }
   }
   if (threadIdx.x < 16) {
     // fault-free padding behind each part, up to the next multiple of 8 positions
