@@ -278,9 +278,36 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     }
   };
 
+  // Lane-constant indices for the relevance test below: lane l looks at the descriptor of trial
+  // l / 6 (its words sit in lanes 6 * (l / 6) .. + 5 of desc_cur).
+  const int d_trial = lane / kMultiDescWords, d_base = d_trial * kMultiDescWords;
   auto decode = [&]() {
     n_act = min(R, n_fast - cur.grp * R);
     has_events = false;
+    if constexpr (!PROP) {
+      // Nearly every item holds no event of this wave.  One lane-parallel test over the R
+      // descriptors settles that (a few shuffles and compares, one ballot) instead of R
+      // scalar decodes of some 45 instructions each.
+      const int row = __shfl((int)desc_cur, d_base + 1, 64), col = __shfl((int)desc_cur, d_base + 2, 64);
+      const int ev = __shfl((int)desc_cur, d_base + 3, 64);
+      const int li = row - cur.m0, lj = col - cur.n0;
+      bool hit;
+      if (OPS && ((ev >> 29) & 1)) {
+        const bool isA = __shfl((int)desc_cur, d_base + 5, 64) == FI_SITE_A;
+        const int wl = isA ? li - wm * WTM : lj - wn * WTN;
+        hit = wl >= 0 && wl < (isA ? WTM : WTN);          // inside the wave's rows / columns of this tile
+      } else {
+        const int wi = li - wm * WTM, wj = lj - wn * WTN;
+        hit = wi >= 0 && wi < WTM && wj >= 0 && wj < WTN;
+      }
+      if (__ballot(hit && ev >= 0 && d_trial < n_act && lane < R * kMultiDescWords) == 0) {
+        static_for<R>([&](auto rr) {
+          trial[rr] = (int)desc_field(rr, 0);
+          hook_step[rr] = -1;
+        });
+        return;
+      }
+    }
     static_for<R>([&](auto rr) {
       constexpr int r = rr;
       trial[r] = (int)desc_field(r, 0);
