@@ -187,7 +187,15 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   // A group's R descriptors, one word per lane; fields are picked out with v_readlane.
   auto load_desc = [&](int grp) -> uint32_t {
     if constexpr (PROP) return lane == 0 ? (uint32_t)grp : lane == 3 ? 0xFFFFFFFFu : 0u;   // {trial, -, -, no event}
-    else return lane < R * kMultiDescWords ? desc[(size_t)grp * (R * kMultiDescWords) + lane] : 0u;
+    else {
+      // a buffer load: scalar base and group offset, the lane's word as a 32-bit offset (a 64-bit
+      // per-lane pointer kept across the k-loop cost two registers the 128 x 64 shape does not have)
+      const __amdgpu_buffer_rsrc_t rs =
+          __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(desc), 0, -1, 0x00020000);
+      const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(
+          rs, (lane < R * kMultiDescWords ? lane : 0) * 4, grp * (R * kMultiDescWords * 4), 0);
+      return lane < R * kMultiDescWords ? w : 0u;
+    }
   };
 
   // ---- fragments and accumulators
@@ -278,16 +286,16 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     }
   };
 
-  // Lane-constant indices for the relevance test below: lane l looks at the descriptor of trial
-  // l / 6 (its words sit in lanes 6 * (l / 6) .. + 5 of desc_cur).
-  const int d_trial = lane / kMultiDescWords, d_base = d_trial * kMultiDescWords;
   auto decode = [&]() {
     n_act = min(R, n_fast - cur.grp * R);
     has_events = false;
     if constexpr (!PROP) {
       // Nearly every item holds no event of this wave.  One lane-parallel test over the R
       // descriptors settles that (a few shuffles and compares, one ballot) instead of R
-      // scalar decodes of some 45 instructions each.
+      // scalar decodes of some 45 instructions each.  Lane l looks at the descriptor of trial
+      // l / 6, whose words sit in lanes 6 * (l / 6) .. + 5 of desc_cur (recomputed per item: two
+      // registers held across the k-loop would not fit the 128 x 64 shape).
+      const int d_trial = lane / kMultiDescWords, d_base = d_trial * kMultiDescWords;
       const int row = __shfl((int)desc_cur, d_base + 1, 64), col = __shfl((int)desc_cur, d_base + 2, 64);
       const int ev = __shfl((int)desc_cur, d_base + 3, 64);
       const int li = row - cur.m0, lj = col - cur.n0;
