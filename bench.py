@@ -27,8 +27,8 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "92350abb82c28f8c63c11059655c2e5994c9295e8dfbc922712984fbea7ad1d1",
-    "fetch_bytes": 2.16748e6 * 2.0 * 1024,
+    "sources_sha256": "506636beb1982d69daf34dc022f9d0f89b5e453ffb336d1a5682cec8a2a34343",
+    "fetch_bytes": 2.16822e6 * 2.0 * 1024,
     "write_bytes": 151.375 * 1.0 * 1024,
 }
 
