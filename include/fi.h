@@ -151,16 +151,19 @@ fi_status fi_plan_buffer(const fi_plan* plan, uint32_t which, const void** d_ptr
 
 /* Optional tuning.  tile_config: -1 keep, else an index into the kernel table:
  *   0..2  one trial per work item on a 256x256, 128x128 or 256x64 output tile (every fault
- *         kind, any K).  When K % 64 == 0 the first two run as persistent workgroups - the
- *         item loop of the multi-trial kernel below with one trial per item (also reachable
- *         as 7 and 8) - and fi_gemm_propagate_batch uses the same persistent kernel.
+ *         kind, any K).  The first two run as persistent workgroups - the item loop of the
+ *         multi-trial kernel below with one trial per item (also reachable as 7 and 8) -
+ *         and fi_gemm_propagate_batch uses the same persistent kernel.
  *   3..8  R trials per workgroup sharing one staged operand tile: R=4 on 128x128, R=2 on
- *         128x128, R=8 on 128x64 (the default when K % 64 == 0), and, with two workgroups of
- *         four waves per compute unit instead of one of eight, R=8 on 64x64; 7 and 8: R=1 (see above).
+ *         128x128, R=8 on 128x64 (the default on large problems), and, with two workgroups of
+ *         four waves per compute unit instead of one of eight, R=8 on 64x64 (the default
+ *         below 2^35 multiply-adds); 7 and 8: R=1 (see above).  Any K: when K is not a
+ *         multiple of 64 the plan keeps copies of A and B with zeros in front of every row
+ *         up to whole 64-wide k-tiles (bit-identical results: leading zero products leave
+ *         an accumulator at +0).
  *         The batch is split on the device into the trials whose fault leaves the operands
  *         alone and the operand-fault trials; the latter run in a second instantiation that
  *         XORs the faulted word in the fragment registers around the faulted trial's MFMAs.
- *         FI_UNSUPPORTED if K % 64 != 0.
  * trial_group: -1 keep, else how many trials (groups of R trials) of the same
  * output tile are scheduled next to each other, 1..4096.  Results do not depend on
  * either (every shape accumulates each element in the same order); `stream` is unused. */
@@ -210,8 +213,8 @@ fi_status fi_gemm_inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t
  * re-reading 4 bytes per element.  Records as fi_gemm_inject_batch.  Allocation and
  * synchronisation as fi_gemm_inject_batch (per-stream scratch).
  * Errors: INVALID_ARG (NULLs, bad policy, n_trials == 0); UNSUPPORTED when d_h_out is not
- * 2-byte aligned or the plan runs the one-trial kernel (K not a multiple of 64, or
- * fi_plan_tune(plan, 2, ...)). */
+ * 2-byte aligned or the plan runs the one-trial kernel
+ * (fi_plan_tune(plan, 2, ...)). */
 fi_status fi_gemm_inject_batch_act(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trials,
                                    uint32_t policy, fi_trial_result* d_results, void* d_h_out,
                                    void* stream);
@@ -265,7 +268,8 @@ fi_status fi_activation_round(uint32_t dtype, const float* d_c, uint64_t n, uint
  * Inf or NaN (they propagate as IEEE and are flagged).  d_c_out as in fi_gemm_inject_batch.
  * The caller owns d_a_stack and keeps it unmodified until the work has run.  All 2*M*N*K
  * flops of every trial are executed (one trial per work item; tile configurations 0..2, of
- * which 0 - the default - and 1 run as persistent workgroups when K % 64 == 0).
+ * which 0 and 1 run as persistent workgroups when K is a multiple of 64, the default chosen
+ * by problem size).
  * Errors: INVALID_ARG (NULLs, n_trials == 0, bad policy, trial_stride too small),
  * UNSUPPORTED (alignment; tiles x trials >= 2^31). */
 fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t trial_stride,

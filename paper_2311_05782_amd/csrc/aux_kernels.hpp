@@ -227,6 +227,22 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
   }
 }
 
+// dst[r][0 .. shift) = 0, dst[r][shift + k] = src[r][k]: an operand padded IN FRONT to whole
+// 64-wide k-tiles.  Leading zero products leave an accumulator that starts at +0 at +0 exactly,
+// and the real terms keep their grouping into 16-wide MFMA steps (shift is a multiple of 16),
+// so a GEMM over the padded operands equals the unpadded one bit for bit.
+__global__ void __launch_bounds__(256) pad_front16_kernel(const uint16_t* __restrict__ src, uint32_t ld,
+                                                          uint16_t* __restrict__ dst, uint32_t rows, uint32_t K,
+                                                          uint32_t shift) {
+  const uint32_t Kp = K + shift;
+  const size_t n = (size_t)rows * Kp;
+  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (size_t)gridDim.x * 256) {
+    const size_t r = e / Kp;
+    const uint32_t c = (uint32_t)(e % Kp);
+    dst[e] = c < shift ? (uint16_t)0 : src[r * ld + (c - shift)];
+  }
+}
+
 // Splits a batch: trials the multi-trial GEMM kernel can take (no fault, an accumulator flip or
 // a product-term fault; out-of-range sites count as "no fault" and get status 1 in their zeroed
 // record) go to the front of perm in list order, all others (operand faults) behind them,
@@ -238,6 +254,8 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
 // with fault-free entries up to the next multiple of 8 positions.  The operand faults' descriptors
 // follow from that position on: event = k/16 with bit 29 set, w0 = the 16-bit mask, w1 = kind;
 // their site words (the operand word before and after) are written here.  B is [N][ldb], k contiguous.
+// kshift: zeros the GEMM kernel's operand copies carry in front of every row (K not a multiple of
+// 64): every event step moves up by kshift / 16; A, B, K here are the caller's unpadded operands.
 // One workgroup.
 template <int DT>
 __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* __restrict__ f, uint32_t n,
@@ -245,7 +263,7 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
                                                                const uint16_t* __restrict__ A,
                                                                const uint16_t* __restrict__ B, uint32_t lda,
                                                                uint32_t ldb, int product_check_mode,
-                                                               uint32_t bm, uint32_t bn,
+                                                               uint32_t bm, uint32_t bn, uint32_t kshift,
                                                                uint32_t* __restrict__ perm,
                                                                uint32_t* __restrict__ counts,
                                                                uint32_t* __restrict__ desc,
@@ -263,11 +281,11 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
   // (as finely as the buckets left over allow): the R trials of a group then have their events
   // in the same k-tile or in neighbouring ones, and a work item runs one or two k-tiles of the
   // checking copy of the loop instead of up to R.
-  const uint32_t n_kt = (K + 63) / 64;
+  const uint32_t n_kt = (K + kshift + 63) / 64;          // k-tiles of the (front-padded) operands
   const uint32_t kq = max(1u, min(n_kt, 1024u / n_major));               // keys < n_major * kq <= 1024
   auto key_of = [&](const fi_fault& x) -> uint32_t {
     const uint32_t major = (x.kind == FI_SITE_A ? x.row / bm : tiles_m + x.col / bn) >> key_shift;
-    const uint32_t kt = min((x.kind == FI_SITE_A ? x.col : x.row) / 64u, n_kt - 1u);
+    const uint32_t kt = min(((x.kind == FI_SITE_A ? x.col : x.row) + kshift) / 64u, n_kt - 1u);
     return major * kq + kt * kq / n_kt;
   };
   bucket[threadIdx.x] = 0;
@@ -384,7 +402,7 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
       const uint32_t kk = isA ? x.col : x.row, m16 = x.xor_mask & 0xFFFFu;
       const uint32_t pos = atomicAdd(&bucket[key_of(x)], 1u);      // order inside a bucket is arbitrary
       uint32_t* d = desc + ((size_t)((n_fast + 7u) & ~7u) + pos) * 6;
-      d[0] = t; d[1] = x.row; d[2] = x.col; d[3] = (kk / 16) | 0x20000000u; d[4] = m16; d[5] = x.kind;
+      d[0] = t; d[1] = x.row; d[2] = x.col; d[3] = ((kk + kshift) / 16) | 0x20000000u; d[4] = m16; d[5] = x.kind;
       results[t].site_word_before = w0;
       results[t].site_word_after = w0 ^ m16;
       perm[n_fast + pos] = t;
@@ -393,13 +411,13 @@ __global__ void __launch_bounds__(1024) partition_trials_kernel(const fi_fault* 
     uint32_t* d = desc + (size_t)q * 6;
     d[0] = t; d[1] = x.row; d[2] = x.col;
     if (k == 2) {
-      d[3] = (x.kblock + 1) * kb / 16 - 1; d[4] = x.xor_mask; d[5] = 0;
+      d[3] = ((x.kblock + 1) * kb + kshift) / 16 - 1; d[4] = x.xor_mask; d[5] = 0;
     } else if (k == 4) {
       float re, re_err;
       bool fired;
       product_fault_terms<DT>((uint16_t)w0, (uint16_t)w1, x.xor_mask, product_check_mode, re, re_err, fired);
       if (fired) results[t].product_flag = 1;
-      d[3] = (x.kblock / 16) | 0x40000000u; d[4] = __float_as_uint(re); d[5] = __float_as_uint(re_err);
+      d[3] = ((x.kblock + kshift) / 16) | 0x40000000u; d[4] = __float_as_uint(re); d[5] = __float_as_uint(re_err);
     } else {
       d[3] = 0xFFFFFFFFu; d[4] = 0; d[5] = 0;
     }

@@ -67,6 +67,11 @@ struct fi_plan {
   const uint16_t* B = nullptr;       // effective [N][ldb] K-contiguous matrix
   uint32_t ldb = 0;
   uint16_t* Bt = nullptr;            // plan-owned transposed copy (b_layout 1) or NULL
+  // K not a multiple of 64: copies of A and B ([M][K + kshift], [N][K + kshift]) with kshift zeros
+  // in front of every row, for the kernels that want whole 64-wide k-tiles; else NULL and 0
+  uint16_t* Apad = nullptr;
+  uint16_t* Bpad = nullptr;
+  uint32_t kshift = 0;
   float* c_star = nullptr;           // [M][N]
   float* s_abs = nullptr;            // [M][N]
   float* kra = nullptr;              // [pad(M)]
@@ -117,13 +122,11 @@ hipError_t launch_prop(int dtype, int mcfg, const GemmArgs& a, int n_blocks, hip
   return hipErrorInvalidValue;
 }
 
-// The multi-trial kernel needs whole 64-wide k-tiles.  Eight trials per tile carry the least
-// operand traffic per flop.  On the largest problems one eight-wave workgroup per CU on a
+// Eight trials per tile carry the least operand traffic per flop.  On the largest problems one eight-wave workgroup per CU on a
 // 128 x 64 tile measured fastest (less traffic into LDS per flop); below that two four-wave
 // workgroups on 64 x 64 tiles win, because the barriers and the per-item epilogue of one run
 // under the MFMAs of the other (+2 .. 16 % on 1024^3, 512 x 3072 x 768 and 3136 x 64 x 576).
 int pick_multi(const fi_plan_desc& d) {
-  if (d.K % 64 != 0) return -1;
   const double work = (double)d.M * (double)d.N * (double)d.K;
   return work >= 34359738368.0 /* 2^35 */ ? 2 : 3;
 }
@@ -215,6 +218,8 @@ fi_status check_plan(const fi_plan* p) {
 
 void free_plan_buffers(fi_plan* p) {
   if (p->Bt) (void)hipFree(p->Bt);
+  if (p->Apad) (void)hipFree(p->Apad);
+  if (p->Bpad) (void)hipFree(p->Bpad);
   if (p->c_star) (void)hipFree(p->c_star);
   if (p->s_abs) (void)hipFree(p->s_abs);
   if (p->kra) (void)hipFree(p->kra);
@@ -277,6 +282,17 @@ fi_status build_plan(fi_plan* p, const void* d_A, const void* d_B, hipStream_t s
     FI_HIP(hipGetLastError());
     p->B = p->Bt;
     p->ldb = d.K;
+  }
+  if (d.K % 64 != 0) {
+    p->kshift = 64 - d.K % 64;
+    const uint32_t kp = d.K + p->kshift;
+    FI_HIP(hipMalloc(&p->Apad, (size_t)d.M * kp * sizeof(uint16_t)));
+    FI_HIP(hipMalloc(&p->Bpad, (size_t)d.N * kp * sizeof(uint16_t)));
+    hipLaunchKernelGGL(fi::pad_front16_kernel, dim3(1024), dim3(256), 0, s, p->A, (uint32_t)d.lda, p->Apad, d.M, d.K,
+                       p->kshift);
+    hipLaunchKernelGGL(fi::pad_front16_kernel, dim3(1024), dim3(256), 0, s, p->B, p->ldb, p->Bpad, d.N, d.K,
+                       p->kshift);
+    FI_HIP(hipGetLastError());
   }
   // statistics
   hipLaunchKernelGGL(fi::fill_u32_kernel, dim3(64), dim3(256), 0, s,
@@ -386,6 +402,12 @@ fi_status inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trial
   if (plan->mcfg >= 0) {
     m.tiles_m = (a.M + mc.bm - 1) / mc.bm;
     m.tiles_n = (a.N + mc.bn - 1) / mc.bn;
+    if (plan->kshift) {
+      // whole k-tiles: the front-padded copies (bit-identical results, see pad_front16_kernel)
+      m.A = plan->Apad; m.B = plan->Bpad;
+      m.K = a.K + (int)plan->kshift;
+      m.lda = m.ldb = (uint32_t)m.K;
+    }
     // Persistent workgroups, as many per CU as the configuration's register budget admits, each
     // walking the work list with the grid as stride; a multiple of 8 keeps a workgroup's items
     // on one XCD.
@@ -419,11 +441,11 @@ fi_status inject_batch(fi_plan* plan, const fi_fault* d_faults, uint32_t n_trial
   if (plan->d.dtype == FI_BF16)
     hipLaunchKernelGGL(fi::partition_trials_kernel<FI_BF16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
                        plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
-                       (uint32_t)mc.bm, (uint32_t)mc.bn, ts.perm, ts.counts, ts.desc, d_results);
+                       (uint32_t)mc.bm, (uint32_t)mc.bn, plan->kshift, ts.perm, ts.counts, ts.desc, d_results);
   else
     hipLaunchKernelGGL(fi::partition_trials_kernel<FI_FP16>, dim3(1), dim3(1024), 0, s, d_faults, n_trials,
                        plan->d.M, plan->d.N, plan->d.K, plan->d.k_block, a.A, a.B, a.lda, a.ldb, plan->product_check,
-                       (uint32_t)mc.bm, (uint32_t)mc.bn, ts.perm, ts.counts, ts.desc, d_results);
+                       (uint32_t)mc.bm, (uint32_t)mc.bn, plan->kshift, ts.perm, ts.counts, ts.desc, d_results);
   FI_HIP(hipGetLastError());
   m.perm = ts.perm;
   m.part_counts = ts.counts;
@@ -509,9 +531,8 @@ fi_status fi_plan_create(const fi_plan_desc* desc, const void* d_A, const void* 
   // Next-layer launches: on problems below 2^35 multiply-adds the 128 x 128 shape with two
   // workgroups per CU measured faster (one's epilogue runs under the other's MFMAs: 0.75 against
   // 0.81 ms on 512 x 768 x 3072, 256 trials), above it the 256 x 256 shape (less LDS traffic per flop).
-  p->prop_cfg = d.K % 64 != 0 ? -1
-                              : (double)d.M * (double)d.N * (double)d.K >= 34359738368.0 ? fi::kMultiOneTrial[0]
-                                                                                       : fi::kMultiOneTrial[1];
+  p->prop_cfg = (double)d.M * (double)d.N * (double)d.K >= 34359738368.0 ? fi::kMultiOneTrial[0]
+                                                                         : fi::kMultiOneTrial[1];
   p->group = 32;
   (void)hipGetDevice(&p->device);
   if (hipDeviceGetAttribute(&p->n_cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess ||
@@ -570,8 +591,6 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
   if (st != FI_OK) return st;
   if (tile_config >= kNumCfg + kNumMulti)
     return fail(FI_INVALID_ARG, "tile_config must be < %d", kNumCfg + kNumMulti);
-  if (tile_config >= kNumCfg && plan->d.K % 64 != 0)
-    return fail(FI_UNSUPPORTED, "multi-trial tiles need K to be a multiple of 64");
   if (trial_group == 0 || trial_group > 4096) return fail(FI_INVALID_ARG, "trial_group must be in 1..4096");
   if (trial_group > 0) plan->group = trial_group;
   // C* does not depend on the tile shape: every shape feeds each output element the same
@@ -581,9 +600,9 @@ fi_status fi_plan_tune(fi_plan* plan, int32_t tile_config, int32_t trial_group, 
     if (kMulti[plan->mcfg].r == 1) plan->prop_cfg = plan->mcfg;
   } else if (tile_config >= 0) {
     plan->cfg = tile_config; plan->cfg_affected = tile_config;
-    // One trial per work item.  With whole 64-wide k-tiles the 256x256 and 128x128 shapes run as
-    // persistent workgroups (the multi-trial kernel's item loop with one trial per item).
-    const bool persistent = plan->d.K % 64 == 0 && tile_config < 2;
+    // One trial per work item.  The 256x256 and 128x128 shapes run as persistent workgroups (the
+    // multi-trial kernel's item loop with one trial per item).
+    const bool persistent = tile_config < 2;
     plan->mcfg = persistent ? fi::kMultiOneTrial[tile_config] : -1;
     plan->prop_cfg = persistent ? fi::kMultiOneTrial[tile_config] : -1;
   }
@@ -675,8 +694,8 @@ fi_status fi_gemm_inject_batch_act(fi_plan* plan, const fi_fault* d_faults, uint
   if (!d_h_out) return fail(FI_INVALID_ARG, "d_h_out is NULL");
   if (reinterpret_cast<uintptr_t>(d_h_out) & 1u) return fail(FI_UNSUPPORTED, "d_h_out must be 2-byte aligned");
   if (plan->mcfg < 0)
-    return fail(FI_UNSUPPORTED, "the fused hand-over needs K to be a multiple of 64 (and a tile_config that is "
-                "not 2); use fi_gemm_inject_batch with d_c_out and fi_activation_round");
+    return fail(FI_UNSUPPORTED, "the fused hand-over is not available with tile_config 2; use fi_gemm_inject_batch "
+                "with d_c_out and fi_activation_round");
   BatchScratch* bs = nullptr;
   st = batch_scratch(plan, as_stream(stream), n_trials, &bs);
   if (st != FI_OK) return st;
@@ -768,7 +787,8 @@ fi_status fi_gemm_propagate_batch(fi_plan* plan, const void* d_a_stack, uint64_t
     return fail(FI_INVALID_ARG, "trial_stride %llu is smaller than one operand ((M-1)*lda + K elements)",
                 (unsigned long long)trial_stride);
   GemmArgs a = base_args(plan);
-  const bool persistent = plan->prop_cfg >= 0 && a.c_star_bytes != 0;   // C* is addressed with 32 bits
+  // C* is addressed with 32 bits; the trials' operands are the caller's, so K must hold whole k-tiles
+  const bool persistent = plan->prop_cfg >= 0 && a.c_star_bytes != 0 && plan->kshift == 0;
   if (persistent) {
     const MultiCfg mc = kMulti[plan->prop_cfg];
     a.tiles_m = (a.M + mc.bm - 1) / mc.bm;

@@ -160,7 +160,7 @@ def test_two_layers_end_to_end_against_the_oracle_chain(fmt):
 
 @pytest.mark.parametrize("fmt", [orc.FP16, orc.BF16])
 @pytest.mark.parametrize("cfg", [None, 0, 1, 3, 4, 5, 6])
-@pytest.mark.parametrize("shape", [(300, 200, 192, 32), (257, 65, 128, 64), (64, 64, 64, 16)])
+@pytest.mark.parametrize("shape", [(300, 200, 192, 32), (257, 65, 128, 64), (64, 64, 64, 16), (96, 40, 96, 48)])
 def test_fused_hand_over_equals_campaign_then_activation_round(fmt, cfg, shape):
     # fi_gemm_inject_batch_act against fi_gemm_inject_batch + fi_activation_round: same words (NaN
     # payloads included: both round the same corrected value with the same integer code), same
@@ -205,8 +205,8 @@ def test_fused_hand_over_equals_campaign_then_activation_round(fmt, cfg, shape):
 
 
 def test_fused_hand_over_is_refused_where_the_one_trial_kernel_runs():
-    Aw, Bw = wl.gaussian(64, 64, 96, orc.BF16, seed=5)           # K = 96: a ragged k-tile
-    plan = gu.make_plan(Aw, Bw, 32, orc.BF16)
+    Aw, Bw = wl.gaussian(64, 64, 96, orc.BF16, seed=5)
+    plan = gu.make_plan(Aw, Bw, 32, orc.BF16, cfg=2)             # 256 x 64 tiles: the one-trial kernel
     import torch
     d_h = torch.empty((2, 64, 64), dtype=torch.int16, device="cuda")
     with pytest.raises(fi.FiError):
