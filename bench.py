@@ -27,7 +27,7 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "506636beb1982d69daf34dc022f9d0f89b5e453ffb336d1a5682cec8a2a34343",
+    "sources_sha256": "c570c420dc7d687fe9fb2e325f2ccb81ebd5af6ef189667bbf713a7dc77c95f4",
     "fetch_bytes": 2.16822e6 * 2.0 * 1024,
     "write_bytes": 151.375 * 1.0 * 1024,
 }
