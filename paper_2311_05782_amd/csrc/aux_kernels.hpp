@@ -145,7 +145,7 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
         for (int u = 0; u < 4; ++u) {
           cv[u] = base + u * 256 + (int)threadIdx.x;
           if (cv[u] < nv) {
-            v[u] = *reinterpret_cast<const f32x4_t*>(crow + 4 * cv[u]);
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(crow + 4 * cv[u]));   // streamed once
             w[u] = *reinterpret_cast<const f32x4_t*>(cb + 4 * cv[u]);
           }
         }
@@ -205,8 +205,9 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
   const size_t step = (size_t)gridDim.x * 256;
   const size_t first = (size_t)blockIdx.x * 256 + threadIdx.x;
   for (size_t i = first; i < n8; i += step) {
-    const f32x4_t v0 = reinterpret_cast<const f32x4_t*>(c)[2 * i];
-    const f32x4_t v1 = reinterpret_cast<const f32x4_t*>(c)[2 * i + 1];
+    // streamed once: loads and the store bypass cache retention
+    const f32x4_t v0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(c) + 2 * i);
+    const f32x4_t v1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(c) + 2 * i + 1);
     uint32_t w[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -219,7 +220,7 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
     o[1] = w[2] | (w[3] << 16);
     o[2] = w[4] | (w[5] << 16);
     o[3] = w[6] | (w[7] << 16);
-    reinterpret_cast<u32x4_t*>(h)[i] = o;
+    __builtin_nontemporal_store(o, reinterpret_cast<u32x4_t*>(h) + i);
   }
   for (size_t i = n8 * 8 + first; i < n; i += step) {
     const float x = c[i];

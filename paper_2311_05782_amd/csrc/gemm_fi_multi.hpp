@@ -41,6 +41,9 @@
 namespace fi {
 
 constexpr int kMultiDescWords = 6;   // trial, row, col, event, w0, w1
+// cache policy of the output stores: non-temporal (written once, read by another kernel later),
+// so that they do not displace the operand panels in L2
+constexpr int kStreamStore = 2;
 
 // VAR: which part of the work this instantiation takes.
 enum { VAR_PLAIN = 0, VAR_OPERAND = 1, VAR_PROPAGATE = 2 };
@@ -571,7 +574,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                   for (int v = 0; v < 16; ++v)
                     __builtin_amdgcn_raw_buffer_store_b32(
                         __float_as_uint(t[v]), rs, lane_off * 4,
-                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 4u), 0);
+                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 4u), kStreamStore);
                 }
                 if (p.h_out) {
                   const __amdgpu_buffer_rsrc_t rs =
@@ -581,7 +584,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                     const float cc = t[v];
                     __builtin_amdgcn_raw_buffer_store_b16(
                         (unsigned short)round16<DT>((cc > 0.0f || cc != cc) ? cc : 0.0f), rs, lane_off * 2,
-                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 2u), 0);
+                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 2u), kStreamStore);
                   }
                 }
               } else
