@@ -112,6 +112,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     size_t a_base;                                       // PROP: element offset of the trial's A operand
   };
   Item cur, nxt;                                         // the current item and the one after it
+  int stage = 0;                                         // LDS stage of the current k-tile
   auto locate = [&](uint32_t w, Item& it) {
     int tile;
     work_of_index(w, n_work, p.tiles_m * p.tiles_n, n_groups, p.group, tile, it.grp);
@@ -539,6 +540,16 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
     }
     uint32_t n_flag[R];
     static_for<R>([&](auto rr) { n_flag[rr] = 0; });
+    // output stores of 16 bytes per lane need 16-byte aligned rows (and two KB of LDS per wave)
+    static_assert(A_G >= 2, "a wave's staging slice holds a 2 KB transposition buffer");
+    const bool wide_c = p.c_out && (p.N & 3) == 0 && (reinterpret_cast<uintptr_t>(p.c_out) & 15u) == 0;
+    const bool wide_h = p.h_out && (p.N & 7) == 0 && (reinterpret_cast<uintptr_t>(p.h_out) & 15u) == 0;
+    uint8_t* const scr = smem + (stage ^ 1) * STAGE + wave * (A_G * 1024);
+    // The lane's parts of the wide stores' addresses are formed here, per item: left to the
+    // compiler they are hoisted to the top of the kernel and cost the k-loop registers it does
+    // not have (the empty asm statement pins them below this point).
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
     auto detect = [&](auto with_out) __attribute__((always_inline)) {
       constexpr bool OUT = decltype(with_out)::value;
       static_for<TM * TN>([&](auto tt) {
@@ -567,24 +578,66 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                                           (uint32_t)(n0 + wn * WTN + 32 * j);           // elements
                 const int lane_off = 4 * lhi * p.N + l32;
                 const uint32_t mn = (uint32_t)p.M * (uint32_t)p.N;
+                // Where rows are 16-byte aligned the 32 x 32 tile goes through LDS first - the
+                // accumulator layout gives a lane one column of 16 rows, a store wants it a piece
+                // of one row - and leaves as 16 bytes per lane: 2 (16-bit) or 4 (FP32) store
+                // instructions per tile instead of 16.  The scratch is this wave's own staging
+                // slice of the LDS stage the item has just finished with (nobody reads it any
+                // more, and only this wave will write it again: the next item's second k-tile).
                 if (p.c_out) {
                   const __amdgpu_buffer_rsrc_t rs =
                       __builtin_amdgcn_make_buffer_rsrc(p.c_out + out0, 0, (int)(mn * 4u), 0x00020000);
+                  if (wide_c) {
+                    const int voff = ((ln >> 3) * p.N + (ln & 7) * 4) * 4;
 #pragma unroll
-                  for (int v = 0; v < 16; ++v)
-                    __builtin_amdgcn_raw_buffer_store_b32(
-                        __float_as_uint(t[v]), rs, lane_off * 4,
-                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 4u), kStreamStore);
+                    for (int half = 0; half < 2; ++half) {
+                      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+                      for (int v = 8 * half; v < 8 * half + 8; ++v)      // rows 16 * half .. + 15
+                        *reinterpret_cast<float*>(scr + (8 * ((v >> 2) & 1) + 4 * (ln >> 5) + (v & 3)) * 128 + (ln & 31) * 4) = t[v];
+                      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+                      for (int ps = 0; ps < 2; ++ps) {
+                        const u32x4 q = *reinterpret_cast<const u32x4*>(scr + (8 * ps + (ln >> 3)) * 128 + (ln & 7) * 16);
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            q, rs, voff, (int)((tile_off + (uint32_t)(16 * half + 8 * ps) * (uint32_t)p.N) * 4u), kStreamStore);
+                      }
+                    }
+                  } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                      __builtin_amdgcn_raw_buffer_store_b32(
+                          __float_as_uint(t[v]), rs, lane_off * 4,
+                          (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 4u), kStreamStore);
+                  }
                 }
                 if (p.h_out) {
                   const __amdgpu_buffer_rsrc_t rs =
                       __builtin_amdgcn_make_buffer_rsrc(p.h_out + out0, 0, (int)(mn * 2u), 0x00020000);
+                  if (wide_h) {
+                    const int voff = ((ln >> 2) * p.N + (ln & 3) * 8) * 2;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
-                  for (int v = 0; v < 16; ++v) {
-                    const float cc = t[v];
-                    __builtin_amdgcn_raw_buffer_store_b16(
-                        (unsigned short)round16<DT>((cc > 0.0f || cc != cc) ? cc : 0.0f), rs, lane_off * 2,
-                        (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 2u), kStreamStore);
+                    for (int v = 0; v < 16; ++v) {
+                      const float cc = t[v];
+                      *reinterpret_cast<uint16_t*>(scr + (8 * (v >> 2) + 4 * (ln >> 5) + (v & 3)) * 64 + (ln & 31) * 2) =
+                          (uint16_t)round16<DT>((cc > 0.0f || cc != cc) ? cc : 0.0f);
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+                    for (int ps = 0; ps < 2; ++ps) {
+                      const u32x4 q = *reinterpret_cast<const u32x4*>(scr + (16 * ps + (ln >> 2)) * 64 + (ln & 3) * 16);
+                      __builtin_amdgcn_raw_buffer_store_b128(
+                          q, rs, voff, (int)((tile_off + (uint32_t)(16 * ps) * (uint32_t)p.N) * 2u), kStreamStore);
+                    }
+                  } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                      const float cc = t[v];
+                      __builtin_amdgcn_raw_buffer_store_b16(
+                          (unsigned short)round16<DT>((cc > 0.0f || cc != cc) ? cc : 0.0f), rs, lane_off * 2,
+                          (int)((tile_off + (uint32_t)(8 * (v >> 2) + (v & 3)) * (uint32_t)p.N) * 2u), kStreamStore);
+                    }
                   }
                 }
               } else
@@ -886,7 +939,6 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
   __syncthreads();
   Frags f0, f1;
   read_frags(f0, smem, 0);
-  int stage = 0;
   const int nkt = p.K / BK;
 
   // ---- items.  Within one: double-buffered LDS, one barrier per k-tile.  The barrier sits
