@@ -723,13 +723,10 @@ void orc_classify(const orc_record* recs, int n, uint8_t* cls, uint64_t counts[3
   }
 }
 
-/* --------------------------------------------------------- O7: sampler
- * Sec. IV-A selects the injection target uniformly at random and flips
- * "a random bit(s)" of it.  Owning the GEMM, the site space is closed-form:
- * (i, j, s) for an accumulator fault, (i, k) for an A-operand fault, (k, j)
- * for a B-operand fault, times the position of an nbits-wide burst.  Draws
- * come from SplitMix64 (Steele, Lea, Flood 2014) keyed by the trial index so
- * any trial can be regenerated alone. */
+/* ------------------------------------------- deviation histogram (Sec. V-B)
+ * 256 log2 bins - the exponent field of the binary32 value - of a per-trial
+ * quantity: the change of the destination register (Fig. 7's statistic) or the
+ * largest output deviation before / after correction (Fig. 9). */
 void orc_deviation_histogram(const orc_record* recs, const orc_fault* faults, int n, int which,
                              uint64_t hist[256]) {
   for (int b = 0; b < 256; ++b) hist[b] = 0;
@@ -747,6 +744,13 @@ void orc_deviation_histogram(const orc_record* recs, const orc_fault* faults, in
   }
 }
 
+/* --------------------------------------------------------- O7: sampler
+ * Sec. IV-A picks the injection target uniformly at random and flips one or
+ * several random bits of it.  Owning the GEMM, the site space is closed-form:
+ * (i, j, s) for an accumulator fault, (i, k) for an A-operand fault, (k, j)
+ * for a B-operand fault, times the position of an nbits-wide burst.  Draws
+ * come from SplitMix64 (Steele, Lea, Flood 2014) keyed by the trial index so
+ * any trial can be regenerated alone. */
 uint64_t orc_splitmix64_next(uint64_t* state) {
   *state += 0x9E3779B97F4A7C15ull;
   uint64_t z = *state;
