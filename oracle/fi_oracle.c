@@ -84,10 +84,9 @@ static void load_b_col(const orc_problem* p, const uint16_t* B, int j, float* ou
 }
 
 /* ------------------------------------ binary32 -> FP16 / BF16, nearest-even
- * The paper's fault lives in "the result of a multiplication operation"
- * (Sec. IV-C) and its detectors read "the register that stores the result of
- * the BF16 multiplication" (Sec. VI-A): the product is held in the operand
- * format.  This is the IEEE round-to-nearest-even conversion written out case
+ * The paper's fault corrupts what one multiplication produces (Sec. IV-C)
+ * and its detectors read the register holding that BF16 product (Sec. VI-A):
+ * the product is held in the operand format.  This is the IEEE round-to-nearest-even conversion written out case
  * by case: NaN, overflow to infinity at the midpoint above the largest finite
  * value, the subnormal range as a fixed-point grid, normal numbers as
  * exponent + rounded significand (a carry out of the significand bumps the

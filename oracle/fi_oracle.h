@@ -89,7 +89,7 @@ typedef struct {
   uint32_t reserved;
 } orc_record;
 
-/* Sec. V-B "numeric deviation analysis" (Fig. 7) and Fig. 9: log2-binned histogram of a
+/* Sec. V-B's analysis of numeric deviations (Fig. 7) and Fig. 9: log2-binned histogram of a
  * per-trial deviation, from which the empirical CDF follows by a running sum.
  *   which 0: |re'_sum - re_sum|, the change of the destination register, computed in binary32
  *            from the two site words (accumulator and product-term faults only);
