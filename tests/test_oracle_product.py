@@ -108,7 +108,7 @@ def test_write_back_examples_worked_by_hand(row):
         re_sum = np.float32(re_sum + np.float32(1.0))
     assert _f32([rec["site_word_before"]])[0] == re_sum
     assert _f32([rec["site_word_after"]])[0] == np.float32(final)
-    # Sec. V-B: "difference of 0" is site word unchanged
+    # Sec. V-B: a trial whose destination register ends up unchanged has a site word that does not change
     assert (rec["site_word_before"] == rec["site_word_after"]) == (np.float32(final) == re_sum)
 
 
