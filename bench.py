@@ -27,8 +27,8 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "c570c420dc7d687fe9fb2e325f2ccb81ebd5af6ef189667bbf713a7dc77c95f4",
-    "fetch_bytes": 2.16822e6 * 2.0 * 1024,
+    "sources_sha256": "4036cbf5e693a126277b93b866a9b00ab3cbade736b19f779b9e889c4b2785ff",
+    "fetch_bytes": 2.16778e6 * 2.0 * 1024,
     "write_bytes": 151.375 * 1.0 * 1024,
 }
 
