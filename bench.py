@@ -375,6 +375,22 @@ def main():
                 pl.fi_gemm_inject_batch_affected(ff, ww.n_trials, ww.policies[0], rr)
             torch.cuda.synchronize()
             others[name]["affected_only_trials_per_s"] = round(5 * ww.n_trials / (time.perf_counter() - t1), 1)
+            if name == "bert_linear":
+                # The same batch size with every trial of ONE fault kind (Sec. IV-A's sites): what the
+                # operand-fault path costs against accumulator flips.
+                by_kind = {}
+                for label, km in (("acc", fi.KIND_ALL_ACC), ("a_operand", fi.KIND_ALL_A), ("b_operand", fi.KIND_ALL_B),
+                                  ("product", fi.KIND_ALL_PRODUCT)):
+                    fk = fi.to_device(fi.fi_sample_faults(ww.fault_seed, 0, ww.n_trials, pl.desc, km, 1))
+                    for _ in range(3):
+                        pl.fi_gemm_inject_batch(fk, ww.n_trials, ww.policies[0], rr)
+                    torch.cuda.synchronize()
+                    t1 = time.perf_counter()
+                    for _ in range(8):
+                        pl.fi_gemm_inject_batch(fk, ww.n_trials, ww.policies[0], rr)
+                    torch.cuda.synchronize()
+                    by_kind[label] = round(ww.flops_per_trial * ww.n_trials * 8 / (time.perf_counter() - t1) / 1e12, 1)
+                others[name]["tflops_by_fault_kind"] = by_kind
             pl.destroy()
             if name == "detector_stress":
                 # Coverage of the three output-side detectors on the same fault list (Sec. VI-A's
