@@ -196,8 +196,8 @@ __global__ void __launch_bounds__(256) detect_correct_kernel(
 
 // Hand-over between two layers: h = RNE_fmt(relu(c)).  relu keeps a NaN and maps negatives
 // and -0 to +0; the rounding is the integer one of round16 (no dependence on the wave's float
-// modes).  HBM bound: 4 bytes read, 2 written per element; eight elements per lane and step
-// (two 16-byte loads in flight, one 16-byte store).
+// modes), in its branch-free form relu_round16.  HBM bound: 4 bytes read, 2 written per element;
+// eight elements per lane and step (two 16-byte loads in flight, one 16-byte store).
 template <int DT>
 __global__ void __launch_bounds__(256) activation_round_kernel(const float* __restrict__ c, size_t n,
                                                               uint16_t* __restrict__ h) {
@@ -212,8 +212,8 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float x = v0[e], y = v1[e];
-      w[e] = round16<DT>((x > 0.0f || x != x) ? x : 0.0f);
-      w[4 + e] = round16<DT>((y > 0.0f || y != y) ? y : 0.0f);
+      w[e] = relu_round16<DT>(x);
+      w[4 + e] = relu_round16<DT>(y);
     }
     u32x4_t o;
     o[0] = w[0] | (w[1] << 16);
@@ -224,7 +224,7 @@ __global__ void __launch_bounds__(256) activation_round_kernel(const float* __re
   }
   for (size_t i = n8 * 8 + first; i < n; i += step) {
     const float x = c[i];
-    h[i] = (uint16_t)round16<DT>((x > 0.0f || x != x) ? x : 0.0f);
+    h[i] = (uint16_t)relu_round16<DT>(x);
   }
 }
 

@@ -142,6 +142,34 @@ __device__ __forceinline__ uint32_t round16(float x) {
   }
 }
 
+// round16(relu(x)) without a branch or a select, for the output paths that convert every element:
+// relu keeps a NaN (quieted, sign kept) and maps negatives and -0 to +0.  Same integer arithmetic
+// as round16: adding (half - 1) + (the bit that becomes the last place) before the shift rounds to
+// nearest even, a carry moves into the exponent; FP16 merges the normal grid (clamped to Inf) with
+// the subnormal grid (multiples of 2^-24; inputs below 2^-25 shift out entirely).  Conditions are
+// sign masks merged bitwise: written as selects, the compiler moves each arm into a branch of its
+// own (exec-mask juggling per element).
+template <int DT>
+__device__ __forceinline__ uint32_t relu_round16(float x) {
+  const uint32_t b = __float_as_uint(x);
+  const uint32_t nan_mask = (uint32_t)((int32_t)(0x7F800000u - (b & 0x7FFFFFFFu)) >> 31);   // magnitude above Inf
+  const uint32_t r = b & ~(uint32_t)((int32_t)b >> 31);                                     // negative words -> +0
+  uint32_t h, nan_word = (b >> 16) & 0x8000u;
+  if constexpr (DT == FI_BF16) {
+    h = (r + 0x7FFFu + ((r >> 16) & 1u)) >> 16;
+    nan_word |= 0x7FC0u;
+  } else {
+    const uint32_t hn = min((r - 0x38000000u + 0xFFFu + ((r >> 13) & 1u)) >> 13, 0x7C00u);
+    const uint32_t sh = min(126u - min(r >> 23, 126u), 25u);
+    const uint32_t m = (r & 0x7FFFFFu) | 0x800000u;
+    const uint32_t hs = (m + ((1u << (sh - 1u)) - 1u) + ((m >> sh) & 1u)) >> sh;
+    const uint32_t sub_mask = (uint32_t)((int32_t)(r - 0x38800000u) >> 31);                 // below 2^-14 (r < 2^31)
+    h = (hs & sub_mask) | (hn & ~sub_mask);
+    nan_word |= 0x7E00u;
+  }
+  return (nan_word & nan_mask) | (h & ~nan_mask);
+}
+
 // Exponent-only check of an erroneous product word (Sec. VI-A).  Bound check (BF16): exponent
 // 1eeexxxx with a 1 among eee means |value| >= 2^17; the three bits are cleared.  Range check:
 // the product's exponent field cannot exceed be_a + be_b - bias + 1 (from m1*m2 < 4); "max"

@@ -621,7 +621,7 @@ __global__ void __launch_bounds__(WM* WN * 64, 2) gemm_fi_multi_kernel(const Gem
                     for (int v = 0; v < 16; ++v) {
                       const float cc = t[v];
                       *reinterpret_cast<uint16_t*>(scr + (8 * (v >> 2) + 4 * (ln >> 5) + (v & 3)) * 64 + (ln & 31) * 2) =
-                          (uint16_t)round16<DT>((cc > 0.0f || cc != cc) ? cc : 0.0f);
+                          (uint16_t)relu_round16<DT>(cc);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
