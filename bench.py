@@ -27,8 +27,8 @@ MFMA_PEAK_TFLOPS = 2516.6     # 256 CUs x 4096 flop/clk/CU x 2.4 GHz, dense FP16
 # commands.  They describe the kernel sources whose digest is recorded with them and are not
 # reported for any other.
 TRAFFIC = {
-    "sources_sha256": "4036cbf5e693a126277b93b866a9b00ab3cbade736b19f779b9e889c4b2785ff",
-    "fetch_bytes": 2.16778e6 * 2.0 * 1024,
+    "sources_sha256": "73bf5516d50982b097438602074423d6b613f3abc0ac6b78b8916481b0b3c584",
+    "fetch_bytes": 2.16782e6 * 2.0 * 1024,
     "write_bytes": 151.375 * 1.0 * 1024,
 }
 

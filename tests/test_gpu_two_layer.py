@@ -29,7 +29,16 @@ def test_activation_round_bit_equal_including_specials_and_a_ragged_tail(fmt):
     assert c.size % 4 != 0
     # every bit pattern of the upper half too: all exponents, both signs
     hi = (np.arange(65536, dtype=np.uint32) << 16 | 0x8000).view(np.float32)
-    for x in (c, hi, c[:3]):
+    # the rounding boundaries of both formats on every exponent and leading mantissa: just below a
+    # tie, the tie (odd and even neighbours), just above - BF16 drops 16 bits, FP16 drops 13 and
+    # moves to a fixed grid below 2^-14
+    up16 = np.arange(65536, dtype=np.uint32) << 16
+    up19 = np.arange(1 << 19, dtype=np.uint32) << 13
+    edges = np.concatenate([up16 | lo for lo in (0x7FFF, 0x8001, 0x0001, 0xFFFF)] +
+                           [up19 | lo for lo in (0x0FFF, 0x1000, 0x1001, 0x1FFF)]).view(np.float32)
+    # FP16's subnormal grid: every binary32 value from below 2^-25 up to 2^-14, every 97th word
+    sub = np.arange(0x32000000, 0x38900000, 97, dtype=np.uint32).view(np.float32)
+    for x in (c, hi, c[:3], edges, sub):
         got, want = _activation_gpu(x, fmt), orc.activation_round(x, fmt)
         nan = np.isnan(x)
         assert np.array_equal(got[~nan], want[~nan])
