@@ -169,7 +169,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="square4096")
     ap.add_argument("--trials", type=int, default=0, help="trials per batch (default: the workload's)")
     ap.add_argument("--tile", type=int, default=-1)
