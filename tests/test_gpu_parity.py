@@ -27,8 +27,13 @@ def _mixed_faults(Aw, Bw, fmt, kb, n, seed):
     """Accumulator, A, B and fault-free trials for the exact regime, with sites forced into
     tile corners and ragged tails.  Operands are even integers, so accumulators are 0 or at
     least 4 in magnitude; accumulator bits 12..31 and operand masks that turn a word into
-    another small integer, 64 or Inf keep every partial sum exactly representable (or send
-    it so far up or down that every summation order rounds it the same way)."""
+    another small integer, 64 or Inf keep every partial sum exactly representable, or send
+    it so far up that the later terms vanish under every summation order.  Bit 30 sends a
+    non-zero accumulator DOWN to about 2^-126: such a residue under later products is outside
+    the exact regime (the oracle's sequential round-to-nearest adds absorb it; the matrix
+    core aligns the incoming accumulator to the step's largest product and rounds it down:
+    -2^-126 plus products that sum to 4 gave 4 - 2^-20), so those flips go to the last
+    k-block, where nothing is added afterwards."""
     rng = np.random.default_rng(seed)
     (M, K), N = Aw.shape, Bw.shape[0]
     S = K // kb
@@ -41,7 +46,8 @@ def _mixed_faults(Aw, Bw, fmt, kb, n, seed):
     for t in range(n):
         kind = [orc.SITE_ACC, orc.SITE_ACC, orc.SITE_A, orc.SITE_B, orc.SITE_NONE][t % 5]
         if kind == orc.SITE_ACC:
-            r = (kind, rng.integers(M), rng.integers(N), rng.integers(S), 1 << int(rng.integers(12, 32)))
+            i, j, s, bit = rng.integers(M), rng.integers(N), rng.integers(S), int(rng.integers(12, 32))
+            r = (kind, i, j, S - 1 if bit == 30 else s, 1 << bit)
         elif kind == orc.SITE_A:
             i, k = rng.integers(M), rng.integers(K)
             r = (kind, i, k, 0, op_mask(Aw[i, k]))
@@ -53,7 +59,8 @@ def _mixed_faults(Aw, Bw, fmt, kb, n, seed):
         rows.append(r)
     # corners and last elements
     rows += [(orc.SITE_ACC, M - 1, N - 1, S - 1, 1 << 31), (orc.SITE_ACC, 0, 0, 0, 1 << 23),
-             (orc.SITE_ACC, M - 1, 0, S - 1, 0x00C00000), (orc.SITE_ACC, 0, N - 1, 0, 1 << 30),
+             (orc.SITE_ACC, M - 1, 0, S - 1, 0x00C00000), (orc.SITE_ACC, 0, N - 1, 0, 1 << 31),
+             (orc.SITE_ACC, 0, N - 1, S - 1, 1 << 30),
              (orc.SITE_A, M - 1, K - 1, 0, 0x8000), (orc.SITE_B, K - 1, N - 1, 0, 0x8000),
              (orc.SITE_A, 0, 0, 0, 0x18000 | op_mask(Aw[0, 0])), (orc.SITE_B, 0, 0, 0, op_mask(Bw[0, 0]))]
     return orc.make_faults(rows)
@@ -89,6 +96,43 @@ def test_exact_regime_everything_bit_equal(fmt, cfg, shape):
             assert np.float32(g["max_dev_post"]) == np.float32(o["max_dev_post"]), (t, faults[t])
             assert int(g["status"]) == 0
     plan.destroy()
+
+
+def test_exact_regime_random_shapes_formats_blocks_and_tile_shapes():
+    # Sixty seeded draws of (format, M, N, K, k-block, tile configuration, trial group, batch size,
+    # policy, outputs or not): shapes of one row or column up to several ragged tiles, K from one
+    # 16-wide step up to 320, every k-block that divides K.  Everything bit for bit, as above.
+    rng = np.random.default_rng(2311)
+    for case in range(60):
+        fmt = [orc.FP16, orc.BF16][int(rng.integers(2))]
+        M, N = int(rng.integers(1, 420)), int(rng.integers(1, 330))
+        steps = int(rng.integers(1, 21))
+        K = 16 * steps
+        divisors = [d for d in range(1, steps + 1) if steps % d == 0]
+        kb = 16 * divisors[int(rng.integers(len(divisors)))]
+        cfg, group = int(rng.integers(-1, 7)), int(rng.integers(1, 9))
+        n, policy, want_c = int(rng.integers(1, 50)), int(rng.integers(3)), bool(rng.integers(2))
+        what = (case, fmt, M, N, K, kb, cfg, group, n, policy, want_c)
+        Aw, Bw = wl.small_integers(M, N, K, fmt, seed=case + 100, lim=4, step=2)
+        faults = _mixed_faults(Aw, Bw, fmt, kb, n, seed=case)
+        plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=None if cfg < 0 else cfg, group=group)
+        p = orc.problem(M, N, K, kb, fmt)
+        got = gu.gpu_campaign(plan, faults, policy, want_c=want_c)
+        recs, cout = got if want_c else (got, None)
+        for t in range(len(faults)):
+            o, cf, cc = orc.trial(p, Aw, Bw, faults[t:t + 1], policy, orc.MODE_FULL, want_outputs=True)
+            nan = np.isnan(cc)
+            g = recs[t]
+            for k in ("n_flagged", "n_dev_pre", "n_dev_post", "site_word_before", "site_word_after"):
+                assert int(g[k]) == int(o[k]), (k, t, faults[t], int(g[k]), int(o[k]), what)
+            if not nan.any():
+                assert int(g["n_bitdiff"]) == int(o["n_bitdiff"]), (t, faults[t], what)
+            assert np.float32(g["max_dev_pre"]) == np.float32(o["max_dev_pre"]), (t, faults[t], what)
+            assert np.float32(g["max_dev_post"]) == np.float32(o["max_dev_post"]), (t, faults[t], what)
+            if want_c:
+                assert np.array_equal(np.isnan(cout[t]), nan), (t, faults[t], what)
+                assert np.array_equal(cout[t][~nan].view(np.uint32), cc[~nan].view(np.uint32)), (t, faults[t], what)
+        plan.destroy()
 
 
 def _check_unfaulted(plan, Aw, Bw, fmt, rows=None):
