@@ -135,6 +135,39 @@ def test_exact_regime_random_shapes_formats_blocks_and_tile_shapes():
         plan.destroy()
 
 
+def test_random_gaussian_campaigns_by_the_guard_band_rule():
+    # 150 seeded draws of (format, shape, k-block, tile configuration, trial group, batch size,
+    # policy, fault kinds, bits per fault, output-side detector, product check) on Gaussian
+    # operands, one invalid site per batch: records against the oracle's by the parity rule.
+    rng = np.random.default_rng(57820)
+    for case in range(150):
+        fmt = [orc.FP16, orc.BF16][int(rng.integers(2))]
+        M, N = int(rng.integers(1, 300)), int(rng.integers(1, 260))
+        steps = int(rng.integers(1, 25))
+        K = 16 * steps
+        divisors = [d for d in range(1, steps + 1) if steps % d == 0]
+        kb = 16 * divisors[int(rng.integers(len(divisors)))]
+        cfg, group = int(rng.integers(-1, 7)), int(rng.integers(1, 9))
+        n, policy = int(rng.integers(1, 200)), int(rng.integers(3))
+        kind_mode, nbits = int(rng.integers(5)), [1, 2, 4][int(rng.integers(3))]
+        bound, pcheck = int(rng.integers(3)), int(rng.integers(4))
+        what = (case, fmt, M, N, K, kb, cfg, group, n, policy, kind_mode, nbits, bound, pcheck)
+        Aw, Bw = wl.gaussian(M, N, K, fmt, seed=case + 11)
+        plan = gu.make_plan(Aw, Bw, kb, fmt, cfg=None if cfg < 0 else cfg, group=group, bound_mode=bound)
+        plan.set_product_check(pcheck)
+        faults = fi.fi_sample_faults(case, 0, n, plan.desc, kind_mode, nbits)
+        if n > 3:
+            faults[3]["row"] = 10 ** 7
+        p = orc.problem(M, N, K, kb, fmt, bound_mode=bound, product_check=pcheck)
+        recs = gu.gpu_campaign(plan, faults, policy)
+        ora = orc.campaign(p, Aw, Bw, gu.to_orc_faults(faults), policy, orc.MODE_AFFECTED)
+        ra, cb, _ = orc.rowcol_absmax(p, Aw, Bw)
+        s = gu.compare_records(recs, ora, faults, site_tol=2.0 ** -12 * K * float(ra.max()) * float(cb.max()))
+        assert not s["mismatches"], (s["mismatches"][:5], what)
+        assert np.array_equal(recs["product_flag"], ora["product_flag"]), what
+        plan.destroy()
+
+
 def _check_unfaulted(plan, Aw, Bw, fmt, rows=None):
     A = orc.decode_array(Aw, fmt).astype(np.float64)
     Bt = orc.decode_array(Bw, fmt).astype(np.float64)
